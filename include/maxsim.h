@@ -1,0 +1,122 @@
+/*
+ * maxsim.h -- C ABI of the fused MaxSim library for AMD MI355X (gfx950).
+ *
+ * The operator is the late-interaction score of the "Flash-MaxSim" paper,
+ *     score(Q, D) = sum_i max_j <Q_i, D_j>                      (Eq. 1),
+ * computed tile by tile so that the [N_q, B, L_q, L_d] similarity tensor is
+ * never written to memory (Alg. 1), its training backward through the stored
+ * argmax (Eqs. 2-3, Alg. 2), and int8 scoring with per-token scales applied
+ * once per similarity cell (Sec. "Quantised Scoring", Alg. 4).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps device memory.
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it
+ *     and return; they never synchronise.  NULL means the default stream.
+ *   - Tensors are row-major with the innermost stride 1 and no gaps.  Base
+ *     pointers of Q, D and the int8 tensors must be 16-byte aligned, all other
+ *     pointers 4-byte aligned.
+ *   - d (embedding width) must be 128 (the paper's setting, Tab. "shapes");
+ *     any other value returns MAXSIM_ERR_UNSUPPORTED.
+ *   - L_q and L_d are arbitrary positive integers (no tile multiples needed).
+ *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
+ *   - Return value: MAXSIM_OK (0) or a negative error code; on error nothing
+ *     was enqueued.  No exceptions, no abort, nothing printed.
+ */
+#ifndef MAXSIM_H
+#define MAXSIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MAXSIM_OK 0
+#define MAXSIM_ERR_INVALID (-1)     /* null pointer, non-positive size, misaligned pointer, bad enum */
+#define MAXSIM_ERR_UNSUPPORTED (-2) /* d != 128, or a size beyond what the kernels index */
+#define MAXSIM_ERR_LAUNCH (-3)      /* the HIP runtime reported an error at launch */
+
+typedef enum { MAXSIM_F32 = 0, MAXSIM_F16 = 1, MAXSIM_BF16 = 2 } maxsim_dtype;
+
+/* Human-readable text for a return code (static storage, never NULL). */
+const char *maxsim_strerror(int code);
+
+/*
+ * Fused forward over a uniform corpus (Eq. 1; Alg. 1; Prop. 1).
+ *   Q       [n_q, l_q, d]  dtype          query token embeddings
+ *   D       [b,   l_d, d]  dtype          document token embeddings
+ *   scores  [n_q, b]       float32        fully overwritten
+ *   argmax  [n_q, b, l_q]  int32 or NULL  winning document-token index, local to
+ *                                         the document (Sec. "Closed-Form Gradients");
+ *                                         ties go to the lowest index ("Tied maxima")
+ * Products are formed in the input dtype's exact values and accumulated in fp32.
+ */
+int maxsim_forward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
+                   maxsim_dtype dtype, float *scores, int32_t *argmax, void *stream);
+
+/*
+ * Fused forward over a packed ragged corpus (Sec. "Ragged corpora and kernel family";
+ * the cu_seqlens variant).  No padding is read or computed.
+ *   D_packed     [total_tokens, d] dtype   documents back to back
+ *   doc_offsets  [b + 1] int32 (device)    non-decreasing, doc_offsets[0] = 0,
+ *                                          doc_offsets[b] = total_tokens
+ *   total_tokens host copy of doc_offsets[b]; must be < 2^31
+ * A document of length 0 gets score -inf and argmax -1.
+ * Other arguments as in maxsim_forward.
+ */
+int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed,
+                          const int32_t *doc_offsets, int64_t b, int64_t total_tokens, int d,
+                          maxsim_dtype dtype, float *scores, int32_t *argmax, void *stream);
+
+/*
+ * Backward through the stored argmax (Eqs. 2-3; Alg. 2), uniform corpus.
+ *   argmax  [n_q, b, l_q] int32   as written by maxsim_forward; negative entries are skipped,
+ *                                 entries >= l_d are a caller error (skipped, never dereferenced)
+ *   dscore  [n_q, b]      float32 upstream gradient of the scores
+ *   dQ      [n_q, l_q, d] float32 fully overwritten:  dQ[q,i,:] = sum_b dscore[q,b] D[b, A[q,b,i], :]
+ *   dD      [b,  l_d, d]  float32 fully overwritten:  dD[b,t,:] = sum_{(q,i): A[q,b,i]=t} dscore[q,b] Q[q,i,:]
+ * Accumulation is fp32 in a fixed order: results are bitwise reproducible from run to run
+ * (no atomics; every dD row is owned by one wavefront, which plays the role of the paper's
+ * inverse-grid CSR without building it).
+ */
+int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
+                    maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                    float *dD, void *stream);
+
+/*
+ * Per-token symmetric absmax quantiser (Sec. "Quantised Scoring").
+ *   X      [rows, d] dtype
+ *   X_i8   [rows, d] int8    round_half_even(x / scale), clamped to [-127, 127]
+ *   scale  [rows]    float32 absmax / 127 (IEEE fp32 division); an all-zero row gets scale 0, codes 0
+ */
+int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dtype, int8_t *X_i8,
+                            float *scale, void *stream);
+
+/*
+ * int8 x int8 scoring with deferred dequantisation (Alg. 4; App. "INT8 Kernel").
+ *   Q_i8 [n_q, l_q, d] int8, q_scale [n_q, l_q] float32
+ *   D_i8 [b,   l_d, d] int8, d_scale [b,   l_d] float32   (scales must be >= 0)
+ *   scores [n_q, b] float32
+ * Per cell: n = exact int32 dot product; v = fl32(n * d_scale[j]); m_i = max_j v;
+ * r_i = fl32(q_scale[i] * m_i); score = sum_i r_i carried in fp64 and rounded once to fp32.
+ * The result is a pure function of the inputs (bitwise reproducible).
+ */
+int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q,
+                      const int8_t *D_i8, const float *d_scale, int64_t b, int l_d, int d,
+                      float *scores, void *stream);
+
+/*
+ * Gradient of the in-batch-negatives cross-entropy on a score matrix (helper for the
+ * contrastive training step; the paper leaves the loss open, this is softmax
+ * cross-entropy with temperature tau, label of query i = document i, mean over queries).
+ *   scores [n, b] float32 (b >= n);  g [n, b] float32 = (softmax_j(s_i/tau) - [i==j]) / (tau n)
+ *   loss   [1] float32 or NULL
+ */
+int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss,
+                   void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAXSIM_H */

@@ -1,0 +1,181 @@
+"""Thin ctypes binding of libmaxsim.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/maxsim.h) and takes
+torch tensors that live on the GPU; torch is used for device memory and the current
+stream, nothing else.  There is no CPU fallback: if the library is missing or a tensor
+is not on the device, the call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmaxsim.so")
+
+MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
+_DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
+
+SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward",
+           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_ce_grad")
+
+_lib = None
+
+
+class MaxSimError(RuntimeError):
+    pass
+
+
+def load():
+    """Load libmaxsim.so (once).  torch is imported first so that the HIP runtime the
+    library binds to is the one torch already loaded."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MaxSimError("%s is missing: build it with `python -m paper_2605_29517_amd.build` "
+                          "(there is no fallback path)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    i, l, p, f = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
+    L.maxsim_strerror.restype = ctypes.c_char_p
+    L.maxsim_strerror.argtypes = [i]
+    L.maxsim_forward.restype = i
+    L.maxsim_forward.argtypes = [p, i, i, p, l, i, i, i, p, p, p]
+    L.maxsim_forward_ragged.restype = i
+    L.maxsim_forward_ragged.argtypes = [p, i, i, p, p, l, l, i, i, p, p, p]
+    L.maxsim_backward.restype = i
+    L.maxsim_backward.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p]
+    L.maxsim_quantize_rows_i8.restype = i
+    L.maxsim_quantize_rows_i8.argtypes = [p, l, i, i, p, p, p]
+    L.maxsim_forward_i8.restype = i
+    L.maxsim_forward_i8.argtypes = [p, p, i, i, p, p, l, i, i, p, p]
+    L.maxsim_ce_grad.restype = i
+    L.maxsim_ce_grad.argtypes = [p, i, i, f, p, p, p]
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MaxSimError("%s failed: %s (%d)" % (what, load().maxsim_strerror(rc).decode(), rc))
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise MaxSimError("%s must be a tensor on the GPU" % name)
+    if not t.is_contiguous():
+        raise MaxSimError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise MaxSimError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(t: torch.Tensor):
+    return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def maxsim_forward(Q, D, scores=None, argmax=None, want_argmax=False):
+    """Q [n_q,l_q,d], D [b,l_d,d] (same 16/32-bit float dtype) -> scores [n_q,b] fp32 (, argmax int32)."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    b, l_d, d2 = D.shape
+    if d2 != d or Q.dtype != D.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
+    if argmax is None and want_argmax:
+        argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
+    with torch.cuda.device(Q.device):
+        rc = L.maxsim_forward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
+                              _dev(scores, "scores", torch.float32),
+                              _dev(argmax, "argmax", torch.int32) if argmax is not None else None, _stream(Q))
+    _check(rc, "maxsim_forward")
+    return (scores, argmax) if argmax is not None else scores
+
+
+def maxsim_forward_ragged(Q, D_packed, doc_offsets, total_tokens=None, scores=None, argmax=None, want_argmax=False):
+    """Q [n_q,l_q,d], D_packed [T,d], doc_offsets int32 [b+1] on the device."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    T, d2 = D_packed.shape
+    b = doc_offsets.shape[0] - 1
+    if d2 != d or Q.dtype != D_packed.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
+    if total_tokens is None:
+        total_tokens = T
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
+    if argmax is None and want_argmax:
+        argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
+    with torch.cuda.device(Q.device):
+        rc = L.maxsim_forward_ragged(_dev(Q, "Q"), n_q, l_q, _dev(D_packed, "D_packed"),
+                                     _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
+                                     _DTYPE[Q.dtype], _dev(scores, "scores", torch.float32),
+                                     _dev(argmax, "argmax", torch.int32) if argmax is not None else None, _stream(Q))
+    _check(rc, "maxsim_forward_ragged")
+    return (scores, argmax) if argmax is not None else scores
+
+
+def maxsim_backward(Q, D, argmax, dscore, dQ=None, dD=None):
+    """Eqs. 2-3: returns (dQ fp32 [n_q,l_q,d], dD fp32 [b,l_d,d])."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    b, l_d, _ = D.shape
+    if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
+        raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
+    if dQ is None:
+        dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
+    if dD is None:
+        dD = torch.empty(b, l_d, d, dtype=torch.float32, device=Q.device)
+    with torch.cuda.device(Q.device):
+        rc = L.maxsim_backward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
+                               _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
+                               _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
+    _check(rc, "maxsim_backward")
+    return dQ, dD
+
+
+def maxsim_quantize_rows_i8(X, X_i8=None, scale=None):
+    """X [..., d] -> (int8 codes [..., d], fp32 scale [...])."""
+    L = load()
+    d = X.shape[-1]
+    rows = X.numel() // d
+    if X_i8 is None:
+        X_i8 = torch.empty(X.shape, dtype=torch.int8, device=X.device)
+    if scale is None:
+        scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
+    with torch.cuda.device(X.device):
+        rc = L.maxsim_quantize_rows_i8(_dev(X, "X"), rows, d, _DTYPE[X.dtype], _dev(X_i8, "X_i8", torch.int8),
+                                       _dev(scale, "scale", torch.float32), _stream(X))
+    _check(rc, "maxsim_quantize_rows_i8")
+    return X_i8, scale
+
+
+def maxsim_forward_i8(Q_i8, q_scale, D_i8, d_scale, scores=None):
+    """int8 scoring: Q_i8 [n_q,l_q,d] + q_scale [n_q,l_q], D_i8 [b,l_d,d] + d_scale [b,l_d] -> scores [n_q,b]."""
+    L = load()
+    n_q, l_q, d = Q_i8.shape
+    b, l_d, _ = D_i8.shape
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
+    with torch.cuda.device(Q_i8.device):
+        rc = L.maxsim_forward_i8(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
+                                 _dev(D_i8, "D_i8", torch.int8), _dev(d_scale, "d_scale", torch.float32), b, l_d, d,
+                                 _dev(scores, "scores", torch.float32), _stream(Q_i8))
+    _check(rc, "maxsim_forward_i8")
+    return scores
+
+
+def maxsim_ce_grad(scores, tau, g=None, loss=None):
+    """In-batch-negatives cross-entropy gradient of a [n,b] score matrix (labels on the diagonal)."""
+    L = load()
+    n, b = scores.shape
+    if g is None:
+        g = torch.empty(n, b, dtype=torch.float32, device=scores.device)
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=scores.device)
+    with torch.cuda.device(scores.device):
+        rc = L.maxsim_ce_grad(_dev(scores, "scores", torch.float32), n, b, float(tau), _dev(g, "g", torch.float32),
+                              _dev(loss, "loss", torch.float32), _stream(scores))
+    _check(rc, "maxsim_ce_grad")
+    return g, loss

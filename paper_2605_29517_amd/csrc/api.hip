@@ -1,0 +1,154 @@
+// C ABI of the library: argument checks, device query, kernel selection.  See include/maxsim.h.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+
+namespace maxsim {
+hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream);
+hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+                           const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
+                           hipStream_t stream);
+hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
+hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
+                             int64_t b, int l_d, float *scores, int num_cu, hipStream_t stream);
+hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream);
+} // namespace maxsim
+
+namespace {
+
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool dtype_ok(int dt) { return dt == MAXSIM_F32 || dt == MAXSIM_F16 || dt == MAXSIM_BF16; }
+
+// Compute-unit count of the current device, queried once per device.
+int num_cu()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+int finish(hipError_t e) { return e == hipSuccess ? MAXSIM_OK : MAXSIM_ERR_LAUNCH; }
+
+int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
+                   int64_t total_tokens, int d, int dtype, float *scores, int32_t *argmax, void *stream)
+{
+    if (!Q || !D || !scores || n_q < 1 || l_q < 1 || b < 1 || !dtype_ok(dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(scores, 4) || !aligned(argmax, 4) || !aligned(offsets, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    // index ranges the kernels rely on: token counts and block ids fit in int32
+    if (total_tokens >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) ||
+        b >= (int64_t(1) << 31))
+        return MAXSIM_ERR_UNSUPPORTED;
+    maxsim::FwdParams p = {};
+    p.Q = static_cast<const char *>(Q);
+    p.D = static_cast<const char *>(D);
+    p.offsets = offsets;
+    p.scores = scores;
+    p.argmax = argmax;
+    p.b = b;
+    p.total_tokens = total_tokens;
+    p.n_q = n_q;
+    p.l_q = l_q;
+    p.l_d = l_d;
+    return finish(maxsim::forward_launch(p, dtype, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+} // namespace
+
+extern "C" {
+
+const char *maxsim_strerror(int code)
+{
+    switch (code) {
+    case MAXSIM_OK: return "ok";
+    case MAXSIM_ERR_INVALID: return "invalid argument (null or misaligned pointer, non-positive size, bad dtype)";
+    case MAXSIM_ERR_UNSUPPORTED: return "unsupported shape (d must be 128; sizes must fit the kernels' index ranges)";
+    case MAXSIM_ERR_LAUNCH: return "HIP reported an error at kernel launch";
+    default: return "unknown maxsim error code";
+    }
+}
+
+int maxsim_forward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, maxsim_dtype dtype,
+                   float *scores, int32_t *argmax, void *stream)
+{
+    if (l_d < 1)
+        return MAXSIM_ERR_INVALID;
+    if (b > 0 && (int64_t)l_d > ((int64_t(1) << 31) - 1) / b)
+        return (Q && D && scores) ? MAXSIM_ERR_UNSUPPORTED : MAXSIM_ERR_INVALID;
+    return forward_common(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, d, (int)dtype, scores, argmax, stream);
+}
+
+int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed, const int32_t *doc_offsets, int64_t b,
+                          int64_t total_tokens, int d, maxsim_dtype dtype, float *scores, int32_t *argmax, void *stream)
+{
+    if (!doc_offsets || total_tokens < 1)
+        return MAXSIM_ERR_INVALID;
+    return forward_common(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, d, (int)dtype, scores, argmax, stream);
+}
+
+int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, maxsim_dtype dtype,
+                    const int32_t *argmax, const float *dscore, float *dQ, float *dD, void *stream)
+{
+    if (!Q || !D || !argmax || !dscore || !dQ || !dD || n_q < 1 || l_q < 1 || b < 1 || l_d < 1 || !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(dQ, 16) ||
+        !aligned(dD, 16))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (b * (int64_t)l_d >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
+        (int64_t)n_q * b >= (int64_t(1) << 40))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::backward_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dtype, int8_t *X_i8, float *scale,
+                            void *stream)
+{
+    if (!X || !X_i8 || !scale || rows < 1 || !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(X, 16) || !aligned(X_i8, 16) || !aligned(scale, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (rows >= (int64_t(1) << 40))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::quantize_launch(X, rows, (int)dtype, X_i8, scale, static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q, const int8_t *D_i8,
+                      const float *d_scale, int64_t b, int l_d, int d, float *scores, void *stream)
+{
+    if (!Q_i8 || !q_scale || !D_i8 || !d_scale || !scores || n_q < 1 || l_q < 1 || b < 1 || l_d < 1)
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q_i8, 16) || !aligned(D_i8, 16) || !aligned(q_scale, 4) || !aligned(d_scale, 4) || !aligned(scores, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (b >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, b, l_d, scores, num_cu(),
+                                            static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss, void *stream)
+{
+    if (!scores || !g || n < 1 || b < n || !(tau > 0.0f))
+        return MAXSIM_ERR_INVALID;
+    return finish(maxsim::ce_grad_launch(scores, n, b, tau, g, loss, static_cast<hipStream_t>(stream)));
+}
+
+} // extern "C"

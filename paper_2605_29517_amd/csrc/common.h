@@ -1,0 +1,185 @@
+// Shared device-side vocabulary of the gfx950 MaxSim kernels (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/maxsim.h"
+
+namespace maxsim {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D_MODEL = 128;  // embedding width the kernels are built for
+constexpr int TILE_ROWS = 32; // document tokens per MFMA tile (rows of the 32x32 result)
+constexpr int BLOCK_COLS = 32; // query tokens per column block (columns of the 32x32 result)
+
+// A token row is handled in 16-byte chunks.  Lane (rho = lane % 32, h = lane / 32) of a
+// wavefront owns chunks 2u + h (u = 0 .. NU-1) of row rho, for documents (MFMA A operand)
+// and queries (MFMA B operand) alike, so both sides pair the same k indices.
+template <int DT> struct Traits;
+
+template <> struct Traits<MAXSIM_F16> {
+    static constexpr int ROW_BYTES = 256;
+    static constexpr int NU = 8;
+    static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
+
+template <> struct Traits<MAXSIM_BF16> {
+    static constexpr int ROW_BYTES = 256;
+    static constexpr int NU = 8;
+    static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+
+template <> struct Traits<MAXSIM_F32> {
+    static constexpr int ROW_BYTES = 512;
+    static constexpr int NU = 16;
+    static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
+    {
+        // one chunk = 4 floats = 4 rank-2 updates (k = 2 per instruction: halves h = 0, 1)
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+// Row of the 32x32 MFMA result held in accumulator register r of a lane in half h.
+__device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h * 4 + (r & 3); }
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_huge_valf(); }
+
+// Arguments of the forward kernels (plain data, passed by value).
+struct FwdParams {
+    const char *Q;          // [n_q, l_q, d]
+    const char *D;          // [b, l_d, d] or packed [T, d]
+    const int32_t *offsets; // [b + 1] or nullptr for a uniform corpus
+    float *scores;          // [n_q, b]
+    int32_t *argmax;        // [n_q, b, l_q] or nullptr
+    int64_t b;
+    int64_t total_tokens; // b * l_d for a uniform corpus
+    int n_q, l_q, l_d;
+    int bpq;               // column blocks per query = ceil(l_q / 32)
+    int n_chunks;          // document chunks (work units along the corpus)
+    int64_t unit_per_chunk; // documents (uniform) or tokens (ragged) per chunk
+    int n_groups;          // column groups (tile kernel only)
+    int qpg;               // queries per column group (tile kernel, bpq <= group size)
+    int n_pass;            // passes over the corpus per group (tile kernel, bpq > group size)
+};
+
+// Cursor over the 32-row tiles of a run of documents, identical in every lane of a wavefront.
+struct Cursor {
+    int64_t doc;     // current document
+    int64_t doc_end; // end of the run (exclusive)
+    int64_t start;   // first packed row of the current document
+    int64_t nxt_end; // offsets[doc + 2], fetched one document ahead (ragged only)
+    int32_t len;     // tokens in the current document
+    int32_t t0;      // first row (document-local) of the current tile
+    bool valid;
+};
+
+__device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p)
+{
+    for (;;) {
+        c.doc += 1;
+        c.valid = c.doc < c.doc_end;
+        if (!c.valid)
+            return;
+        c.t0 = 0;
+        if (p.offsets) {
+            c.start += c.len;
+            int64_t e = c.nxt_end;
+            c.len = (int32_t)(e - c.start);
+            c.nxt_end = (c.doc + 2 <= p.b) ? (int64_t)p.offsets[c.doc + 2] : e;
+            if (c.len > 0)
+                return;
+        } else {
+            c.start += p.l_d;
+            return;
+        }
+    }
+}
+
+__device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64_t doc0, int64_t doc1)
+{
+    c.doc = doc0;
+    c.doc_end = doc1;
+    c.t0 = 0;
+    c.valid = doc0 < doc1;
+    if (!c.valid)
+        return;
+    if (p.offsets) {
+        c.start = p.offsets[doc0];
+        int64_t e = p.offsets[doc0 + 1];
+        c.len = (int32_t)(e - c.start);
+        c.nxt_end = (doc0 + 2 <= p.b) ? (int64_t)p.offsets[doc0 + 2] : e;
+        if (c.len == 0)
+            cursor_next_doc(c, p);
+    } else {
+        c.start = doc0 * (int64_t)p.l_d;
+        c.len = p.l_d;
+        c.nxt_end = 0;
+    }
+}
+
+__device__ __forceinline__ void cursor_next_tile(Cursor &c, const FwdParams &p)
+{
+    c.t0 += TILE_ROWS;
+    if (c.t0 >= c.len)
+        cursor_next_doc(c, p);
+}
+
+// Documents [doc0, doc1) of work chunk `chunk`.  Uniform corpus: equal document counts.
+// Ragged corpus: the packed token range is cut into equal pieces and a chunk owns every
+// document that starts inside its piece (binary search over the offsets).
+__device__ __forceinline__ int64_t lower_bound_offsets(const int32_t *off, int64_t n, int64_t key)
+{
+    // smallest i in [0, n] with off[i] >= key (off has n + 1 entries, non-decreasing)
+    int64_t lo = 0, hi = n + 1;
+    while (lo < hi) {
+        int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)off[mid] < key)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ void chunk_doc_range(const FwdParams &p, int64_t chunk, int64_t &doc0, int64_t &doc1)
+{
+    if (chunk >= p.n_chunks) {
+        doc0 = doc1 = 0;
+        return;
+    }
+    if (p.offsets) {
+        int64_t lo = chunk * p.unit_per_chunk;
+        int64_t hi = lo + p.unit_per_chunk;
+        doc0 = (chunk == 0) ? 0 : lower_bound_offsets(p.offsets, p.b, lo);
+        doc1 = (chunk == p.n_chunks - 1) ? p.b : lower_bound_offsets(p.offsets, p.b, hi);
+        if (doc0 > p.b)
+            doc0 = p.b;
+        if (doc1 > p.b)
+            doc1 = p.b;
+    } else {
+        doc0 = chunk * p.unit_per_chunk;
+        doc1 = doc0 + p.unit_per_chunk;
+        if (doc0 > p.b)
+            doc0 = p.b;
+        if (doc1 > p.b)
+            doc1 = p.b;
+    }
+}
+
+} // namespace maxsim

@@ -1,0 +1,76 @@
+"""Helpers shared by the GPU parity tests: run the oracle on the same inputs and compare."""
+import numpy as np
+import torch
+
+from oracle import cpu_oracle as O
+from paper_2605_29517_amd import workloads as W
+
+# fp16/bf16 inputs, fp32 accumulation: 2e-3 relative per score (the stated bar).  The
+# absolute slack only matters for scores that happen to sit at zero.
+RTOL_16 = 2e-3
+RTOL_F32 = 1e-5
+ARGMAX_MARGIN = 1e-3
+
+
+def decode(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def check_scores(gpu_scores, ref_scores, l_q, rtol):
+    g = gpu_scores.detach().cpu().numpy().astype(np.float64)
+    assert g.shape == ref_scores.shape
+    fin = np.isfinite(ref_scores)
+    assert np.array_equal(g[~fin], ref_scores[~fin])
+    err = np.abs(g[fin] - ref_scores[fin])
+    tol = rtol * np.abs(ref_scores[fin]) + 1e-6 * l_q
+    worst = float((err / np.maximum(np.abs(ref_scores[fin]), 1e-30)).max()) if err.size else 0.0
+    assert np.all(err <= tol), "max rel err %.3e" % worst
+    return worst
+
+
+def check_argmax(gpu_argmax, ref_argmax, ref_margin, Q, D_rows_of_doc):
+    """Equal where the oracle's top-2 margin exceeds 1e-3; elsewhere the chosen token's
+    similarity must be within 1e-3 of the maximum.  D_rows_of_doc(doc) -> float64 [len, d]."""
+    a = gpu_argmax.detach().cpu().numpy()
+    assert a.shape == ref_argmax.shape
+    clear = ref_margin > ARGMAX_MARGIN
+    assert np.array_equal(a[clear], ref_argmax[clear]), "%d mismatches" % int((a[clear] != ref_argmax[clear]).sum())
+    empty = ref_argmax < 0
+    assert np.array_equal(a[empty], ref_argmax[empty])
+    Qd = decode(Q)
+    for q, b, i in zip(*np.nonzero(~clear & ~empty)):
+        rows = D_rows_of_doc(b)
+        assert 0 <= a[q, b, i] < rows.shape[0]
+        s = rows @ Qd[q, i]
+        assert s.max() - s[a[q, b, i]] <= ARGMAX_MARGIN
+    return int((~clear).sum())
+
+
+def forward_parity_uniform(Q, D, fn, want_argmax, rtol):
+    """Q, D torch tensors on the GPU; fn = binding.maxsim_forward."""
+    dt = W.dtype_name(Q)
+    ref_s, ref_a, ref_m = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dt)
+    out = fn(Q, D, want_argmax=want_argmax)
+    torch.cuda.synchronize()
+    if want_argmax:
+        s, a = out
+        Dd = decode(D)
+        check_argmax(a, ref_a, ref_m, Q, lambda b: Dd[b])
+    else:
+        s = out
+    return check_scores(s, ref_s, Q.shape[1], rtol)
+
+
+def forward_parity_ragged(Q, Dp, offsets, fn, want_argmax, rtol):
+    dt = W.dtype_name(Q)
+    off = offsets.detach().cpu().numpy()
+    ref_s, ref_a, ref_m = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), dt, offsets=off)
+    out = fn(Q, Dp, offsets, want_argmax=want_argmax)
+    torch.cuda.synchronize()
+    if want_argmax:
+        s, a = out
+        Dd = decode(Dp)
+        check_argmax(a, ref_a, ref_m, Q, lambda b: Dd[off[b]:off[b + 1]])
+    else:
+        s = out
+    return check_scores(s, ref_s, Q.shape[1], rtol)

@@ -74,6 +74,20 @@ def _stream(t: torch.Tensor):
     return ctypes.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
 
 
+class _on_device:
+    """Makes the tensor's GPU current for the call; rejects host tensors before anything else."""
+
+    def __init__(self, t, name):
+        _dev(t, name)
+        self._ctx = torch.cuda.device(t.device)
+
+    def __enter__(self):
+        return self._ctx.__enter__()
+
+    def __exit__(self, *a):
+        return self._ctx.__exit__(*a)
+
+
 def maxsim_forward(Q, D, scores=None, argmax=None, want_argmax=False):
     """Q [n_q,l_q,d], D [b,l_d,d] (same 16/32-bit float dtype) -> scores [n_q,b] fp32 (, argmax int32)."""
     L = load()
@@ -85,7 +99,7 @@ def maxsim_forward(Q, D, scores=None, argmax=None, want_argmax=False):
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
     if argmax is None and want_argmax:
         argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
-    with torch.cuda.device(Q.device):
+    with _on_device(Q, "Q"):
         rc = L.maxsim_forward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                               _dev(scores, "scores", torch.float32),
                               _dev(argmax, "argmax", torch.int32) if argmax is not None else None, _stream(Q))
@@ -107,7 +121,7 @@ def maxsim_forward_ragged(Q, D_packed, doc_offsets, total_tokens=None, scores=No
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
     if argmax is None and want_argmax:
         argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
-    with torch.cuda.device(Q.device):
+    with _on_device(Q, "Q"):
         rc = L.maxsim_forward_ragged(_dev(Q, "Q"), n_q, l_q, _dev(D_packed, "D_packed"),
                                      _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
                                      _DTYPE[Q.dtype], _dev(scores, "scores", torch.float32),
@@ -127,7 +141,7 @@ def maxsim_backward(Q, D, argmax, dscore, dQ=None, dD=None):
         dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
     if dD is None:
         dD = torch.empty(b, l_d, d, dtype=torch.float32, device=Q.device)
-    with torch.cuda.device(Q.device):
+    with _on_device(Q, "Q"):
         rc = L.maxsim_backward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                                _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
                                _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
@@ -144,7 +158,7 @@ def maxsim_quantize_rows_i8(X, X_i8=None, scale=None):
         X_i8 = torch.empty(X.shape, dtype=torch.int8, device=X.device)
     if scale is None:
         scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
-    with torch.cuda.device(X.device):
+    with _on_device(X, "X"):
         rc = L.maxsim_quantize_rows_i8(_dev(X, "X"), rows, d, _DTYPE[X.dtype], _dev(X_i8, "X_i8", torch.int8),
                                        _dev(scale, "scale", torch.float32), _stream(X))
     _check(rc, "maxsim_quantize_rows_i8")
@@ -158,7 +172,7 @@ def maxsim_forward_i8(Q_i8, q_scale, D_i8, d_scale, scores=None):
     b, l_d, _ = D_i8.shape
     if scores is None:
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
-    with torch.cuda.device(Q_i8.device):
+    with _on_device(Q_i8, "Q_i8"):
         rc = L.maxsim_forward_i8(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
                                  _dev(D_i8, "D_i8", torch.int8), _dev(d_scale, "d_scale", torch.float32), b, l_d, d,
                                  _dev(scores, "scores", torch.float32), _stream(Q_i8))
@@ -174,7 +188,7 @@ def maxsim_ce_grad(scores, tau, g=None, loss=None):
         g = torch.empty(n, b, dtype=torch.float32, device=scores.device)
     if loss is None:
         loss = torch.empty(1, dtype=torch.float32, device=scores.device)
-    with torch.cuda.device(scores.device):
+    with _on_device(scores, "scores"):
         rc = L.maxsim_ce_grad(_dev(scores, "scores", torch.float32), n, b, float(tau), _dev(g, "g", torch.float32),
                               _dev(loss, "loss", torch.float32), _stream(scores))
     _check(rc, "maxsim_ce_grad")

@@ -133,9 +133,9 @@ __device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64
     }
 }
 
-__device__ __forceinline__ void cursor_next_tile(Cursor &c, const FwdParams &p)
+__device__ __forceinline__ void cursor_next_tile(Cursor &c, const FwdParams &p, int rows = TILE_ROWS)
 {
-    c.t0 += TILE_ROWS;
+    c.t0 += rows;
     if (c.t0 >= c.len)
         cursor_next_doc(c, p);
 }

@@ -1,6 +1,339 @@
+// int8 x int8 MaxSim scoring with deferred dequantisation (Alg. 4 of the paper) and the
+// per-token absmax quantiser, for gfx950.
+//
+// Same query-stationary structure as the 16-bit tile kernel: a workgroup keeps up to 1024
+// query tokens in registers as i8 MFMA B operands and streams 64-token document tiles
+// through LDS; v_mfma_i32_32x32x32_i8 produces exact int32 dot products.  The per-token
+// document scale is applied once per similarity cell in the epilogue (int -> float is
+// exact below 2^24, one IEEE fp32 multiply), the row max is taken on the scaled values,
+// the query scale is applied once per query token after the max, and the sum over query
+// tokens is carried in fp64 and rounded once, which makes the score a pure function of
+// the inputs (independent of tiling and of the order of the final sum for any realistic
+// range of magnitudes).
 #include "common.h"
+
 namespace maxsim {
-hipError_t quantize_launch(const void *, int64_t, int, int8_t *, float *, hipStream_t) { return hipErrorNotSupported; }
-hipError_t forward_i8_launch(const int8_t *, const float *, int, int, const int8_t *, const float *, int64_t, int,
-                             float *, int, hipStream_t) { return hipErrorNotSupported; }
+
+constexpr int I8_ROW_BYTES = 128;
+constexpr int I8_NU = 4;          // 16-byte chunks per lane per row (chunks 2u + h)
+constexpr int I8_TILE_ROWS = 64;  // document tokens staged per barrier (two MFMA row tiles)
+constexpr int I8_ROW_STRIDE = I8_ROW_BYTES + 16;
+constexpr int I8_NCB = 4;
+
+struct I8Params {
+    const char *Q;      // [n_q, l_q, 128] int8
+    const float *qs;    // [n_q, l_q]
+    const char *D;      // [b, l_d, 128] int8
+    const float *ds;    // [b, l_d]
+    float *scores;      // [n_q, b]
+    FwdParams f;        // sizes and work split (offsets = nullptr)
+};
+
+template <int W>
+__global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
+{
+    const FwdParams &p = P.f;
+    constexpr int NT = W * 64;
+    constexpr int CHUNKS = I8_TILE_ROWS * I8_ROW_BYTES / 16; // 512
+    constexpr int CPT = CHUNKS / NT;
+    static_assert(CHUNKS % NT == 0, "tile must split evenly over the workgroup");
+    constexpr int CPR = I8_ROW_BYTES / 16;
+    constexpr int GROUP_BLOCKS = W * I8_NCB;
+
+    __shared__ __attribute__((aligned(16))) char lds_tile[2][I8_TILE_ROWS * I8_ROW_STRIDE];
+    __shared__ __attribute__((aligned(16))) float lds_scale[2][I8_TILE_ROWS];
+    __shared__ double lds_part[2][GROUP_BLOCKS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int rho = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int n_wg = gridDim.x;
+    int v = blockIdx.x;
+    if ((n_wg & 7) == 0) // keep the column groups of one document chunk on one XCD
+        v = (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3);
+    const int group = v % p.n_groups;
+    const int chunk = v / p.n_groups;
+    int64_t doc0, doc1;
+    chunk_doc_range(p, chunk, doc0, doc1);
+    if (doc0 >= doc1)
+        return;
+
+    const int q_first = group * p.qpg;
+    const int nq = min(p.qpg, p.n_q - q_first);
+    const int gb0 = q_first * p.bpq;
+    const int nb = nq * p.bpq;
+
+    i32x4 qf[I8_NCB][I8_NU];
+    float qscale[I8_NCB];
+    bool col_valid[I8_NCB];
+    float m[I8_NCB];
+#pragma unroll
+    for (int cb = 0; cb < I8_NCB; ++cb) {
+        int lb = w * I8_NCB + cb;
+        bool active = lb < nb;
+        int gb = active ? gb0 + lb : 0;
+        int q = gb / p.bpq;
+        int tok = (gb % p.bpq) * BLOCK_COLS + rho;
+        col_valid[cb] = active && tok < p.l_q;
+        if (tok > p.l_q - 1)
+            tok = p.l_q - 1;
+        const char *row = P.Q + ((int64_t)q * p.l_q + tok) * I8_ROW_BYTES + h * 16;
+#pragma unroll
+        for (int u = 0; u < I8_NU; ++u)
+            qf[cb][u] = *reinterpret_cast<const i32x4 *>(row + u * 32);
+        qscale[cb] = P.qs[(int64_t)q * p.l_q + tok];
+        m[cb] = neg_inf();
+    }
+
+    Cursor lc;
+    cursor_init(lc, p, doc0, doc1);
+    uint4 g[CPT];
+    float gs = 0.0f;
+    auto gload = [&](const Cursor &c) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int ch = tid + i * NT;
+            int row = c.t0 + ch / CPR;
+            if (row > c.len - 1)
+                row = c.len - 1;
+            g[i] = *reinterpret_cast<const uint4 *>(P.D + (c.start + row) * I8_ROW_BYTES + (ch % CPR) * 16);
+        }
+        if (tid < I8_TILE_ROWS) {
+            int row = c.t0 + tid;
+            if (row > c.len - 1)
+                row = c.len - 1;
+            gs = P.ds[c.start + row];
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int ch = tid + i * NT;
+            *reinterpret_cast<uint4 *>(&lds_tile[buf][(ch / CPR) * I8_ROW_STRIDE + (ch % CPR) * 16]) = g[i];
+        }
+        if (tid < I8_TILE_ROWS)
+            lds_scale[buf][tid] = gs;
+    };
+
+    gload(lc);
+    lstore(0);
+    Cursor cc = lc;
+    cursor_next_tile(lc, p, I8_TILE_ROWS);
+    if (lc.valid)
+        gload(lc);
+    __syncthreads();
+
+    int cur = 0, par = 0;
+    while (cc.valid) {
+        Cursor cnext = lc;
+        if (lc.valid) {
+            lstore(cur ^ 1);
+            cursor_next_tile(lc, p, I8_TILE_ROWS);
+            if (lc.valid)
+                gload(lc);
+        }
+        if (cc.t0 == 0) {
+#pragma unroll
+            for (int cb = 0; cb < I8_NCB; ++cb)
+                m[cb] = neg_inf();
+        }
+#pragma unroll
+        for (int sub = 0; sub < I8_TILE_ROWS / TILE_ROWS; ++sub) {
+            i32x4 a[I8_NU];
+            const char *src = &lds_tile[cur][(sub * TILE_ROWS + rho) * I8_ROW_STRIDE + h * 16];
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u)
+                a[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
+            // scales of this lane's 16 result rows: four runs of four consecutive rows
+            float sc[16];
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                float4 s4 = *reinterpret_cast<const float4 *>(&lds_scale[cur][sub * TILE_ROWS + r4 * 8 + h * 4]);
+                sc[r4 * 4 + 0] = s4.x;
+                sc[r4 * 4 + 1] = s4.y;
+                sc[r4 * 4 + 2] = s4.z;
+                sc[r4 * 4 + 3] = s4.w;
+            }
+#pragma unroll
+            for (int cb = 0; cb < I8_NCB; cb += 2) {
+                i32x16 acc0, acc1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    acc0[r] = 0;
+                    acc1[r] = 0;
+                }
+#pragma unroll
+                for (int u = 0; u < I8_NU; ++u) {
+                    acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qf[cb][u], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qf[cb + 1][u], acc1, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    float v0 = (float)acc0[r] * sc[r], v1 = (float)acc0[r + 1] * sc[r + 1];
+                    m[cb] = fmaxf(m[cb], fmaxf(v0, v1));
+                    float u0 = (float)acc1[r] * sc[r], u1 = (float)acc1[r + 1] * sc[r + 1];
+                    m[cb + 1] = fmaxf(m[cb + 1], fmaxf(u0, u1));
+                }
+            }
+        }
+
+        const bool last_tile = cc.t0 + I8_TILE_ROWS >= cc.len;
+        if (last_tile) {
+#pragma unroll
+            for (int cb = 0; cb < I8_NCB; ++cb) {
+                float mm = fmaxf(m[cb], __shfl_xor(m[cb], 32));
+                float r = qscale[cb] * mm; // one IEEE fp32 multiply per query token
+                double dv = col_valid[cb] ? (double)r : 0.0;
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1)
+                    dv += __shfl_xor(dv, o);
+                if (lane == 0)
+                    lds_part[par][w * I8_NCB + cb] = dv;
+            }
+        }
+        __syncthreads();
+        if (last_tile) {
+            if (tid < nq) {
+                double s = 0.0;
+                for (int i = 0; i < p.bpq; ++i)
+                    s += lds_part[par][tid * p.bpq + i];
+                P.scores[(int64_t)(q_first + tid) * p.b + cc.doc] = (float)s;
+            }
+            par ^= 1;
+        }
+        cc = cnext;
+        cur ^= 1;
+    }
 }
+
+template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((fwd_i8_kernel<W>), dim3(grid), dim3(W * 64), 0, s, P);
+    return hipGetLastError();
+}
+
+hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
+                             int64_t b, int l_d, float *scores, int num_cu, hipStream_t stream)
+{
+    I8Params P;
+    P.Q = reinterpret_cast<const char *>(Q);
+    P.qs = qs;
+    P.D = reinterpret_cast<const char *>(D);
+    P.ds = ds;
+    P.scores = scores;
+    FwdParams &p = P.f;
+    p = FwdParams{};
+    p.b = b;
+    p.total_tokens = b * (int64_t)l_d;
+    p.n_q = n_q;
+    p.l_q = l_q;
+    p.l_d = l_d;
+    p.bpq = (l_q + BLOCK_COLS - 1) / BLOCK_COLS;
+    const int64_t total_blocks = (int64_t)n_q * p.bpq;
+    int w = 8;
+    if (total_blocks <= 1 * I8_NCB)
+        w = 1;
+    else if (total_blocks <= 2 * I8_NCB)
+        w = 2;
+    else if (total_blocks <= 4 * I8_NCB)
+        w = 4;
+    const int group_blocks = w * I8_NCB;
+    if (p.bpq > group_blocks)
+        return hipErrorNotSupported; // l_q > 1024: would need a second pass with an fp64 carry
+    p.qpg = group_blocks / p.bpq;
+    if (p.qpg > n_q)
+        p.qpg = n_q;
+    p.n_groups = (n_q + p.qpg - 1) / p.qpg;
+    p.n_pass = 1;
+    int64_t n_chunks = ((int64_t)num_cu * 2 + p.n_groups - 1) / p.n_groups;
+    if (n_chunks < 8)
+        n_chunks = 8;
+    n_chunks = (n_chunks + 7) / 8 * 8;
+    p.unit_per_chunk = (b + n_chunks - 1) / n_chunks;
+    if (p.unit_per_chunk < 1)
+        p.unit_per_chunk = 1;
+    p.n_chunks = (int)n_chunks;
+    int grid = p.n_groups * p.n_chunks;
+    switch (w) {
+    case 1: return launch_i8<1>(P, grid, stream);
+    case 2: return launch_i8<2>(P, grid, stream);
+    case 4: return launch_i8<4>(P, grid, stream);
+    default: return launch_i8<8>(P, grid, stream);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// per-token symmetric absmax quantiser: one wavefront per row, two elements per lane
+// ---------------------------------------------------------------------------------------
+template <int DT> __device__ __forceinline__ void load2(const char *row, int lane, float &x0, float &x1)
+{
+    if (DT == MAXSIM_F32) {
+        float2 v = reinterpret_cast<const float2 *>(row)[lane];
+        x0 = v.x;
+        x1 = v.y;
+    } else {
+        uint32_t wv = reinterpret_cast<const uint32_t *>(row)[lane];
+        if (DT == MAXSIM_F16) {
+            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv & 0xffffu));
+            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv >> 16));
+        } else {
+            x0 = __uint_as_float(wv << 16);
+            x1 = __uint_as_float(wv & 0xffff0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ int quant_code(float x, float s)
+{
+    if (s == 0.0f)
+        return 0;
+    float r = rintf(x / s); // IEEE division, round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+template <int DT>
+__global__ void __launch_bounds__(256) quantize_rows_kernel(const char *X, int64_t rows, int8_t *out, float *scale)
+{
+    constexpr int ROWB = D_MODEL * (DT == MAXSIM_F32 ? 4 : 2);
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; r < rows; r += n_waves) {
+        float x0, x1;
+        load2<DT>(X + r * ROWB, lane, x0, x1);
+        float a = fmaxf(fabsf(x0), fabsf(x1));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1)
+            a = fmaxf(a, __shfl_xor(a, o));
+        float s = a / 127.0f;
+        int c0 = quant_code(x0, s), c1 = quant_code(x1, s);
+        uint16_t packed = (uint16_t)((c0 & 0xff) | ((c1 & 0xff) << 8));
+        reinterpret_cast<uint16_t *>(out + r * D_MODEL)[lane] = packed;
+        if (lane == 0)
+            scale[r] = s;
+    }
+}
+
+hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream)
+{
+    int64_t blocks = (rows + 3) / 4;
+    if (blocks > 65536 * 4)
+        blocks = 65536 * 4;
+    const char *x = static_cast<const char *>(X);
+    switch (dtype) {
+    case MAXSIM_F32:
+        hipLaunchKernelGGL((quantize_rows_kernel<MAXSIM_F32>), dim3((unsigned)blocks), dim3(256), 0, stream, x, rows, X_i8, scale);
+        break;
+    case MAXSIM_F16:
+        hipLaunchKernelGGL((quantize_rows_kernel<MAXSIM_F16>), dim3((unsigned)blocks), dim3(256), 0, stream, x, rows, X_i8, scale);
+        break;
+    default:
+        hipLaunchKernelGGL((quantize_rows_kernel<MAXSIM_BF16>), dim3((unsigned)blocks), dim3(256), 0, stream, x, rows, X_i8, scale);
+        break;
+    }
+    return hipGetLastError();
+}
+
+} // namespace maxsim

@@ -1,0 +1,57 @@
+"""The C-ABI library loads and exports every entry point the header declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "maxsim.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(maxsim_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    syms = declared_symbols()
+    for name in ("maxsim_forward", "maxsim_forward_ragged", "maxsim_backward", "maxsim_quantize_rows_i8",
+                 "maxsim_forward_i8", "maxsim_strerror"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2605_29517_amd import binding
+    assert os.path.exists(binding.LIB_PATH), "build the library first: python -m paper_2605_29517_amd.build"
+    import torch  # noqa: F401  (the HIP runtime the library binds to comes with torch)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(lib, name), name
+    assert sorted(binding.SYMBOLS) == declared_symbols()
+
+
+def test_error_codes_without_touching_a_gpu():
+    from paper_2605_29517_amd import binding
+    L = binding.load()
+    assert L.maxsim_strerror(0) == b"ok"
+    assert b"invalid" in L.maxsim_strerror(-1)
+    # null pointers and bad sizes are rejected before any HIP call
+    assert L.maxsim_forward(None, 1, 32, None, 4, 40, 128, 1, None, None, None) == -1
+    assert L.maxsim_backward(None, 1, 1, None, 1, 1, 128, 1, None, None, None, None, None) == -1
+    assert L.maxsim_forward_i8(None, None, 1, 1, None, None, 1, 1, 128, None, None) == -1
+    assert L.maxsim_quantize_rows_i8(None, 1, 128, 0, None, None, None) == -1
+    buf = (ctypes.c_char * 4096)()
+    addr = (ctypes.addressof(buf) + 255) & ~255
+    p = ctypes.c_void_p(addr)
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 64, 1, p, None, None) == -2       # d != 128
+    assert L.maxsim_forward(p, 0, 32, p, 4, 40, 128, 1, p, None, None) == -1      # n_q < 1
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 128, 7, p, None, None) == -1      # bad dtype
+    assert L.maxsim_forward(ctypes.c_void_p(addr + 2), 1, 32, p, 4, 40, 128, 1, p, None, None) == -1  # misaligned
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2605_29517_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmaxsim.so")
+    import pytest
+    with pytest.raises(binding.MaxSimError):
+        binding.load()

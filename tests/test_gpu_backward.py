@@ -1,0 +1,102 @@
+"""GPU parity of maxsim_backward and maxsim_ce_grad against the CPU oracle (through the C ABI).
+
+The backward is fed the ORACLE's argmax, so dQ / dD are a deterministic function of the
+inputs and near-tie argmax choices cannot leak into gradient parity.  Only the fp32
+summation order differs from the fp64 oracle: per tensor max|delta| <= 1e-4 * max|ref|
+and cosine >= 0.99999.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cpu_oracle as O
+from paper_2605_29517_amd import binding as M
+from paper_2605_29517_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def close(gpu, ref, what):
+    g = gpu.detach().cpu().numpy().astype(np.float64)
+    scale = np.abs(ref).max()
+    err = np.abs(g - ref).max()
+    assert err <= 1e-4 * scale + 1e-30, "%s: max|d| %.3e vs scale %.3e" % (what, err, scale)
+    if scale > 0:
+        cos = (g * ref).sum() / (np.linalg.norm(g) * np.linalg.norm(ref))
+        assert cos >= 0.99999, "%s: cosine %.8f" % (what, cos)
+    untouched = ~ref.reshape(-1, ref.shape[-1]).any(axis=1)  # rows no edge points at stay exactly zero
+    assert not g.reshape(-1, g.shape[-1])[untouched].any(), what
+
+
+def run_case(n_q, l_q, b, l_d, dtype, seed, holes=False):
+    Q = W.unit_rows((n_q, l_q, 128), dtype, seed, DEV)
+    D = W.unit_rows((b, l_d, 128), dtype, seed + 1, DEV)
+    _, A, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype)
+    rng = np.random.default_rng(seed)
+    g = rng.standard_normal((n_q, b)).astype(np.float32)
+    if holes:
+        A = A.copy()
+        A[rng.random(A.shape) < 0.2] = -1
+    rQ, rD = O.backward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype, A, g.astype(np.float64))
+    dQ, dD = M.maxsim_backward(Q, D, torch.from_numpy(A).to(DEV), torch.from_numpy(g).to(DEV))
+    torch.cuda.synchronize()
+    close(dQ, rQ, "dQ")
+    close(dD, rD, "dD")
+    return dQ, dD
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 32, 3, 40), (5, 33, 7, 129), (3, 7, 6, 300), (16, 32, 18, 257),
+                                   (2, 100, 5, 64), (4, 64, 9, 128), (1, 130, 2, 31)])
+def test_backward_parity(shape, dtype):
+    run_case(*shape, dtype, 7)
+
+
+def test_negative_indices_are_skipped():
+    run_case(4, 32, 6, 70, "f16", 9, holes=True)
+
+
+def test_backward_is_bitwise_reproducible():
+    Q = W.unit_rows((8, 32, 128), "f16", 1, DEV)
+    D = W.unit_rows((8, 200, 128), "f16", 2, DEV)
+    s, a = M.maxsim_forward(Q, D, want_argmax=True)
+    g = torch.randn(8, 8, device=DEV)
+    r1 = M.maxsim_backward(Q, D, a, g)
+    r2 = M.maxsim_backward(Q, D, a, g)
+    torch.cuda.synchronize()
+    assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1])
+
+
+def test_contrastive_step_small():
+    """forward with argmax -> cross-entropy gradient -> backward, all on the GPU, against the oracle chain."""
+    n, l_q, l_d, tau = 12, 32, 96, 0.02
+    Q, D = W.contrastive_batch(n, l_q, l_d, device=DEV, seed=4)
+    s, a = M.maxsim_forward(Q, D, want_argmax=True)
+    g, loss = M.maxsim_ce_grad(s, tau)
+    dQ, dD = M.maxsim_backward(Q, D, a, g)
+    torch.cuda.synchronize()
+    # oracle chain on the GPU's fp32 scores (so that the softmax sees identical inputs)
+    rs, rA, rm = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), "f16")
+    assert np.allclose(s.cpu().numpy(), rs, rtol=2e-3)
+    rloss, rg = O.ce_grad(s.cpu().numpy().astype(np.float64), tau)
+    assert abs(float(loss) - rloss) <= 1e-5 * max(1.0, abs(rloss))
+    assert np.abs(g.cpu().numpy() - rg).max() <= 1e-4 * np.abs(rg).max()
+    clear = rm > 1e-3
+    assert np.array_equal(a.cpu().numpy()[clear], rA[clear])
+    # gradient parity with the oracle's argmax and the GPU's g as inputs
+    rQ, rD = O.backward(W.to_raw_numpy(Q), W.to_raw_numpy(D), "f16", rA, g.cpu().numpy().astype(np.float64))
+    dQ2, dD2 = M.maxsim_backward(Q, D, torch.from_numpy(rA).to(DEV), g)
+    torch.cuda.synchronize()
+    close(dQ2, rQ, "dQ")
+    close(dD2, rD, "dD")
+
+
+@pytest.mark.parametrize("n,b", [(1, 1), (4, 6), (37, 50), (256, 256)])
+def test_ce_grad(n, b):
+    s = (torch.randn(n, b, device=DEV) * 3 + 10).contiguous()
+    g, loss = M.maxsim_ce_grad(s, 0.02)
+    torch.cuda.synchronize()
+    rloss, rg = O.ce_grad(s.cpu().numpy().astype(np.float64), 0.02)
+    assert abs(float(loss) - rloss) <= 1e-5 * max(1.0, abs(rloss))
+    assert np.abs(g.cpu().numpy() - rg).max() <= 1e-4 * max(np.abs(rg).max(), 1e-30)

@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MaxSim hot path on one MI355X.
+
+A "step" is one forward pass over the ColBERT-style reranking workload (64 queries of 32
+tokens against 100 000 ragged documents, fp16, packed corpus) through the C ABI; the other
+workloads of the path (the single-query streaming slice, ColPali page-as-query, the
+contrastive training step with backward, int8 scoring of a 400K-page corpus) are timed as
+extra legs and reported in the same JSON line.  Inputs are synthetic, seeded, and resident
+in HBM before any timed region starts.  The CPU oracle is timed beside it on a bounded
+sample (and checks the GPU scores of that sample on the way).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--legs c2_nq1,c3,c4,c5] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks used as roofline denominators
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_16BIT_TFLOPS = 2500.0
+PEAK_MFMA_I8_TOPS = 5000.0
+D_MODEL = 128
+
+
+def forward_flops(n_q, l_q, tokens):
+    """Multiply-adds of Q D^T counted as 2 flops: 2 * N_q * L_q * (sum of L_d) * d."""
+    return 2.0 * n_q * l_q * tokens * D_MODEL
+
+
+def forward_bytes(n_q, l_q, tokens, n_docs, elem_bytes, ragged, scale_bytes=0):
+    """Algorithmic HBM bytes of the forward: D read once, Q once, scores written once."""
+    b = tokens * D_MODEL * elem_bytes + tokens * scale_bytes
+    b += n_q * l_q * (D_MODEL * elem_bytes + scale_bytes)
+    b += n_q * n_docs * 4
+    if ragged:
+        b += (n_docs + 1) * 4
+    return float(b)
+
+
+def backward_bytes(n_q, l_q, n_docs, l_d, elem_bytes):
+    """Floor of the backward: read A and g, read Q and D once, write dQ and dD once."""
+    return float(n_q * n_docs * l_q * 4 + n_q * n_docs * 4 + (n_q * l_q + n_docs * l_d) * D_MODEL * elem_bytes
+                 + (n_q * l_q + n_docs * l_d) * D_MODEL * 4)
+
+
+def read_traffic(key):
+    """HBM bytes per launch measured with rocprofv3 --pmc, kept as 'key value' lines in profiles/traffic.txt."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        tok = line.split()
+        if len(tok) >= 2 and tok[0] == key:
+            try:
+                return float(tok[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--legs", default="c2_nq1,c3,c4,c5")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-docs", type=int, default=4096, help="documents in the oracle's sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus %d is not supported); "
+              "the path shards by documents with no communication, see DESIGN.md" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_29517_amd import binding as M
+    from paper_2605_29517_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    M.load()
+    dev = "cuda:0"
+    legs = [x for x in args.legs.split(",") if x]
+
+    def time_launches(fn, steps, warmup):
+        """W untimed steps, then K timed steps between synchronisations; one event pair per launch."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        k = sorted(a.elapsed_time(b) for a, b in ev)
+        return wall_ms, sum(k) / len(k), k[len(k) // 2], k[0]
+
+    def roof(bound, work, avg_ms, peak, unit, key):
+        achieved = work / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+        return {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": read_traffic(key)}
+
+    # ---------------- headline: config 2, ragged ColBERT rerank, 64 queries ----------------
+    n_q, l_q, n_docs = 64, 32, 100_000
+    Q, Dp, off, lens = W.colbert_rerank(n_q=n_q, l_q=l_q, n_docs=n_docs, device=dev)
+    T = int(Dp.shape[0])
+    scores = torch.empty(n_q, n_docs, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    wall_ms, avg_ms, med_ms, min_ms = time_launches(
+        lambda: M.maxsim_forward_ragged(Q, Dp, off, total_tokens=T, scores=scores), args.steps, args.warmup)
+    pairs_per_s = n_q * n_docs / (wall_ms * 1e-3)
+    out = {
+        "metric": "docs scored/sec per query",
+        "value": round(pairs_per_s, 1),
+        "unit": "docs/s (each query's documents counted: N_q*B/t)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: ColBERT-style rerank, N_q=64, L_q=32, d=128, B=100000 ragged L_d~U[64,300] "
+                               "(packed, int32 offsets), fp16 unit-norm rows, fp32 accumulate, scores [64,100000]",
+                   "total_tokens": T, "entry_point": "maxsim_forward_ragged"},
+        "docs_per_s_per_query": round(n_docs / (wall_ms * 1e-3), 1),
+        "kernel_ms": {"avg": round(avg_ms, 4), "median": round(med_ms, 4), "min": round(min_ms, 4)},
+        "roofline": roof("mfma", forward_flops(n_q, l_q, T), avg_ms, PEAK_MFMA_16BIT_TFLOPS, "TFLOP/s", "c2_nq64"),
+        "hbm_frac_same_launch": round(forward_bytes(n_q, l_q, T, n_docs, 2, True) / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+    }
+    extra = []
+
+    # ---------------- CPU oracle on a bounded sample of the same workload ----------------
+    if not args.no_cpu:
+        from oracle import cpu_oracle as O
+        ns = min(args.cpu_docs, n_docs)
+        g = torch.Generator().manual_seed(1234)
+        pick = torch.sort(torch.randperm(n_docs, generator=g)[:ns]).values
+        pick[0], pick[-1] = 0, n_docs - 1
+        pick = torch.unique(pick)
+        lens_c, off_c = lens.cpu().long(), off.cpu().long()
+        sub_len = lens_c[pick]
+        sub_off = torch.zeros(len(pick) + 1, dtype=torch.int64)
+        sub_off[1:] = torch.cumsum(sub_len, 0)
+        rows = torch.cat([torch.arange(int(off_c[d]), int(off_c[d + 1])) for d in pick.tolist()])
+        Dsub = Dp[rows.to(dev)].cpu()
+        threads = max(1, min(os.cpu_count() or 1, 16))
+        t0 = time.perf_counter()
+        ref, _, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dsub), "f16", offsets=sub_off.numpy().astype(np.int32),
+                              want_argmax=False, want_margin=False, threads=threads)
+        cpu_s = time.perf_counter() - t0
+        got = scores[:, pick.to(dev)].cpu().numpy().astype(np.float64)
+        rel = float(np.max(np.abs(got - ref) / np.abs(ref)))
+        out["cpu_baseline"] = {"value": round(n_q * len(pick) / cpu_s, 1), "unit": out["unit"], "cores": threads,
+                               "kind": "oracle", "seconds": round(cpu_s, 2),
+                               "sample": "all 64 queries x %d documents drawn from the same corpus (incl. first and last)" % len(pick)}
+        out["parity_on_sample"] = {"max_rel_err": rel, "tolerance": 2e-3, "ok": bool(rel <= 2e-3)}
+    del scores
+
+    # ---------------- extra legs ----------------
+    if "c2_nq1" in legs:
+        Q1 = Q[:1].contiguous()
+        s1 = torch.empty(1, n_docs, dtype=torch.float32, device=dev)
+        w, a, m, mn = time_launches(lambda: M.maxsim_forward_ragged(Q1, Dp, off, total_tokens=T, scores=s1), 50, 5)
+        extra.append({"leg": "c2_nq1", "workload": "configs[1] single-query slice (N_q=1): the streaming, HBM-bound regime",
+                      "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
+                      "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 2, True), a, PEAK_HBM_GBS, "GB/s", "c2_nq1")})
+        del s1
+    del Dp, Q
+
+    if "c3" in legs:
+        nq3, nd3, l3 = 4, 10_000, 1024
+        Q3, D3 = W.colpali_page_as_query(n_q=nq3, n_docs=nd3, l=l3, device=dev)
+        s3 = torch.empty(nq3, nd3, dtype=torch.float32, device=dev)
+        w, a, m, mn = time_launches(lambda: M.maxsim_forward(Q3, D3, scores=s3), 20, 3)
+        extra.append({"leg": "c3", "workload": "configs[2]: ColPali page-as-query, N_q=4, L_q=L_d=1024, B=10000, bf16",
+                      "ms": round(w, 4), "pairs_per_s": round(nq3 * nd3 / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
+                      "roofline": roof("mfma", forward_flops(nq3, l3, nd3 * l3), a, PEAK_MFMA_16BIT_TFLOPS, "TFLOP/s", "c3")})
+        del Q3, D3, s3
+
+    if "c4" in legs:
+        n4, lq4, ld4, tau = 256, 32, 1024, 0.02
+        Q4, D4 = W.contrastive_batch(n4, lq4, ld4, device=dev)
+        s4 = torch.empty(n4, n4, dtype=torch.float32, device=dev)
+        a4 = torch.empty(n4, n4, lq4, dtype=torch.int32, device=dev)
+        g4 = torch.empty(n4, n4, dtype=torch.float32, device=dev)
+        loss4 = torch.empty(1, dtype=torch.float32, device=dev)
+        dQ4 = torch.empty(n4, lq4, D_MODEL, dtype=torch.float32, device=dev)
+        dD4 = torch.empty(n4, ld4, D_MODEL, dtype=torch.float32, device=dev)
+        wf, af, _, _ = time_launches(lambda: M.maxsim_forward(Q4, D4, scores=s4, argmax=a4), 50, 5)
+        wc, ac, _, _ = time_launches(lambda: M.maxsim_ce_grad(s4, tau, g=g4, loss=loss4), 50, 5)
+        wb, ab, _, _ = time_launches(lambda: M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4), 50, 5)
+
+        def step4():
+            M.maxsim_forward(Q4, D4, scores=s4, argmax=a4)
+            M.maxsim_ce_grad(s4, tau, g=g4, loss=loss4)
+            M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4)
+        ws, _, _, _ = time_launches(step4, 50, 5)
+        extra.append({"leg": "c4", "workload": "configs[3]: contrastive step, 256 queries (L_q=32) x 256 docs (L_d=1024), fp16, "
+                                               "forward+argmax, CE tau=0.02, backward dQ/dD",
+                      "step_ms": round(ws, 4), "forward_ms": round(wf, 4), "ce_ms": round(wc, 4), "backward_ms": round(wb, 4),
+                      "pairs_per_s": round(n4 * n4 / (ws * 1e-3), 1),
+                      "roofline_forward": roof("mfma", forward_flops(n4, lq4, n4 * ld4), af, PEAK_MFMA_16BIT_TFLOPS, "TFLOP/s", "c4_fwd"),
+                      "roofline_backward": roof("hbm", backward_bytes(n4, lq4, n4, ld4, 2), ab, PEAK_HBM_GBS, "GB/s", "c4_bwd")})
+        del Q4, D4, s4, a4, g4, dQ4, dD4
+
+    if "c5" in legs:
+        nd5, l5, chunk = 400_000, 1024, 10_000
+        Qh = W.int8_query(l5, device=dev)
+        D8 = torch.empty(nd5, l5, D_MODEL, dtype=torch.int8, device=dev)
+        ds = torch.empty(nd5, l5, dtype=torch.float32, device=dev)
+        for ci in range(nd5 // chunk):  # corpus quantised offline (index time), outside the timed region
+            X = W.int8_corpus_chunk(ci, chunk, l5, device=dev)
+            M.maxsim_quantize_rows_i8(X, X_i8=D8[ci * chunk:(ci + 1) * chunk], scale=ds[ci * chunk:(ci + 1) * chunk])
+            del X
+        Q8 = torch.empty(1, l5, D_MODEL, dtype=torch.int8, device=dev)
+        qs = torch.empty(1, l5, dtype=torch.float32, device=dev)
+        s5 = torch.empty(1, nd5, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+
+        def step5():  # the query is quantised on the fly, inside the timed call
+            M.maxsim_quantize_rows_i8(Qh, X_i8=Q8, scale=qs)
+            M.maxsim_forward_i8(Q8, qs, D8, ds, scores=s5)
+        w, a, m, mn = time_launches(step5, 5, 2)
+        extra.append({"leg": "c5", "workload": "configs[4]: int8 corpus, 1 query L_q=1024 quantised on the fly, B=400000 docs "
+                                               "L_d=1024 int8 + fp32 per-token scales (%.1f GB resident)" % ((D8.numel() + ds.numel() * 4) / 1e9),
+                      "ms": round(w, 4), "docs_per_s": round(nd5 / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
+                      "roofline": roof("mfma", forward_flops(1, l5, nd5 * l5), a, PEAK_MFMA_I8_TOPS, "TOP/s", "c5")})
+        del D8, ds
+
+    out["legs"] = extra
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -11,6 +11,8 @@ SOURCES = ["api.hip", "forward.hip", "backward.hip", "int8.hip"]
 # the test machines); the host pass warns that it does not know the feature, which is harmless
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # inputs are finite by contract: without this every max is preceded by a NaN-quieting copy
+         "-fno-honor-nans",
          "-Wall", "-Wno-unused-function"]
 
 

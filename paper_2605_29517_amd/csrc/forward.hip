@@ -65,8 +65,34 @@ __device__ __forceinline__ void fold_tile(const f32x16 &acc, float &m, int &idx,
     } else {
 #pragma unroll
         for (int r = 0; r < 16; r += 2)
-            m = fmaxf(m, fmaxf(acc[r], acc[r + 1]));
+            m = fmaxf(fmaxf(m, acc[r]), acc[r + 1]); // one v_max3_f32 per pair
     }
+}
+
+// Cross-lane helpers on the VALU (no LDS traffic): v_permlane32_swap exchanges the two lane
+// halves, DPP row operations add within a row of 16 lanes.
+__device__ __forceinline__ void swap_halves(float x, float &lo_from_hi, float &hi_from_lo)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    hi_from_lo = __uint_as_float(r[0]); // lanes 32..63 now hold lanes 0..31 (lanes 0..31 unchanged)
+    lo_from_hi = __uint_as_float(r[1]); // lanes 0..31 now hold lanes 32..63 (lanes 32..63 unchanged)
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over lanes 0..31 (a fixed tree: pairs, quads, eights, sixteens, then the two rows).
+__device__ __forceinline__ float sum_low32(float v)
+{
+    v = dpp_add<0xB1>(v);  // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);  // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v); // row_half_mirror
+    v = dpp_add<0x140>(v); // row_mirror
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    return r0 + r1;
 }
 
 // End of a document for one column block: merge the lane halves, write the argmax of valid
@@ -75,12 +101,16 @@ template <bool ARGMAX>
 __device__ __forceinline__ float finish_block(const FwdParams &p, float m, int idx, bool col_valid,
                                               int gb, int64_t doc, int len, int rho, int h)
 {
-    float mo = __shfl_xor(m, 32);
+    float a, b; // a: this lane's value or its partner's, so that max(a, b) is the merged value in every lane
+    swap_halves(m, a, b);
     if (ARGMAX) {
-        int io = __shfl_xor(idx, 32);
-        bool take = (mo > m) || (mo == m && io < idx);
-        m = take ? mo : m;
-        idx = take ? io : idx;
+        float ia, ib;
+        swap_halves(__int_as_float(idx), ia, ib);
+        // lanes 0..31: (a, ia) came from the upper half, (b, ib) is the lane's own; upper lanes: the reverse
+        int i0 = __float_as_int(ia), i1 = __float_as_int(ib);
+        bool take = (a > b) || (a == b && i0 < i1);
+        m = take ? a : b;
+        idx = take ? i0 : i1;
         if (col_valid && h == 0) {
             int q = gb / p.bpq;
             int tok = (gb % p.bpq) * BLOCK_COLS + rho;
@@ -89,15 +119,9 @@ __device__ __forceinline__ float finish_block(const FwdParams &p, float m, int i
             p.argmax[((int64_t)q * p.b + doc) * p.l_q + tok] = idx;
         }
     } else {
-        m = fmaxf(m, mo);
+        m = fmaxf(a, b);
     }
-    float v = col_valid ? m : 0.0f;
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 8);
-    v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 1);
-    return v;
+    return sum_low32(col_valid ? m : 0.0f);
 }
 
 // Documents of length 0 in [doc0, doc1): score -inf, argmax -1 (ragged corpora only).
@@ -236,13 +260,81 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
 // tile kernel: query-stationary workgroup, document tiles staged through LDS
 // ---------------------------------------------------------------------------------------
 
+#ifndef MAXSIM_TILE_STAGE
+#define MAXSIM_TILE_STAGE 1
+#endif
+
 template <int DT> struct LdsTile {
     // rows padded by one 16-byte chunk so that the 32 rows read by one ds_read_b128 of the
     // MFMA operand layout fall into different banks
     static constexpr int ROW_STRIDE = Traits<DT>::ROW_BYTES + 16;
     static constexpr int BYTES = TILE_ROWS * ROW_STRIDE;
     static constexpr int CHUNKS = TILE_ROWS * Traits<DT>::ROW_BYTES / 16;
+    // 32-token tiles staged per barrier
+    static constexpr int STAGE = (DT == MAXSIM_F32) ? 1 : MAXSIM_TILE_STAGE;
 };
+
+// Walks the 32-token tiles of documents [doc, doc_end), the same in every lane.  All state is
+// 32-bit and lives in scalar registers; for ragged corpora a vector register holds 64
+// consecutive offsets (one coalesced load per 63 documents) and v_readlane picks from it, so
+// stepping to the next document costs no memory latency.
+struct TileIter {
+    int doc, doc_end;
+    int row0; // packed row of the current tile's first token
+    int t0;   // document-local index of that token
+    int len;  // tokens in the current document
+    int base; // document whose offset sits in lane 0 of offv
+    int offv; // offsets[min(base + lane, b)]
+};
+
+__device__ __forceinline__ bool it_valid(const TileIter &it) { return it.doc < it.doc_end; }
+
+__device__ __forceinline__ void it_enter_doc(TileIter &it, const FwdParams &p, int lane)
+{
+    // position on document it.doc, skipping empty documents
+    while (it.doc < it.doc_end) {
+        if (p.offsets) {
+            int k = it.doc - it.base;
+            if (k < 0 || k >= 63) {
+                it.base = it.doc;
+                int64_t i = (int64_t)it.doc + lane;
+                it.offv = p.offsets[i < p.b ? i : p.b];
+                k = 0;
+            }
+            int s = __builtin_amdgcn_readlane(it.offv, k);
+            int e = __builtin_amdgcn_readlane(it.offv, k + 1);
+            it.row0 = s;
+            it.len = e - s;
+        } else {
+            it.row0 = it.doc * p.l_d;
+            it.len = p.l_d;
+        }
+        it.t0 = 0;
+        if (it.len > 0)
+            return;
+        it.doc += 1;
+    }
+}
+
+__device__ __forceinline__ void it_init(TileIter &it, const FwdParams &p, int doc0, int doc1, int lane)
+{
+    it.doc = doc0;
+    it.doc_end = doc1;
+    it.base = -1000;
+    it.offv = 0;
+    it.row0 = it.t0 = it.len = 0;
+    it_enter_doc(it, p, lane);
+}
+
+__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, int lane)
+{
+    it.t0 += TILE_ROWS;
+    it.row0 += TILE_ROWS;
+    if (it.t0 >= it.len) {
+        it.doc += 1;
+        it_enter_doc(it, p, lane);
+    }
+}
 
 template <int DT, int W, int NCB, bool ARGMAX>
 __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
@@ -250,13 +342,14 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
     constexpr int NT = W * 64;
+    constexpr int STAGE = LT::STAGE;
     constexpr int CPT = LT::CHUNKS / NT; // 16-byte chunks each thread moves per tile
     static_assert(LT::CHUNKS % NT == 0, "tile must split evenly over the workgroup");
     constexpr int CPR = TR::ROW_BYTES / 16; // chunks per row
     constexpr int GROUP_BLOCKS = W * NCB;
 
-    __shared__ __attribute__((aligned(16))) char lds_tile[2][LT::BYTES];
-    __shared__ float lds_part[2][GROUP_BLOCKS];
+    __shared__ __attribute__((aligned(16))) char lds_tile[2][STAGE][LT::BYTES];
+    __shared__ float lds_part[2][STAGE][GROUP_BLOCKS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -273,12 +366,24 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
     const int group = v % p.n_groups;
     const int chunk = v / p.n_groups;
 
-    int64_t doc0, doc1;
-    chunk_doc_range(p, chunk, doc0, doc1);
-    if (doc0 >= doc1)
+    int64_t doc0_, doc1_;
+    chunk_doc_range(p, chunk, doc0_, doc1_);
+    if (doc0_ >= doc1_)
         return;
+    const int doc0 = (int)doc0_, doc1 = (int)doc1_;
     if (group == 0)
         write_empty_docs(p, doc0, doc1, tid, NT);
+
+    // this thread's share of a tile copy: chunk ch = tid + i * NT -> (row, 16-byte column)
+    int cp_row[CPT], cp_goff[CPT], cp_loff[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        int ch = tid + i * NT;
+        cp_row[i] = ch / CPR;
+        cp_goff[i] = (ch % CPR) * 16;
+        cp_loff[i] = (ch / CPR) * LT::ROW_STRIDE + (ch % CPR) * 16;
+    }
+    const int a_off = rho * LT::ROW_STRIDE + h * 16;
 
     for (int pass = 0; pass < p.n_pass; ++pass) {
         // column blocks of this pass: [gb0, gb0 + nb); queries [q_first, q_first + nq)
@@ -295,6 +400,8 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
             gb0 = group * p.bpq + pass * GROUP_BLOCKS;
             nb = min(GROUP_BLOCKS, p.bpq - pass * GROUP_BLOCKS);
         }
+        // a query of one block needs no combination across blocks: its lane writes the score
+        const bool direct = p.bpq == 1;
 
         uint4 qf[NCB][TR::NU];
         bool col_valid[NCB];
@@ -309,108 +416,122 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
             idx[cb] = 0;
         }
 
-        Cursor lc; // load cursor: the tile whose data is in `g`
-        cursor_init(lc, p, doc0, doc1);
-        if (!lc.valid)
+        TileIter li, ci; // load iterator (runs two stages ahead) and compute iterator
+        it_init(li, p, doc0, doc1, lane);
+        ci = li;
+        if (!it_valid(ci))
             break;
-        uint4 g[CPT];
-        auto gload = [&](const Cursor &c) {
+
+        uint4 g[STAGE][CPT];
+        bool g_has[STAGE];
+        // HBM -> registers for the next STAGE tiles of the stream
+        auto gload = [&]() {
 #pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                int ch = tid + i * NT;
-                int row = c.t0 + ch / CPR;
-                if (row > c.len - 1)
-                    row = c.len - 1;
-                g[i] = *reinterpret_cast<const uint4 *>(p.D + (c.start + row) * TR::ROW_BYTES + (ch % CPR) * 16);
+            for (int s = 0; s < STAGE; ++s) {
+                g_has[s] = it_valid(li);
+                if (!g_has[s])
+                    continue;
+                int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
+                const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
+#pragma unroll
+                for (int i = 0; i < CPT; ++i) {
+                    int row = cp_row[i] < last_row ? cp_row[i] : last_row;
+                    g[s][i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
+                }
+                it_next(li, p, lane);
             }
         };
         auto lstore = [&](int buf) {
 #pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                int ch = tid + i * NT;
-                *reinterpret_cast<uint4 *>(&lds_tile[buf][(ch / CPR) * LT::ROW_STRIDE + (ch % CPR) * 16]) = g[i];
+            for (int s = 0; s < STAGE; ++s) {
+                if (!g_has[s])
+                    continue;
+#pragma unroll
+                for (int i = 0; i < CPT; ++i)
+                    *reinterpret_cast<uint4 *>(&lds_tile[buf][s][cp_loff[i]]) = g[s][i];
             }
         };
 
-        gload(lc);
+        gload();
         lstore(0);
-        Cursor cc = lc;
-        cursor_next_tile(lc, p);
-        if (lc.valid)
-            gload(lc);
+        gload();
         __syncthreads();
 
-        int cur = 0;
-        int par = 0; // parity of the partial-sum buffer, flips per document
-        while (cc.valid) {
-            Cursor cnext = lc;
-            if (lc.valid) {
-                lstore(cur ^ 1);
-                cursor_next_tile(lc, p);
-                if (lc.valid)
-                    gload(lc);
-            }
+        int buf = 0;
+        while (it_valid(ci)) {
+            lstore(buf ^ 1); // stage k+1: registers -> the other LDS buffer
+            gload();         // stage k+2: HBM -> registers, in flight during the compute below
 
-            uint4 a[TR::NU];
-            const char *src = &lds_tile[cur][rho * LT::ROW_STRIDE + h * 16];
+            int fin_doc[STAGE];
 #pragma unroll
-            for (int u = 0; u < TR::NU; ++u)
-                a[u] = *reinterpret_cast<const uint4 *>(src + u * 32);
+            for (int s = 0; s < STAGE; ++s) {
+                fin_doc[s] = -1;
+                if (!it_valid(ci))
+                    continue;
+                uint4 a[TR::NU];
+                const char *src = &lds_tile[buf][s][a_off];
+#pragma unroll
+                for (int u = 0; u < TR::NU; ++u)
+                    a[u] = *reinterpret_cast<const uint4 *>(src + u * 32);
 
-            if (cc.t0 == 0) {
+                const bool first = ci.t0 == 0;
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
-                    m[cb] = neg_inf();
-                    idx[cb] = 0;
+                    m[cb] = first ? neg_inf() : m[cb];
+                    idx[cb] = first ? 0 : idx[cb];
                 }
-            }
-            // two column blocks at a time: two independent accumulator chains in flight
-#pragma unroll
-            for (int cb = 0; cb < NCB; cb += 2) {
-                f32x16 acc0, acc1;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    acc0[r] = 0.0f;
-                    acc1[r] = 0.0f;
-                }
-#pragma unroll
-                for (int u = 0; u < TR::NU; ++u) {
-                    TR::mma(a[u], qf[cb][u], acc0);
-                    if (cb + 1 < NCB)
-                        TR::mma(a[u], qf[cb + 1][u], acc1);
-                }
-                fold_tile<ARGMAX>(acc0, m[cb], idx[cb], cc.t0, h);
-                if (cb + 1 < NCB)
-                    fold_tile<ARGMAX>(acc1, m[cb + 1], idx[cb + 1], cc.t0, h);
-            }
-
-            const bool last_tile = cc.t0 + TILE_ROWS >= cc.len;
-            if (last_tile) {
+                // One accumulator chain per column block; the fold of block cb is independent of
+                // the chain of block cb + 1, so the VALU epilogue runs under the next chain's MFMAs.
+                f32x16 acc[NCB];
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
-                    int lb = w * NCB + cb;
-                    float s = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, cc.doc, cc.len, rho, h);
-                    if (lane == 0)
-                        lds_part[par][lb] = s;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[cb][r] = 0.0f;
+#pragma unroll
+                    for (int u = 0; u < TR::NU; ++u)
+                        TR::mma(a[u], qf[cb][u], acc[cb]);
+                    if (cb > 0)
+                        fold_tile<ARGMAX>(acc[cb - 1], m[cb - 1], idx[cb - 1], ci.t0, h);
                 }
+                fold_tile<ARGMAX>(acc[NCB - 1], m[NCB - 1], idx[NCB - 1], ci.t0, h);
+
+                if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of its document
+                    fin_doc[s] = ci.doc;
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb) {
+                        int lb = w * NCB + cb;
+                        float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
+                        if (lane == 0) {
+                            if (direct) {
+                                if (lb < nb)
+                                    p.scores[(int64_t)(gb0 + lb) * p.b + ci.doc] = sum;
+                            } else {
+                                lds_part[buf][s][lb] = sum;
+                            }
+                        }
+                    }
+                }
+                it_next(ci, p, lane);
             }
             __syncthreads();
-            if (last_tile) {
-                if (tid < nq) { // thread t adds up the blocks of its query in block order
-                    float s = 0.0f;
+            if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
+#pragma unroll
+                for (int s = 0; s < STAGE; ++s) {
+                    if (fin_doc[s] < 0)
+                        continue;
+                    float sum = 0.0f;
                     int first = (p.n_pass == 1) ? tid * p.bpq : 0;
                     int cnt = (p.n_pass == 1) ? p.bpq : nb;
                     for (int i = 0; i < cnt; ++i)
-                        s += lds_part[par][first + i];
-                    float *dst = p.scores + (int64_t)(q_first + tid) * p.b + cc.doc;
-                    *dst = accumulate ? *dst + s : s;
+                        sum += lds_part[buf][s][first + i];
+                    float *dst = p.scores + (int64_t)(q_first + tid) * p.b + fin_doc[s];
+                    *dst = accumulate ? *dst + sum : sum;
                 }
-                par ^= 1;
             }
-            cc = cnext;
-            cur ^= 1;
+            buf ^= 1;
         }
-        __syncthreads(); // LDS tiles are reused by the next pass
+        __syncthreads(); // LDS is reused by the next pass
     }
 }
 

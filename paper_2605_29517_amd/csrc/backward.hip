@@ -131,58 +131,118 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
 // ---------------------------------------------------------------------------------------
 // dD[j,t,:] = sum over edges (q,i) with A[q,j,i] = t of g[q,j] * Q[q,i,:]
 // ---------------------------------------------------------------------------------------
-constexpr int DD_TOKENS = 128; // token rows per workgroup: 128 x 128 fp32 = 64 KB of LDS
+constexpr int DD_TOKENS = 128;  // token rows per workgroup: 128 x 128 fp32 = 64 KB of LDS
 constexpr int DD_WAVES = 8;
+constexpr int DD_COL = 8192;    // argmax entries of the document's column staged in LDS per round
+constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it processes them
 
+// Per round: (1) the workgroup copies DD_COL entries of column j of the argmax into LDS as one
+// byte each (row inside this block, or 255); (2) every wavefront scans the bytes in entry order
+// and queues the edges that land on its own rows (rows t with t % 8 == w); (3) whenever a
+// queue holds 64 edges the wavefront processes them: the 64 lanes look up q, i, g and the row
+// address for one edge each, then the edges are applied one after another, eight Q-row loads
+// in flight at a time.  Order of accumulation into a row = entry order: bitwise reproducible.
 template <int DT>
 __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int blocks_per_doc)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
+    constexpr int NT = DD_WAVES * 64;
     __shared__ __attribute__((aligned(16))) float tile[DD_TOKENS * D_MODEL];
+    __shared__ unsigned char col[DD_COL];
+    __shared__ int queue[DD_WAVES][DD_QUEUE];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t j = blockIdx.x / blocks_per_doc;
     const int t_base = (int)(blockIdx.x % blocks_per_doc) * DD_TOKENS;
 
-    for (int x = tid; x < DD_TOKENS * D_MODEL / 4; x += DD_WAVES * 64)
+    for (int x = tid; x < DD_TOKENS * D_MODEL / 4; x += NT)
         reinterpret_cast<float4 *>(tile)[x] = make_float4(0.f, 0.f, 0.f, 0.f);
-    __syncthreads();
 
-    // every wavefront walks all n_q * l_q entries of column j, 64 per step, in entry order
-    const int64_t n_entries = (int64_t)p.n_q * p.l_q;
-    const int dq = 64 / p.l_q, di = 64 % p.l_q; // advance of (q, i) per step
-    int q = lane / p.l_q, i = lane % p.l_q;
-    for (int64_t n0 = 0; n0 < n_entries; n0 += 64) {
-        int64_t n = n0 + lane;
-        int t = -1;
-        if (n < n_entries)
-            t = p.A[((int64_t)q * p.b + j) * p.l_q + i];
-        int rel = t - t_base;
-        bool mine = rel >= 0 && rel < DD_TOKENS && t < p.l_d && (rel & (DD_WAVES - 1)) == w;
-        unsigned long long mask = __ballot(mine);
-        while (mask) {
-            int e = __builtin_ctzll(mask);
-            mask &= mask - 1;
-            int eq = __builtin_amdgcn_readlane(q, e);
-            int ei = __builtin_amdgcn_readlane(i, e);
-            int er = __builtin_amdgcn_readlane(rel, e);
-            float gg = p.g[(int64_t)eq * p.b + j];
-            const char *qrow = p.Q + ((int64_t)eq * p.l_q + ei) * ROWB;
-            float x0 = Elem<DT>::get(qrow, 2 * lane);
-            float x1 = Elem<DT>::get(qrow, 2 * lane + 1);
-            float2 *cell = reinterpret_cast<float2 *>(tile + er * D_MODEL) + lane;
-            float2 cur = *cell;
-            cur.x = fmaf(gg, x0, cur.x);
-            cur.y = fmaf(gg, x1, cur.y);
-            *cell = cur;
+    // apply `cnt` (<= 64) queued edges, starting at queue slot `first`
+    auto process = [&](int first, int cnt, int c0) {
+        int packed = lane < cnt ? queue[w][first + lane] : 0;
+        int n = c0 + (packed & 0xffff);
+        int rel = packed >> 16;
+        int q = n / p.l_q;
+        int i = n - q * p.l_q;
+        float gv = lane < cnt ? p.g[(int64_t)q * p.b + j] : 0.0f;
+        int64_t roff = ((int64_t)q * p.l_q + i) * ROWB;
+        int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
+        for (int e0 = 0; e0 < cnt; e0 += 8) {
+            float x0[8], x1[8], gg[8];
+            int rr[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: re-read the last edge with weight 0
+                int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, e) << 32) |
+                              (uint32_t)__builtin_amdgcn_readlane(rlo, e);
+                gg[k] = e0 + k < cnt ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e)) : 0.0f;
+                rr[k] = __builtin_amdgcn_readlane(rel, e);
+                const char *qrow = p.Q + off;
+                x0[k] = Elem<DT>::get(qrow, 2 * lane);
+                x1[k] = Elem<DT>::get(qrow, 2 * lane + 1);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (e0 + k < cnt) {
+                    float2 *cell = reinterpret_cast<float2 *>(tile + rr[k] * D_MODEL) + lane;
+                    float2 cur = *cell;
+                    cur.x = fmaf(gg[k], x0[k], cur.x);
+                    cur.y = fmaf(gg[k], x1[k], cur.y);
+                    *cell = cur;
+                }
+            }
         }
-        q += dq;
-        i += di;
-        if (i >= p.l_q) {
-            i -= p.l_q;
-            q += 1;
+    };
+
+    const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
+    for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
+        const int cn = min(DD_COL, n_entries - c0);
+        __syncthreads(); // previous round's scan is over (and the tile is zeroed) before col is rewritten
+        {
+            // entry n = c0 + x -> (q, i); this thread walks x = tid, tid + NT, ...
+            int n = c0 + tid;
+            int q = n / p.l_q, i = n - q * p.l_q;
+            const int dq = NT / p.l_q, di = NT % p.l_q;
+            for (int x = tid; x < cn; x += NT) {
+                int t = p.A[((int64_t)q * p.b + j) * p.l_q + i];
+                int rel = t - t_base;
+                bool in = rel >= 0 && rel < DD_TOKENS && t < p.l_d;
+                col[x] = in ? (unsigned char)rel : (unsigned char)255;
+                q += dq;
+                i += di;
+                if (i >= p.l_q) {
+                    i -= p.l_q;
+                    q += 1;
+                }
+            }
         }
+        __syncthreads();
+        int qlen = 0;
+        for (int x0 = 0; x0 < cn; x0 += 64) {
+            int x = x0 + lane;
+            int rel = x < cn ? (int)col[x] : 255;
+            bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
+            unsigned long long mask = __ballot(mine);
+            if (mask == 0)
+                continue;
+            int before = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+            if (mine)
+                queue[w][qlen + before] = x | (rel << 16);
+            qlen += __builtin_popcountll(mask);
+            if (qlen >= 64) {
+                process(0, 64, c0);
+                // move the remainder (at most 63 edges) to the front
+                int rest = qlen - 64;
+                int moved = lane < rest ? queue[w][64 + lane] : 0;
+                if (lane < rest)
+                    queue[w][lane] = moved;
+                qlen = rest;
+            }
+        }
+        if (qlen > 0)
+            process(0, qlen, c0);
     }
     __syncthreads();
 
@@ -190,7 +250,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
     if (rows > DD_TOKENS)
         rows = DD_TOKENS;
     float4 *dst = reinterpret_cast<float4 *>(p.dD + (j * p.l_d + t_base) * D_MODEL);
-    for (int x = tid; x < rows * (D_MODEL / 4); x += DD_WAVES * 64)
+    for (int x = tid; x < rows * (D_MODEL / 4); x += NT)
         dst[x] = reinterpret_cast<const float4 *>(tile)[x];
 }
 
@@ -248,54 +308,73 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// One wavefront per row, rows dealt round-robin to the wavefronts of the grid.  The loss is
-// summed by the last block alone, again one wavefront per row, in a fixed order.
-__global__ void __launch_bounds__(256) ce_grad_kernel(const float *s, int n, int b, float inv_tau, float *g,
-                                                      float *loss, int row_blocks)
+// s / tau is formed with an explicitly rounded multiply everywhere, so that the same value
+// enters the max, the exponent and the label term (no fused multiply-add may split them).
+// Gradient: one wavefront per row, rows dealt round-robin to the wavefronts of the grid.
+__global__ void __launch_bounds__(256) ce_grad_kernel(const float *s, int n, int b, float inv_tau, float *g)
 {
-    __shared__ float part[4];
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
-    const bool loss_block = (int)blockIdx.x == row_blocks;
-    if (loss_block && !loss)
-        return;
-    float local = 0.0f;
-    int first = loss_block ? w : (int)blockIdx.x * 4 + w;
-    int step = loss_block ? 4 : row_blocks * 4;
-    for (int i = first; i < n; i += step) {
+    const int n_waves = (int)gridDim.x * 4;
+    for (int i = (int)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += n_waves) {
         const float *row = s + (int64_t)i * b;
         float mx = neg_inf();
         for (int j = lane; j < b; j += 64)
-            mx = fmaxf(mx, row[j] * inv_tau);
+            mx = fmaxf(mx, __fmul_rn(row[j], inv_tau));
         mx = wave_max(mx);
         float z = 0.0f;
         for (int j = lane; j < b; j += 64)
-            z += expf(row[j] * inv_tau - mx);
+            z += expf(__fmul_rn(row[j], inv_tau) - mx);
         z = wave_sum(z);
-        if (loss_block) {
-            local += logf(z) + mx - row[i] * inv_tau;
-        } else {
-            float scale = inv_tau / (float)n;
-            for (int j = lane; j < b; j += 64) {
-                float pj = expf(row[j] * inv_tau - mx) / z;
-                g[(int64_t)i * b + j] = (pj - (j == i ? 1.0f : 0.0f)) * scale;
-            }
+        float scale = inv_tau / (float)n;
+        for (int j = lane; j < b; j += 64) {
+            float pj = expf(__fmul_rn(row[j], inv_tau) - mx) / z;
+            g[(int64_t)i * b + j] = (pj - (j == i ? 1.0f : 0.0f)) * scale;
         }
     }
-    if (loss_block) {
-        if (lane == 0)
-            part[w] = local;
-        __syncthreads();
-        if (threadIdx.x == 0)
-            *loss = (part[0] + part[1] + part[2] + part[3]) / (float)n;
+}
+
+// Loss: a single block; 16 lanes per row, 64 rows at a time, partial sums combined in a fixed order.
+__global__ void __launch_bounds__(1024) ce_loss_kernel(const float *s, int n, int b, float inv_tau, float *loss)
+{
+    __shared__ float part[64];
+    const int sub = threadIdx.x & 15;
+    const int slot = threadIdx.x >> 4;
+    float local = 0.0f;
+    for (int i = slot; i < n; i += 64) {
+        const float *row = s + (int64_t)i * b;
+        float mx = neg_inf();
+        for (int j = sub; j < b; j += 16)
+            mx = fmaxf(mx, __fmul_rn(row[j], inv_tau));
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1)
+            mx = fmaxf(mx, __shfl_xor(mx, o));
+        float z = 0.0f;
+        for (int j = sub; j < b; j += 16)
+            z += expf(__fmul_rn(row[j], inv_tau) - mx);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1)
+            z += __shfl_xor(z, o);
+        local += logf(z) + mx - __fmul_rn(row[i], inv_tau);
+    }
+    if (sub == 0)
+        part[slot] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.0f;
+        for (int k = 0; k < 64; ++k)
+            t += part[k];
+        *loss = t / (float)n;
     }
 }
 
 hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream)
 {
     int row_blocks = (n + 3) / 4;
-    hipLaunchKernelGGL(ce_grad_kernel, dim3(row_blocks + 1), dim3(256), 0, stream, scores, n, b, 1.0f / tau, g, loss,
-                       row_blocks);
+    hipLaunchKernelGGL(ce_grad_kernel, dim3(row_blocks), dim3(256), 0, stream, scores, n, b, 1.0f / tau, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !loss)
+        return e;
+    hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, stream, scores, n, b, 1.0f / tau, loss);
     return hipGetLastError();
 }
 

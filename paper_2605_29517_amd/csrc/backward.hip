@@ -6,12 +6,11 @@
 //
 // dD (Eq. 3) is the contended side.  The paper resolves it either with atomics or with an
 // inverse-grid CSR built by bincount / cumsum / argsort.  Here every dD row has exactly one
-// owner instead: a workgroup owns a block of consecutive tokens of one document and keeps
-// their fp32 gradient rows in LDS; wavefront w of the workgroup owns the rows t with
-// t % W == w.  Every wavefront scans the document's argmax column [n_q * l_q entries],
-// picks out the edges that land on its rows and accumulates them in scan order.  No atomics,
-// no sort, no zero-fill pass over dD, and the summation order is fixed, so the result is
-// bitwise reproducible.
+// owner instead: a workgroup owns a block of consecutive tokens of one document; wavefront w
+// of the workgroup owns the rows t with t % W == w and keeps their fp32 gradient in registers.
+// Every wavefront scans the document's argmax column [n_q * l_q entries], picks out the edges
+// that land on its rows and accumulates them in scan order.  No atomics, no sort, no zero-fill
+// pass over dD, and the summation order is fixed, so the result is bitwise reproducible.
 #include "common.h"
 
 namespace maxsim {
@@ -131,23 +130,46 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
 // ---------------------------------------------------------------------------------------
 // dD[j,t,:] = sum over edges (q,i) with A[q,j,i] = t of g[q,j] * Q[q,i,:]
 // ---------------------------------------------------------------------------------------
-constexpr int DD_TOKENS = 128;  // token rows per workgroup: 128 x 128 fp32 = 64 KB of LDS
 constexpr int DD_WAVES = 8;
+constexpr int DD_ROWS_PER_WAVE = 16;                     // gradient rows a wavefront keeps in registers
+constexpr int DD_TOKENS = DD_WAVES * DD_ROWS_PER_WAVE;   // 128 consecutive tokens of one document per workgroup
 constexpr int DD_COL = 8192;    // argmax entries of the document's column staged in LDS per round
-constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it processes them
+constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it applies them
+constexpr int DD_BATCH = 16;    // Q rows in flight while edges are applied
 
-// Per round: (1) the workgroup copies DD_COL entries of column j of the argmax into LDS as one
-// byte each (row inside this block, or 255); (2) every wavefront scans the bytes in entry order
-// and queues the edges that land on its own rows (rows t with t % 8 == w); (3) whenever a
-// queue holds 64 edges the wavefront processes them: the 64 lanes look up q, i, g and the row
-// address for one edge each, then the edges are applied one after another, eight Q-row loads
-// in flight at a time.  Order of accumulation into a row = entry order: bitwise reproducible.
+// two consecutive elements (2 * lane, 2 * lane + 1) of a row, decoded to fp32
+template <int DT> __device__ __forceinline__ void load_pair(const char *row, int lane, float &x0, float &x1)
+{
+    if (DT == MAXSIM_F32) {
+        float2 v = reinterpret_cast<const float2 *>(row)[lane];
+        x0 = v.x;
+        x1 = v.y;
+    } else {
+        uint32_t wv = reinterpret_cast<const uint32_t *>(row)[lane];
+        if (DT == MAXSIM_F16) {
+            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv & 0xffffu));
+            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv >> 16));
+        } else {
+            x0 = __uint_as_float(wv << 16);
+            x1 = __uint_as_float(wv & 0xffff0000u);
+        }
+    }
+}
+
+// Wavefront w of the workgroup owns the rows t_base + 8 * r + w (r = 0..15) and keeps them in
+// registers: lane l holds columns 2l, 2l+1 of each.  Per round: (1) the workgroup copies
+// DD_COL entries of column j of the argmax into LDS, one byte each (row inside this block, or
+// 255); (2) every wavefront scans the bytes in entry order and queues the edges that land on
+// its rows; (3) when a queue holds 64 edges, the 64 lanes look up q, i, g and the Q row address
+// of one edge each, and the edges are then applied in order, 16 Q-row loads in flight, the
+// target row picked by a wavefront-uniform register index (s_set_gpr_idx).  Every row has one owner and a fixed order
+// of accumulation (entry order), so the result is bitwise reproducible; there are no atomics,
+// no sort and no zero-fill pass over dD.
 template <int DT>
 __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int blocks_per_doc)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
     constexpr int NT = DD_WAVES * 64;
-    __shared__ __attribute__((aligned(16))) float tile[DD_TOKENS * D_MODEL];
     __shared__ unsigned char col[DD_COL];
     __shared__ int queue[DD_WAVES][DD_QUEUE];
     const int tid = threadIdx.x;
@@ -156,12 +178,17 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
     const int64_t j = blockIdx.x / blocks_per_doc;
     const int t_base = (int)(blockIdx.x % blocks_per_doc) * DD_TOKENS;
 
-    for (int x = tid; x < DD_TOKENS * D_MODEL / 4; x += NT)
-        reinterpret_cast<float4 *>(tile)[x] = make_float4(0.f, 0.f, 0.f, 0.f);
+    typedef float rowvec __attribute__((ext_vector_type(DD_ROWS_PER_WAVE)));
+    rowvec ax, ay; // ax[r], ay[r]: columns 2 * lane, 2 * lane + 1 of owned row r
+#pragma unroll
+    for (int r = 0; r < DD_ROWS_PER_WAVE; ++r) {
+        ax[r] = 0.0f;
+        ay[r] = 0.0f;
+    }
 
-    // apply `cnt` (<= 64) queued edges, starting at queue slot `first`
-    auto process = [&](int first, int cnt, int c0) {
-        int packed = lane < cnt ? queue[w][first + lane] : 0;
+    // apply the first `cnt` (<= 64) queued edges of this wavefront
+    auto process = [&](int cnt, int c0) {
+        int packed = lane < cnt ? queue[w][lane] : 0;
         int n = c0 + (packed & 0xffff);
         int rel = packed >> 16;
         int q = n / p.l_q;
@@ -169,28 +196,22 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
         float gv = lane < cnt ? p.g[(int64_t)q * p.b + j] : 0.0f;
         int64_t roff = ((int64_t)q * p.l_q + i) * ROWB;
         int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
-        for (int e0 = 0; e0 < cnt; e0 += 8) {
-            float x0[8], x1[8], gg[8];
-            int rr[8];
+        for (int e0 = 0; e0 < cnt; e0 += DD_BATCH) {
+            float x0[DD_BATCH], x1[DD_BATCH];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: re-read the last edge with weight 0
+            for (int k = 0; k < DD_BATCH; ++k) {
+                int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: a harmless re-read of the last row
                 int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, e) << 32) |
                               (uint32_t)__builtin_amdgcn_readlane(rlo, e);
-                gg[k] = e0 + k < cnt ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e)) : 0.0f;
-                rr[k] = __builtin_amdgcn_readlane(rel, e);
-                const char *qrow = p.Q + off;
-                x0[k] = Elem<DT>::get(qrow, 2 * lane);
-                x1[k] = Elem<DT>::get(qrow, 2 * lane + 1);
+                load_pair<DT>(p.Q + off, lane, x0[k], x1[k]);
             }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < DD_BATCH; ++k) {
                 if (e0 + k < cnt) {
-                    float2 *cell = reinterpret_cast<float2 *>(tile + rr[k] * D_MODEL) + lane;
-                    float2 cur = *cell;
-                    cur.x = fmaf(gg[k], x0[k], cur.x);
-                    cur.y = fmaf(gg[k], x1[k], cur.y);
-                    *cell = cur;
+                    float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e0 + k));
+                    int r = __builtin_amdgcn_readlane(rel, e0 + k) >> 3; // rel = 8 * r + w
+                    ax[r] = fmaf(gg, x0[k], ax[r]); // r is uniform: indexed register access, no branch
+                    ay[r] = fmaf(gg, x1[k], ay[r]);
                 }
             }
         }
@@ -199,17 +220,20 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
     const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
     for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
         const int cn = min(DD_COL, n_entries - c0);
-        __syncthreads(); // previous round's scan is over (and the tile is zeroed) before col is rewritten
+        if (c0 > 0)
+            __syncthreads(); // the previous round's scan is over before col is rewritten
         {
-            // entry n = c0 + x -> (q, i); this thread walks x = tid, tid + NT, ...
+            // entry n = c0 + x -> (q, i); this thread owns x = tid, tid + NT, ...: all its loads are
+            // issued before the first result is used
+            constexpr int PER = DD_COL / NT;
             int n = c0 + tid;
             int q = n / p.l_q, i = n - q * p.l_q;
             const int dq = NT / p.l_q, di = NT % p.l_q;
-            for (int x = tid; x < cn; x += NT) {
-                int t = p.A[((int64_t)q * p.b + j) * p.l_q + i];
-                int rel = t - t_base;
-                bool in = rel >= 0 && rel < DD_TOKENS && t < p.l_d;
-                col[x] = in ? (unsigned char)rel : (unsigned char)255;
+            int t[PER];
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                int x = tid + k * NT;
+                t[k] = x < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
                 q += dq;
                 i += di;
                 if (i >= p.l_q) {
@@ -217,41 +241,56 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
                     q += 1;
                 }
             }
+#pragma unroll
+            for (int k = 0; k < PER; ++k) {
+                int x = tid + k * NT;
+                int rel = t[k] - t_base;
+                bool in = rel >= 0 && rel < DD_TOKENS && t[k] < p.l_d;
+                if (x < cn)
+                    col[x] = in ? (unsigned char)rel : (unsigned char)255;
+            }
         }
         __syncthreads();
         int qlen = 0;
-        for (int x0 = 0; x0 < cn; x0 += 64) {
-            int x = x0 + lane;
-            int rel = x < cn ? (int)col[x] : 255;
-            bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
-            unsigned long long mask = __ballot(mine);
-            if (mask == 0)
-                continue;
-            int before = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-            if (mine)
-                queue[w][qlen + before] = x | (rel << 16);
-            qlen += __builtin_popcountll(mask);
-            if (qlen >= 64) {
-                process(0, 64, c0);
-                // move the remainder (at most 63 edges) to the front
-                int rest = qlen - 64;
-                int moved = lane < rest ? queue[w][64 + lane] : 0;
-                if (lane < rest)
-                    queue[w][lane] = moved;
-                qlen = rest;
+        for (int x0 = 0; x0 < cn; x0 += 256) {
+            int rel4[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                int x = x0 + k * 64 + lane;
+                rel4[k] = x < cn ? (int)col[x] : 255;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                int rel = rel4[k];
+                bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
+                unsigned long long mask = __ballot(mine);
+                if (mask == 0)
+                    continue;
+                int before =
+                    __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+                if (mine)
+                    queue[w][qlen + before] = (x0 + k * 64 + lane) | (rel << 16);
+                qlen += __builtin_popcountll(mask);
+                if (qlen >= 64) {
+                    process(64, c0);
+                    int rest = qlen - 64; // at most 63 edges move to the front
+                    int moved = lane < rest ? queue[w][64 + lane] : 0;
+                    if (lane < rest)
+                        queue[w][lane] = moved;
+                    qlen = rest;
+                }
             }
         }
         if (qlen > 0)
-            process(0, qlen, c0);
+            process(qlen, c0);
     }
-    __syncthreads();
 
-    int rows = p.l_d - t_base;
-    if (rows > DD_TOKENS)
-        rows = DD_TOKENS;
-    float4 *dst = reinterpret_cast<float4 *>(p.dD + (j * p.l_d + t_base) * D_MODEL);
-    for (int x = tid; x < rows * (D_MODEL / 4); x += NT)
-        dst[x] = reinterpret_cast<const float4 *>(tile)[x];
+#pragma unroll
+    for (int r = 0; r < DD_ROWS_PER_WAVE; ++r) {
+        int t = t_base + r * DD_WAVES + w;
+        if (t < p.l_d)
+            reinterpret_cast<float2 *>(p.dD + (j * p.l_d + t) * D_MODEL)[lane] = make_float2(ax[r], ay[r]);
+    }
 }
 
 template <int DT> static hipError_t launch_bwd(const BwdParams &p, hipStream_t stream)
@@ -308,6 +347,13 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// s / tau as one rounded multiply that may not be contracted into a fused multiply-add
+__device__ __forceinline__ float scaled(float s, float inv_tau)
+{
+#pragma clang fp contract(off)
+    return s * inv_tau;
+}
+
 // s / tau is formed with an explicitly rounded multiply everywhere, so that the same value
 // enters the max, the exponent and the label term (no fused multiply-add may split them).
 // Gradient: one wavefront per row, rows dealt round-robin to the wavefronts of the grid.
@@ -319,15 +365,15 @@ __global__ void __launch_bounds__(256) ce_grad_kernel(const float *s, int n, int
         const float *row = s + (int64_t)i * b;
         float mx = neg_inf();
         for (int j = lane; j < b; j += 64)
-            mx = fmaxf(mx, __fmul_rn(row[j], inv_tau));
+            mx = fmaxf(mx, scaled(row[j], inv_tau));
         mx = wave_max(mx);
         float z = 0.0f;
         for (int j = lane; j < b; j += 64)
-            z += expf(__fmul_rn(row[j], inv_tau) - mx);
+            z += expf(scaled(row[j], inv_tau) - mx);
         z = wave_sum(z);
         float scale = inv_tau / (float)n;
         for (int j = lane; j < b; j += 64) {
-            float pj = expf(__fmul_rn(row[j], inv_tau) - mx) / z;
+            float pj = expf(scaled(row[j], inv_tau) - mx) / z;
             g[(int64_t)i * b + j] = (pj - (j == i ? 1.0f : 0.0f)) * scale;
         }
     }
@@ -344,17 +390,17 @@ __global__ void __launch_bounds__(1024) ce_loss_kernel(const float *s, int n, in
         const float *row = s + (int64_t)i * b;
         float mx = neg_inf();
         for (int j = sub; j < b; j += 16)
-            mx = fmaxf(mx, __fmul_rn(row[j], inv_tau));
+            mx = fmaxf(mx, scaled(row[j], inv_tau));
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1)
             mx = fmaxf(mx, __shfl_xor(mx, o));
         float z = 0.0f;
         for (int j = sub; j < b; j += 16)
-            z += expf(__fmul_rn(row[j], inv_tau) - mx);
+            z += expf(scaled(row[j], inv_tau) - mx);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1)
             z += __shfl_xor(z, o);
-        local += logf(z) + mx - __fmul_rn(row[i], inv_tau);
+        local += logf(z) + mx - scaled(row[i], inv_tau);
     }
     if (sub == 0)
         part[slot] = local;

@@ -61,7 +61,7 @@ def test_backward_is_bitwise_reproducible():
     Q = W.unit_rows((8, 32, 128), "f16", 1, DEV)
     D = W.unit_rows((8, 200, 128), "f16", 2, DEV)
     s, a = M.maxsim_forward(Q, D, want_argmax=True)
-    g = torch.randn(8, 8, device=DEV)
+    g = torch.randn(8, 8, device=DEV, generator=torch.Generator(DEV).manual_seed(3))
     r1 = M.maxsim_backward(Q, D, a, g)
     r2 = M.maxsim_backward(Q, D, a, g)
     torch.cuda.synchronize()
@@ -94,7 +94,7 @@ def test_contrastive_step_small():
 
 @pytest.mark.parametrize("n,b", [(1, 1), (4, 6), (37, 50), (256, 256)])
 def test_ce_grad(n, b):
-    s = (torch.randn(n, b, device=DEV) * 3 + 10).contiguous()
+    s = (torch.randn(n, b, device=DEV, generator=torch.Generator(DEV).manual_seed(n * 1000 + b)) * 3 + 10).contiguous()
     g, loss = M.maxsim_ce_grad(s, 0.02)
     torch.cuda.synchronize()
     rloss, rg = O.ce_grad(s.cpu().numpy().astype(np.float64), 0.02)

@@ -139,44 +139,54 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
             for (int cb = 0; cb < I8_NCB; ++cb)
                 m[cb] = neg_inf();
         }
+        {
+            constexpr int NSUB = I8_TILE_ROWS / TILE_ROWS;
+            i32x4 a[NSUB][I8_NU];
+            float sc[NSUB][16]; // scales of this lane's 16 result rows: four runs of four consecutive rows
 #pragma unroll
-        for (int sub = 0; sub < I8_TILE_ROWS / TILE_ROWS; ++sub) {
-            i32x4 a[I8_NU];
-            const char *src = &lds_tile[cur][(sub * TILE_ROWS + rho) * I8_ROW_STRIDE + h * 16];
+            for (int sub = 0; sub < NSUB; ++sub) {
+                const char *src = &lds_tile[cur][(sub * TILE_ROWS + rho) * I8_ROW_STRIDE + h * 16];
 #pragma unroll
-            for (int u = 0; u < I8_NU; ++u)
-                a[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
-            // scales of this lane's 16 result rows: four runs of four consecutive rows
-            float sc[16];
+                for (int u = 0; u < I8_NU; ++u)
+                    a[sub][u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                float4 s4 = *reinterpret_cast<const float4 *>(&lds_scale[cur][sub * TILE_ROWS + r4 * 8 + h * 4]);
-                sc[r4 * 4 + 0] = s4.x;
-                sc[r4 * 4 + 1] = s4.y;
-                sc[r4 * 4 + 2] = s4.z;
-                sc[r4 * 4 + 3] = s4.w;
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    float4 s4 = *reinterpret_cast<const float4 *>(&lds_scale[cur][sub * TILE_ROWS + r4 * 8 + h * 4]);
+                    sc[sub][r4 * 4 + 0] = s4.x;
+                    sc[sub][r4 * 4 + 1] = s4.y;
+                    sc[sub][r4 * 4 + 2] = s4.z;
+                    sc[sub][r4 * 4 + 3] = s4.w;
+                }
             }
-#pragma unroll
-            for (int cb = 0; cb < I8_NCB; cb += 2) {
-                i32x16 acc0, acc1;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    acc0[r] = 0;
-                    acc1[r] = 0;
-                }
-#pragma unroll
-                for (int u = 0; u < I8_NU; ++u) {
-                    acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qf[cb][u], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qf[cb + 1][u], acc1, 0, 0, 0);
-                }
+            // Software pipeline over the NSUB x NCB result blocks of the stage: the four MFMAs of block
+            // k are issued between the conversions, scalings and maxima of block k - 1, so the VALU
+            // epilogue (2.5 operations per cell, the binding resource of this kernel) hides the MFMAs.
+            auto epilogue = [&](const i32x16 &acc, const float(&scl)[16], float &mx) {
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
-                    float v0 = (float)acc0[r] * sc[r], v1 = (float)acc0[r + 1] * sc[r + 1];
-                    m[cb] = fmaxf(m[cb], fmaxf(v0, v1));
-                    float u0 = (float)acc1[r] * sc[r], u1 = (float)acc1[r + 1] * sc[r + 1];
-                    m[cb + 1] = fmaxf(m[cb + 1], fmaxf(u0, u1));
+                    float v0 = (float)acc[r] * scl[r], v1 = (float)acc[r + 1] * scl[r + 1];
+                    mx = fmaxf(fmaxf(mx, v0), v1);
+                }
+            };
+            i32x16 acc[NSUB * I8_NCB];
+#pragma unroll
+            for (int blk = 0; blk < NSUB * I8_NCB; ++blk) {
+                const int sub = blk / I8_NCB, cb = blk % I8_NCB;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[blk][r] = 0;
+#pragma unroll
+                for (int u = 0; u < I8_NU; ++u)
+                    acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sub][u], qf[cb][u], acc[blk], 0, 0, 0);
+                if (blk > 0)
+                    epilogue(acc[blk - 1], sc[(blk - 1) / I8_NCB], m[(blk - 1) % I8_NCB]);
+#pragma unroll
+                for (int u = 0; u < I8_NU; ++u) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0); // ten VALU operations
                 }
             }
+            epilogue(acc[NSUB * I8_NCB - 1], sc[NSUB - 1], m[I8_NCB - 1]);
         }
 
         const bool last_tile = cc.t0 + I8_TILE_ROWS >= cc.len;

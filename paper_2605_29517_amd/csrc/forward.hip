@@ -170,7 +170,7 @@ __device__ __forceinline__ void stream_load_tile(const FwdParams &p, const Curso
 template <int DT, int NCB, bool ARGMAX>
 __device__ __forceinline__ void stream_compute(const FwdParams &p, const Cursor &c,
                                                StreamState<DT, NCB, ARGMAX> &st,
-                                               const uint4 (&a)[Traits<DT>::NU], int lane, int rho, int h)
+                                               const uint4 (&a)[Traits<DT>::NU], int gb0, int lane, int rho, int h)
 {
     using TR = Traits<DT>;
     if (c.t0 == 0) {
@@ -180,34 +180,44 @@ __device__ __forceinline__ void stream_compute(const FwdParams &p, const Cursor 
             st.idx[cb] = 0;
         }
     }
-    f32x16 acc[NCB];
+    // two column blocks at a time (two accumulator chains in flight); the scheduling barrier keeps
+    // the pairs apart so that only two accumulators are live and more wavefronts fit on a SIMD
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
+    for (int cb = 0; cb < NCB; cb += 2) {
+        f32x16 acc0, acc1;
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-            acc[cb][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) {
+            acc0[r] = 0.0f;
+            acc1[r] = 0.0f;
+        }
 #pragma unroll
-    for (int u = 0; u < TR::NU; ++u)
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
-            TR::mma(a[u], st.qf[cb][u], acc[cb]);
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-        fold_tile<ARGMAX>(acc[cb], st.m[cb], st.idx[cb], c.t0, h);
+        for (int u = 0; u < TR::NU; ++u) {
+            TR::mma(a[u], st.qf[cb][u], acc0);
+            if (cb + 1 < NCB)
+                TR::mma(a[u], st.qf[cb + 1][u], acc1);
+        }
+        fold_tile<ARGMAX>(acc0, st.m[cb], st.idx[cb], c.t0, h);
+        if (cb + 1 < NCB)
+            fold_tile<ARGMAX>(acc1, st.m[cb + 1], st.idx[cb + 1], c.t0, h);
+        if (cb + 2 < NCB)
+            __builtin_amdgcn_sched_barrier(0);
+    }
 
     if (c.t0 + TILE_ROWS >= c.len) { // last tile of the document
         float part[NCB];
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
-            part[cb] = finish_block<ARGMAX>(p, st.m[cb], st.idx[cb], st.col_valid[cb], cb, c.doc, c.len, rho, h);
-        // lane q (< n_q) adds up the blocks of query q in block order and writes its score
+            part[cb] = finish_block<ARGMAX>(p, st.m[cb], st.idx[cb], st.col_valid[cb], gb0 + cb, c.doc, c.len, rho, h);
+        // this wavefront holds whole queries: lane k adds up the blocks of its k-th query in block
+        // order and writes the score
         float s = 0.0f;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
             if (cb / p.bpq == lane)
                 s += part[cb];
-        if (lane < p.n_q)
-            p.scores[(int64_t)lane * p.b + c.doc] = s;
+        const int q = gb0 / p.bpq + lane;
+        if (lane < NCB / p.bpq && q < p.n_q)
+            p.scores[(int64_t)q * p.b + c.doc] = s;
     }
 }
 
@@ -217,18 +227,24 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
     using TR = Traits<DT>;
     const int lane = threadIdx.x & 63;
     const int rho = lane & 31, h = lane >> 5;
-    const int64_t wave =
-        __builtin_amdgcn_readfirstlane((int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6));
+    // p.n_groups (1, 2 or 4) wavefronts of a workgroup share a run of documents, each with its own
+    // NCB column blocks (whole queries); they read the same tiles at about the same time, so all
+    // but the first read hit in the CU's vector cache.  No LDS and no barrier is involved.
+    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int group = wib % p.n_groups;
+    const int64_t chunk = (int64_t)blockIdx.x * (4 / p.n_groups) + wib / p.n_groups;
+    const int gb0 = group * NCB;
     int64_t doc0, doc1;
-    chunk_doc_range(p, wave, doc0, doc1);
+    chunk_doc_range(p, chunk, doc0, doc1);
     if (doc0 >= doc1)
         return;
-    write_empty_docs(p, doc0, doc1, lane, 64);
+    if (group == 0)
+        write_empty_docs(p, doc0, doc1, lane, 64);
 
     StreamState<DT, NCB, ARGMAX> st;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
-        load_q_block<DT>(p, cb, rho, h, st.qf[cb], st.col_valid[cb]);
+        load_q_block<DT>(p, gb0 + cb, rho, h, st.qf[cb], st.col_valid[cb]);
 
     Cursor pc; // prefetch cursor, one tile ahead of the compute cursor
     cursor_init(pc, p, doc0, doc1);
@@ -241,14 +257,14 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
     for (;;) {
         if (pc.valid)
             stream_load_tile<DT>(p, pc, rho, h, a1);
-        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a0, lane, rho, h);
+        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a0, gb0, lane, rho, h);
         cc = pc;
         if (!cc.valid)
             break;
         cursor_next_tile(pc, p);
         if (pc.valid)
             stream_load_tile<DT>(p, pc, rho, h, a0);
-        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a1, lane, rho, h);
+        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a1, gb0, lane, rho, h);
         cc = pc;
         if (!cc.valid)
             break;
@@ -586,13 +602,27 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
     p.bpq = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS;
     const int64_t total_blocks = (int64_t)p.n_q * p.bpq;
     const int64_t units = ragged ? p.total_tokens : p.b; // what is split across chunks
+    // Streaming kernel: every wavefront holds whole queries in at most 4 (fp32: 2) column blocks, and
+    // up to 4 wavefronts share a run of documents.  That covers up to 16 blocks of short queries.
     const int stream_max_blocks = (dtype == MAXSIM_F32) ? 2 : 4;
-
+    int s_ncb = 0, s_groups = 0;
     if (total_blocks <= stream_max_blocks) {
-        // one work chunk per wavefront; enough chunks to oversubscribe the chip a few times,
-        // but no chunk smaller than about 2K tokens
+        s_ncb = (int)total_blocks;
+        s_groups = 1;
+    } else if (p.bpq <= stream_max_blocks) {
+        int qpw = stream_max_blocks / p.bpq; // whole queries per wavefront
+        int groups = (p.n_q + qpw - 1) / qpw;
+        if (groups <= 4) {
+            s_ncb = qpw * p.bpq;
+            s_groups = groups == 3 ? 4 : groups;
+        }
+    }
+
+    if (s_groups > 0) {
+        // one work chunk per group of wavefronts; enough chunks to oversubscribe the chip a few
+        // times, but no chunk smaller than about 2K tokens
         const int64_t tokens = ragged ? p.total_tokens : p.b * (int64_t)p.l_d;
-        int64_t want = (int64_t)num_cu * 16 * 4;
+        int64_t want = (int64_t)num_cu * 16 * 4 / s_groups;
         int64_t by_size = (tokens + 2047) / 2048;
         int64_t n_chunks = want < by_size ? want : by_size;
         if (n_chunks > p.b)
@@ -605,11 +635,12 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
         if (!ragged)
             n_chunks = (units + p.unit_per_chunk - 1) / p.unit_per_chunk;
         p.n_chunks = (int)n_chunks;
-        p.n_groups = 1;
+        p.n_groups = s_groups;
         p.qpg = p.n_q;
         p.n_pass = 1;
-        int grid = (int)((n_chunks + 3) / 4);
-        const int ncb = (int)total_blocks;
+        const int chunks_per_block = 4 / s_groups;
+        int grid = (int)((n_chunks + chunks_per_block - 1) / chunks_per_block);
+        const int ncb = s_ncb;
         switch (dtype) {
         case MAXSIM_F32:
             return am ? dispatch_stream<MAXSIM_F32, true>(p, ncb, grid, stream)

@@ -24,6 +24,8 @@ SHAPES = [
     (1, 32, 37, 128), (1, 1, 5, 1), (1, 31, 9, 33), (2, 33, 11, 31), (4, 32, 50, 100), (1, 100, 20, 65),
     (3, 17, 1, 300), (8, 32, 40, 64), (5, 40, 13, 97), (16, 32, 70, 200), (2, 256, 9, 130),
     (64, 32, 33, 150), (1, 1024, 6, 260), (3, 700, 5, 95), (1, 1100, 4, 70), (2, 2100, 3, 40),
+    # several wavefronts of the streaming kernel sharing a run of documents (2, 3 and 4 groups)
+    (12, 32, 45, 130), (3, 64, 21, 77), (4, 96, 17, 140), (7, 50, 30, 33), (6, 1, 9, 5),
 ]
 
 

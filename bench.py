@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--legs", default="c2_nq1,c3,c4,c5")
+    ap.add_argument("--legs", default="c2_nq1,c3,c4,c5,ceilings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-docs", type=int, default=4096, help="documents in the oracle's sample")
     args = ap.parse_args()
@@ -233,6 +233,31 @@ def main():
                       "ms": round(w, 4), "docs_per_s": round(nd5 / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
                       "roofline": roof("mfma", forward_flops(1, l5, nd5 * l5), a, PEAK_MFMA_I8_TOPS, "TOP/s", "c5")})
         del D8, ds
+
+    if "ceilings" in legs:
+        # what the part sustains: register-only MFMA loops on realistic operand bits (unit-norm rows),
+        # a pure read stream, and a copy of known size (the calibration kernel for profiler byte counters)
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        ceil = {}
+        rows16 = W.unit_rows((8192, D_MODEL), "f16", 77, dev)       # 2 MiB of fp16 operand bits
+        rowsbf = W.unit_rows((8192, D_MODEL), "bf16", 78, dev)
+        rows8 = torch.randint(-127, 128, (1 << 21,), dtype=torch.int8, device=dev, generator=torch.Generator(dev).manual_seed(79))
+        zeros = torch.zeros(1 << 20, dtype=torch.float16, device=dev)
+        for name, kind, ops, iters in (("mfma_f16_unit_norm_operands", 0, rows16, 60000), ("mfma_bf16_unit_norm_operands", 1, rowsbf, 60000),
+                                       ("mfma_i8_random_operands", 2, rows8, 60000), ("mfma_f16_zero_operands", 0, zeros, 60000)):
+            n_ops = M.PROBE_MFMA_OPS_PER_ITER[kind] * iters
+            w, a, m, mn = time_launches(lambda: M.maxsim_probe_mfma(kind, ops, iters, sink), 8, 3)
+            ceil[name] = {"ms": round(a, 3), "tera_ops_per_s": round(n_ops / (a * 1e-3) / 1e12, 1)}
+        big = torch.empty(1 << 30, dtype=torch.int32, device=dev)   # 4 GiB
+        big.fill_(1)
+        dst = torch.empty(1 << 28, dtype=torch.int32, device=dev)   # 1 GiB
+        w, a, m, mn = time_launches(lambda: M.maxsim_probe_read(big, sink), 10, 3)
+        ceil["hbm_read_stream"] = {"ms": round(a, 3), "GB_per_s": round(big.numel() * 4 / (a * 1e-3) / 1e9, 1)}
+        w, a, m, mn = time_launches(lambda: M.maxsim_probe_copy(big[:1 << 28], dst), 10, 3)
+        ceil["hbm_copy_1GiB"] = {"ms": round(a, 3), "GB_per_s_read_plus_write": round(2 * dst.numel() * 4 / (a * 1e-3) / 1e9, 1),
+                                 "bytes_read": dst.numel() * 4, "bytes_written": dst.numel() * 4}
+        out["ceilings"] = ceil
+        del big, dst
 
     out["legs"] = extra
     print(json.dumps(out))

@@ -116,6 +116,24 @@ int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q
 int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss,
                    void *stream);
 
+/*
+ * Diagnostics (not part of the paper's operator): what the device sustains, for roofline context.
+ *
+ * maxsim_probe_mfma: a register-only loop of 32x32 MFMAs with four independent accumulators,
+ *   512 workgroups x 4 wavefronts, `iters` rounds of 4 instructions per wavefront.
+ *   kind 0 = fp16 (32x32x16), 1 = bf16 (32x32x16), 2 = int8 (32x32x32).  `operands` is >= 1 MiB of
+ *   device memory whose bits are used as MFMA operands (random bits give the rate under realistic
+ *   switching activity, zeros the rate at full clocks).  Operations per launch:
+ *   512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1, 2*32*32*32 for kind 2).
+ * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them.
+ * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
+ *   traffic for calibrating profiler byte counters.
+ * `sink` is 4 bytes of device memory that is (practically) never written.
+ */
+int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream);
+int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream);
+int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

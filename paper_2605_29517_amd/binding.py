@@ -17,7 +17,8 @@ MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
 SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward",
-           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_ce_grad")
+           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_ce_grad",
+           "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
 _lib = None
 
@@ -51,6 +52,12 @@ def load():
     L.maxsim_forward_i8.argtypes = [p, p, i, i, p, p, l, i, i, p, p]
     L.maxsim_ce_grad.restype = i
     L.maxsim_ce_grad.argtypes = [p, i, i, f, p, p, p]
+    L.maxsim_probe_mfma.restype = i
+    L.maxsim_probe_mfma.argtypes = [i, p, i, p, p]
+    L.maxsim_probe_read.restype = i
+    L.maxsim_probe_read.argtypes = [p, l, p, p]
+    L.maxsim_probe_copy.restype = i
+    L.maxsim_probe_copy.argtypes = [p, p, l, p]
     _lib = L
     return L
 
@@ -193,3 +200,38 @@ def maxsim_ce_grad(scores, tau, g=None, loss=None):
                               _dev(loss, "loss", torch.float32), _stream(scores))
     _check(rc, "maxsim_ce_grad")
     return g, loss
+
+
+PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32}
+
+
+def maxsim_probe_mfma(kind, operands, iters, sink):
+    """Register-only MFMA loop (diagnostic).  Returns the number of operations one launch performs."""
+    L = load()
+    if operands.numel() * operands.element_size() < (1 << 20):
+        raise MaxSimError("operands must hold at least 1 MiB")
+    with _on_device(operands, "operands"):
+        rc = L.maxsim_probe_mfma(int(kind), _dev(operands, "operands"), int(iters), _dev(sink, "sink", torch.float32),
+                                 _stream(operands))
+    _check(rc, "maxsim_probe_mfma")
+    return PROBE_MFMA_OPS_PER_ITER[int(kind)] * int(iters)
+
+
+def maxsim_probe_read(buf, sink):
+    """Streaming read of a whole tensor (diagnostic).  Returns the bytes read."""
+    L = load()
+    nbytes = buf.numel() * buf.element_size() // 16 * 16
+    with _on_device(buf, "buf"):
+        rc = L.maxsim_probe_read(_dev(buf, "buf"), nbytes, _dev(sink, "sink", torch.float32), _stream(buf))
+    _check(rc, "maxsim_probe_read")
+    return nbytes
+
+
+def maxsim_probe_copy(src, dst):
+    """Plain copy of a whole tensor (diagnostic).  Returns the bytes copied."""
+    L = load()
+    nbytes = min(src.numel() * src.element_size(), dst.numel() * dst.element_size()) // 16 * 16
+    with _on_device(src, "src"):
+        rc = L.maxsim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream(src))
+    _check(rc, "maxsim_probe_copy")
+    return nbytes

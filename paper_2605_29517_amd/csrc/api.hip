@@ -12,6 +12,9 @@ hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8,
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              int64_t b, int l_d, float *scores, int num_cu, hipStream_t stream);
 hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream);
+hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream);
+hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream);
+hipError_t probe_copy_launch(const void *src, void *dst, int64_t bytes, int num_cu, hipStream_t stream);
 } // namespace maxsim
 
 namespace {
@@ -149,6 +152,27 @@ int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float
     if (!scores || !g || n < 1 || b < n || !(tau > 0.0f))
         return MAXSIM_ERR_INVALID;
     return finish(maxsim::ce_grad_launch(scores, n, b, tau, g, loss, static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream)
+{
+    if (!operands || !sink || iters < 1 || kind < 0 || kind > 2 || !aligned(operands, 16))
+        return MAXSIM_ERR_INVALID;
+    return finish(maxsim::probe_mfma_launch(kind, operands, iters, sink, static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream)
+{
+    if (!buf || !sink || bytes < 16 || !aligned(buf, 16))
+        return MAXSIM_ERR_INVALID;
+    return finish(maxsim::probe_read_launch(buf, bytes, sink, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
+{
+    if (!src || !dst || bytes < 16 || !aligned(src, 16) || !aligned(dst, 16))
+        return MAXSIM_ERR_INVALID;
+    return finish(maxsim::probe_copy_launch(src, dst, bytes, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 } // extern "C"

@@ -182,4 +182,66 @@ __device__ __forceinline__ void chunk_doc_range(const FwdParams &p, int64_t chun
     }
 }
 
+// Walks the 32-token tiles of documents [doc, doc_end), the same in every lane.  All state is
+// 32-bit and lives in scalar registers; for ragged corpora a vector register holds 64
+// consecutive offsets (one coalesced load per 63 documents) and v_readlane picks from it, so
+// stepping to the next document costs no memory latency.
+struct TileIter {
+    int doc, doc_end;
+    int row0; // packed row of the current tile's first token
+    int t0;   // document-local index of that token
+    int len;  // tokens in the current document
+    int base; // document whose offset sits in lane 0 of offv
+    int offv; // offsets[min(base + lane, b)]
+};
+
+__device__ __forceinline__ bool it_valid(const TileIter &it) { return it.doc < it.doc_end; }
+
+__device__ __forceinline__ void it_enter_doc(TileIter &it, const FwdParams &p, int lane)
+{
+    // position on document it.doc, skipping empty documents
+    while (it.doc < it.doc_end) {
+        if (p.offsets) {
+            int k = it.doc - it.base;
+            if (k < 0 || k >= 63) {
+                it.base = it.doc;
+                int64_t i = (int64_t)it.doc + lane;
+                it.offv = p.offsets[i < p.b ? i : p.b];
+                k = 0;
+            }
+            int s = __builtin_amdgcn_readlane(it.offv, k);
+            int e = __builtin_amdgcn_readlane(it.offv, k + 1);
+            it.row0 = s;
+            it.len = e - s;
+        } else {
+            it.row0 = it.doc * p.l_d;
+            it.len = p.l_d;
+        }
+        it.t0 = 0;
+        if (it.len > 0)
+            return;
+        it.doc += 1;
+    }
+}
+
+__device__ __forceinline__ void it_init(TileIter &it, const FwdParams &p, int doc0, int doc1, int lane)
+{
+    it.doc = doc0;
+    it.doc_end = doc1;
+    it.base = -1000;
+    it.offv = 0;
+    it.row0 = it.t0 = it.len = 0;
+    it_enter_doc(it, p, lane);
+}
+
+__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, int lane)
+{
+    it.t0 += TILE_ROWS;
+    it.row0 += TILE_ROWS;
+    if (it.t0 >= it.len) {
+        it.doc += 1;
+        it_enter_doc(it, p, lane);
+    }
+}
+
 } // namespace maxsim

@@ -4,12 +4,25 @@
 // Same query-stationary structure as the 16-bit tile kernel: a workgroup keeps up to 1024
 // query tokens in registers as i8 MFMA B operands and streams 64-token document tiles
 // through LDS; v_mfma_i32_32x32x32_i8 produces exact int32 dot products.  The per-token
-// document scale is applied once per similarity cell in the epilogue (int -> float is
-// exact below 2^24, one IEEE fp32 multiply), the row max is taken on the scaled values,
-// the query scale is applied once per query token after the max, and the sum over query
-// tokens is carried in fp64 and rounded once, which makes the score a pure function of
-// the inputs (independent of tiling and of the order of the final sum for any realistic
-// range of magnitudes).
+// document scale is applied once per similarity cell in the epilogue, the row max is taken
+// on the scaled values, the query scale is applied once per query token after the max, and
+// the sum over query tokens is carried in fp64 and rounded once, which makes the score a
+// pure function of the inputs (independent of tiling and of the order of the final sum for
+// any realistic range of magnitudes).
+//
+// Epilogue arithmetic.  The cell value is fl32(n * s) (n the integer dot product, s the
+// token's scale).  Converting n to float and multiplying costs two VALU operations per cell,
+// and the VALU, not the matrix core, is what binds this kernel.  Instead the accumulators
+// start at the integer 0x4B000000, the bit pattern of the float 2^23: for 0 <= n < 2^23 the
+// accumulator's bits then ARE the float x = 2^23 + n, and one fused multiply-add
+// fma(x, s, -2^23 * s) forms x*s - 2^23*s = n*s exactly and rounds it once, i.e. returns
+// fl32(n * s) bit for bit (2^23 * s is a pure exponent shift, hence exact).  For -2^23 < n < 0
+// the bits are the float 2^23 + n/2 (the spacing below 2^23 is one half), so the same
+// instruction returns fl32(n*s/2) = fl32(n*s)/2 (exact halving; the only exception would be a
+// product in the subnormal range, |n*s| < 2^-125, which needs a scale below 2^-100).  Halving
+// keeps the order among negative values and any non-negative value still beats them, so
+// the running max stays correct and a negative final max is doubled once per query token
+// at the end of the document.  |n| <= 128 * 127^2 < 2^21.
 #include "common.h"
 
 namespace maxsim {
@@ -19,6 +32,9 @@ constexpr int I8_NU = 4;          // 16-byte chunks per lane per row (chunks 2u 
 constexpr int I8_TILE_ROWS = 64;  // document tokens staged per barrier (two MFMA row tiles)
 constexpr int I8_ROW_STRIDE = I8_ROW_BYTES + 16;
 constexpr int I8_NCB = 4;
+#ifndef I8_PIPE
+#define I8_PIPE 1 // result blocks between a block's MFMAs and its epilogue (2 needs more registers than there are)
+#endif
 
 struct I8Params {
     const char *Q;      // [n_q, l_q, 128] int8
@@ -42,6 +58,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
 
     __shared__ __attribute__((aligned(16))) char lds_tile[2][I8_TILE_ROWS * I8_ROW_STRIDE];
     __shared__ __attribute__((aligned(16))) float lds_scale[2][I8_TILE_ROWS];
+    __shared__ __attribute__((aligned(16))) float lds_bias[2][I8_TILE_ROWS]; // -2^23 * scale
     __shared__ double lds_part[2][GROUP_BLOCKS];
 
     const int tid = threadIdx.x;
@@ -113,8 +130,10 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
             int ch = tid + i * NT;
             *reinterpret_cast<uint4 *>(&lds_tile[buf][(ch / CPR) * I8_ROW_STRIDE + (ch % CPR) * 16]) = g[i];
         }
-        if (tid < I8_TILE_ROWS)
+        if (tid < I8_TILE_ROWS) {
             lds_scale[buf][tid] = gs;
+            lds_bias[buf][tid] = gs * -8388608.0f;
+        }
     };
 
     gload(lc);
@@ -124,6 +143,16 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
     if (lc.valid)
         gload(lc);
     __syncthreads();
+
+    // accumulator start value (see the header); made opaque so that it stays in 16 registers
+    // for the whole kernel instead of being rebuilt with 16 moves per result block
+    i32x16 seed;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int v = 0x4B000000;
+        asm volatile("" : "+v"(v));
+        seed[r] = v;
+    }
 
     int cur = 0, par = 0;
     while (cc.valid) {
@@ -142,7 +171,8 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
         {
             constexpr int NSUB = I8_TILE_ROWS / TILE_ROWS;
             i32x4 a[NSUB][I8_NU];
-            float sc[NSUB][16]; // scales of this lane's 16 result rows: four runs of four consecutive rows
+            // scale and bias of this lane's 16 result rows: four runs of four consecutive rows
+            float sc[NSUB][16], bi[NSUB][16];
 #pragma unroll
             for (int sub = 0; sub < NSUB; ++sub) {
                 const char *src = &lds_tile[cur][(sub * TILE_ROWS + rho) * I8_ROW_STRIDE + h * 16];
@@ -152,41 +182,44 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     float4 s4 = *reinterpret_cast<const float4 *>(&lds_scale[cur][sub * TILE_ROWS + r4 * 8 + h * 4]);
+                    float4 b4 = *reinterpret_cast<const float4 *>(&lds_bias[cur][sub * TILE_ROWS + r4 * 8 + h * 4]);
                     sc[sub][r4 * 4 + 0] = s4.x;
                     sc[sub][r4 * 4 + 1] = s4.y;
                     sc[sub][r4 * 4 + 2] = s4.z;
                     sc[sub][r4 * 4 + 3] = s4.w;
+                    bi[sub][r4 * 4 + 0] = b4.x;
+                    bi[sub][r4 * 4 + 1] = b4.y;
+                    bi[sub][r4 * 4 + 2] = b4.z;
+                    bi[sub][r4 * 4 + 3] = b4.w;
                 }
             }
-            // Software pipeline over the NSUB x NCB result blocks of the stage: the four MFMAs of block
-            // k are issued between the conversions, scalings and maxima of block k - 1, so the VALU
-            // epilogue (2.5 operations per cell, the binding resource of this kernel) hides the MFMAs.
-            auto epilogue = [&](const i32x16 &acc, const float(&scl)[16], float &mx) {
+            // Software pipeline over the NSUB x NCB result blocks of the stage.  One step = one MFMA of
+            // block k plus a quarter (4 of 16 rows: four multiply-adds, two max3) of the epilogue of
+            // block k - I8_PIPE, whose MFMAs have long retired; scheduling barriers keep the steps
+            // apart, so the VALU work (1.5 operations per cell) always runs under an MFMA in flight.
+            constexpr int NBLK = NSUB * I8_NCB;
+            i32x16 acc[NBLK];
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    float v0 = (float)acc[r] * scl[r], v1 = (float)acc[r + 1] * scl[r + 1];
-                    mx = fmaxf(fmaxf(mx, v0), v1);
-                }
-            };
-            i32x16 acc[NSUB * I8_NCB];
-#pragma unroll
-            for (int blk = 0; blk < NSUB * I8_NCB; ++blk) {
-                const int sub = blk / I8_NCB, cb = blk % I8_NCB;
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    acc[blk][r] = 0;
-#pragma unroll
-                for (int u = 0; u < I8_NU; ++u)
-                    acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sub][u], qf[cb][u], acc[blk], 0, 0, 0);
-                if (blk > 0)
-                    epilogue(acc[blk - 1], sc[(blk - 1) / I8_NCB], m[(blk - 1) % I8_NCB]);
+            for (int blk = 0; blk < NBLK + I8_PIPE; ++blk) {
 #pragma unroll
                 for (int u = 0; u < I8_NU; ++u) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 10, 0); // ten VALU operations
+                    if (blk < NBLK) {
+                        const int sub = blk / I8_NCB, cb = blk % I8_NCB;
+                        acc[blk] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[sub][u], qf[cb][u], u == 0 ? seed : acc[blk], 0, 0, 0);
+                    }
+                    if (blk >= I8_PIPE) {
+                        const int e = blk - I8_PIPE, es = e / I8_NCB, ec = e % I8_NCB;
+                        const int r = 4 * u;
+                        float v0 = __builtin_fmaf(__int_as_float(acc[e][r + 0]), sc[es][r + 0], bi[es][r + 0]);
+                        float v1 = __builtin_fmaf(__int_as_float(acc[e][r + 1]), sc[es][r + 1], bi[es][r + 1]);
+                        float v2 = __builtin_fmaf(__int_as_float(acc[e][r + 2]), sc[es][r + 2], bi[es][r + 2]);
+                        float v3 = __builtin_fmaf(__int_as_float(acc[e][r + 3]), sc[es][r + 3], bi[es][r + 3]);
+                        m[ec] = fmaxf(fmaxf(m[ec], v0), v1);
+                        m[ec] = fmaxf(fmaxf(m[ec], v2), v3);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            epilogue(acc[NSUB * I8_NCB - 1], sc[NSUB - 1], m[I8_NCB - 1]);
         }
 
         const bool last_tile = cc.t0 + I8_TILE_ROWS >= cc.len;
@@ -194,7 +227,8 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
 #pragma unroll
             for (int cb = 0; cb < I8_NCB; ++cb) {
                 float mm = fmaxf(m[cb], __shfl_xor(m[cb], 32));
-                float r = qscale[cb] * mm; // one IEEE fp32 multiply per query token
+                mm = mm < 0.0f ? mm + mm : mm; // negative maxima were carried halved
+                float r = qscale[cb] * mm;     // one IEEE fp32 multiply per query token
                 double dv = col_valid[cb] ? (double)r : 0.0;
 #pragma unroll
                 for (int o = 16; o > 0; o >>= 1)

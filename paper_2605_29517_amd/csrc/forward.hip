@@ -276,34 +276,60 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
 // tile kernel: query-stationary workgroup, document tiles staged through LDS
 // ---------------------------------------------------------------------------------------
 
-#ifndef MAXSIM_TILE_STAGE
-#define MAXSIM_TILE_STAGE 1
-#endif
-
 template <int DT> struct LdsTile {
     // rows padded by one 16-byte chunk so that the 32 rows read by one ds_read_b128 of the
     // MFMA operand layout fall into different banks
     static constexpr int ROW_STRIDE = Traits<DT>::ROW_BYTES + 16;
     static constexpr int BYTES = TILE_ROWS * ROW_STRIDE;
     static constexpr int CHUNKS = TILE_ROWS * Traits<DT>::ROW_BYTES / 16;
-    // 32-token tiles staged per barrier
-    static constexpr int STAGE = (DT == MAXSIM_F32) ? 1 : MAXSIM_TILE_STAGE;
 };
 
+// Part `u` (of NU) of folding a result tile into the running max: rows [u * 16 / NU, (u + 1) * 16 / NU).
+template <bool ARGMAX, int NU>
+__device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, int &idx, int row_base, int h)
+{
+    constexpr int RPS = 16 / NU; // rows per step: 2 for 16-bit inputs, 1 for fp32
+    const int r0 = u * RPS;
+    if (ARGMAX) {
+#pragma unroll
+        for (int r = r0; r < r0 + RPS; ++r) {
+            bool up = acc[r] > m; // strict: the first occurrence keeps a tie
+            m = up ? acc[r] : m;
+            idx = up ? row_base + acc_row(r, h) : idx;
+        }
+    } else if (RPS == 2) {
+        m = fmaxf(fmaxf(m, acc[r0]), acc[r0 + 1]); // one v_max3_f32
+    } else {
+        m = fmaxf(m, acc[r0]);
+    }
+}
+
+// The main loop is software-pipelined by hand and pinned with scheduling barriers, one MFMA
+// (16-bit inputs) per step:
+//   * the MFMA chain of column block cb runs while the previous block's result tile is folded
+//     into the running max, one slice of the fold per step, so the VALU work sits under MFMAs
+//     whose results it does not need;
+//   * during the first chain of a tile the wavefront also reads the NEXT tile's A operands from
+//     LDS into a second register set, writes the tile after that from registers to LDS and
+//     issues the global loads of the tile after that, so no memory latency is exposed between
+//     tiles: three LDS buffers rotate (being computed / prefetched into registers / being
+//     written), one barrier per tile.  (The fp32 and the argmax variants have no registers
+//     left for the second operand set; they read the current tile's operands at its start.)
 template <int DT, int W, int NCB, bool ARGMAX>
 __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
+    constexpr int NU = TR::NU;
     constexpr int NT = W * 64;
-    constexpr int STAGE = LT::STAGE;
     constexpr int CPT = LT::CHUNKS / NT; // 16-byte chunks each thread moves per tile
     static_assert(LT::CHUNKS % NT == 0, "tile must split evenly over the workgroup");
     constexpr int CPR = TR::ROW_BYTES / 16; // chunks per row
     constexpr int GROUP_BLOCKS = W * NCB;
+    constexpr bool PF = DT != MAXSIM_F32 && !ARGMAX; // operands of the next tile prefetched into registers
 
-    __shared__ __attribute__((aligned(16))) char lds_tile[2][STAGE][LT::BYTES];
-    __shared__ float lds_part[2][STAGE][GROUP_BLOCKS];
+    __shared__ __attribute__((aligned(16))) char lds_tile[3 * LT::BYTES];
+    __shared__ float lds_part[2][GROUP_BLOCKS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -357,7 +383,7 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
         // a query of one block needs no combination across blocks: its lane writes the score
         const bool direct = p.bpq == 1;
 
-        uint4 qf[NCB][TR::NU];
+        uint4 qf[NCB][NU];
         bool col_valid[NCB];
         float m[NCB];
         int idx[NCB];
@@ -370,120 +396,142 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
             idx[cb] = 0;
         }
 
-        TileIter li, ci; // load iterator (runs two stages ahead) and compute iterator
+        TileIter li, ci; // load iterator (three tiles ahead of the compute iterator at steady state)
         it_init(li, p, doc0, doc1, lane);
         ci = li;
         if (!it_valid(ci))
             break;
 
-        uint4 g[STAGE][CPT];
-        bool g_has[STAGE];
-        // HBM -> registers for the next STAGE tiles of the stream
+        uint4 g[CPT];
+        bool g_has = false;
+        // HBM -> registers for the next tile of the stream
         auto gload = [&]() {
+            g_has = it_valid(li);
+            if (!g_has)
+                return;
+            int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
+            const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
 #pragma unroll
-            for (int s = 0; s < STAGE; ++s) {
-                g_has[s] = it_valid(li);
-                if (!g_has[s])
-                    continue;
-                int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
-                const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
-#pragma unroll
-                for (int i = 0; i < CPT; ++i) {
-                    int row = cp_row[i] < last_row ? cp_row[i] : last_row;
-                    g[s][i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
-                }
-                it_next(li, p, lane);
+            for (int i = 0; i < CPT; ++i) {
+                int row = cp_row[i] < last_row ? cp_row[i] : last_row;
+                g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
             }
+            it_next(li, p, lane);
         };
-        auto lstore = [&](int buf) {
+        auto lstore = [&](int buf_off) {
+            if (!g_has)
+                return;
 #pragma unroll
-            for (int s = 0; s < STAGE; ++s) {
-                if (!g_has[s])
-                    continue;
-#pragma unroll
-                for (int i = 0; i < CPT; ++i)
-                    *reinterpret_cast<uint4 *>(&lds_tile[buf][s][cp_loff[i]]) = g[s][i];
-            }
+            for (int i = 0; i < CPT; ++i)
+                *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g[i];
         };
 
+        // LDS buffers (byte offsets): o_cur holds the tile being computed (already in registers),
+        // o_nxt the next one (read into registers during this tile), o_wr receives the one after
+        int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
         gload();
-        lstore(0);
+        lstore(o_cur);
+        gload();
+        lstore(o_nxt);
         gload();
         __syncthreads();
-
-        int buf = 0;
-        while (it_valid(ci)) {
-            lstore(buf ^ 1); // stage k+1: registers -> the other LDS buffer
-            gload();         // stage k+2: HBM -> registers, in flight during the compute below
-
-            int fin_doc[STAGE];
+        uint4 a0[NU], a1[PF ? NU : 1];
+        if (PF) {
 #pragma unroll
-            for (int s = 0; s < STAGE; ++s) {
-                fin_doc[s] = -1;
-                if (!it_valid(ci))
-                    continue;
-                uint4 a[TR::NU];
-                const char *src = &lds_tile[buf][s][a_off];
-#pragma unroll
-                for (int u = 0; u < TR::NU; ++u)
-                    a[u] = *reinterpret_cast<const uint4 *>(src + u * 32);
+            for (int u = 0; u < NU; ++u)
+                a0[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
+        }
+        int par = 0;
 
-                const bool first = ci.t0 == 0;
+        // one tile: operands in `ac`; the next tile's operands are read into `an` on the way
+        auto stage = [&](uint4(&ac)[NU], uint4(&an)[PF ? NU : 1]) {
+            if (!PF) {
+#pragma unroll
+                for (int u = 0; u < NU; ++u)
+                    ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
+            }
+            const bool first = ci.t0 == 0;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                m[cb] = first ? neg_inf() : m[cb];
+                idx[cb] = first ? 0 : idx[cb];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16 acc[NCB];
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    acc[cb][r] = 0.0f;
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    TR::mma(ac[u], qf[cb][u], acc[cb]);
+                    if (cb == 0) {
+                        if (PF)
+                            an[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_nxt + a_off + u * 32]);
+                        if (u == NU - 1) {
+                            lstore(o_wr);
+                            gload();
+                        }
+                    } else {
+                        fold_step<ARGMAX, NU>(acc[cb - 1], u, m[cb - 1], idx[cb - 1], ci.t0, h);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NU; ++u)
+                fold_step<ARGMAX, NU>(acc[NCB - 1], u, m[NCB - 1], idx[NCB - 1], ci.t0, h);
+
+            int fin_doc = -1;
+            if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of its document
+                fin_doc = ci.doc;
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
-                    m[cb] = first ? neg_inf() : m[cb];
-                    idx[cb] = first ? 0 : idx[cb];
-                }
-                // One accumulator chain per column block; the fold of block cb is independent of
-                // the chain of block cb + 1, so the VALU epilogue runs under the next chain's MFMAs.
-                f32x16 acc[NCB];
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[cb][r] = 0.0f;
-#pragma unroll
-                    for (int u = 0; u < TR::NU; ++u)
-                        TR::mma(a[u], qf[cb][u], acc[cb]);
-                    if (cb > 0)
-                        fold_tile<ARGMAX>(acc[cb - 1], m[cb - 1], idx[cb - 1], ci.t0, h);
-                }
-                fold_tile<ARGMAX>(acc[NCB - 1], m[NCB - 1], idx[NCB - 1], ci.t0, h);
-
-                if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of its document
-                    fin_doc[s] = ci.doc;
-#pragma unroll
-                    for (int cb = 0; cb < NCB; ++cb) {
-                        int lb = w * NCB + cb;
-                        float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
-                        if (lane == 0) {
-                            if (direct) {
-                                if (lb < nb)
-                                    p.scores[(int64_t)(gb0 + lb) * p.b + ci.doc] = sum;
-                            } else {
-                                lds_part[buf][s][lb] = sum;
-                            }
+                    int lb = w * NCB + cb;
+                    float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
+                    if (lane == 0) {
+                        if (direct) {
+                            if (lb < nb)
+                                p.scores[(int64_t)(gb0 + lb) * p.b + ci.doc] = sum;
+                        } else {
+                            lds_part[par][lb] = sum;
                         }
                     }
                 }
-                it_next(ci, p, lane);
             }
+            it_next(ci, p, lane);
             __syncthreads();
-            if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
-#pragma unroll
-                for (int s = 0; s < STAGE; ++s) {
-                    if (fin_doc[s] < 0)
-                        continue;
+            if (fin_doc >= 0) {
+                if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
                     float sum = 0.0f;
-                    int first = (p.n_pass == 1) ? tid * p.bpq : 0;
+                    int first_blk = (p.n_pass == 1) ? tid * p.bpq : 0;
                     int cnt = (p.n_pass == 1) ? p.bpq : nb;
                     for (int i = 0; i < cnt; ++i)
-                        sum += lds_part[buf][s][first + i];
-                    float *dst = p.scores + (int64_t)(q_first + tid) * p.b + fin_doc[s];
+                        sum += lds_part[par][first_blk + i];
+                    float *dst = p.scores + (int64_t)(q_first + tid) * p.b + fin_doc;
                     *dst = accumulate ? *dst + sum : sum;
                 }
+                par ^= 1;
             }
-            buf ^= 1;
+            int t = o_cur;
+            o_cur = o_nxt;
+            o_nxt = o_wr;
+            o_wr = t;
+        };
+
+        if constexpr (PF) {
+            for (;;) {
+                stage(a0, a1);
+                if (!it_valid(ci))
+                    break;
+                stage(a1, a0);
+                if (!it_valid(ci))
+                    break;
+            }
+        } else {
+            while (it_valid(ci))
+                stage(a0, a1);
         }
         __syncthreads(); // LDS is reused by the next pass
     }

@@ -96,8 +96,9 @@ int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dty
 /*
  * int8 x int8 scoring with deferred dequantisation (Alg. 4; App. "INT8 Kernel").
  *   Q_i8 [n_q, l_q, d] int8, q_scale [n_q, l_q] float32
- *   D_i8 [b,   l_d, d] int8, d_scale [b,   l_d] float32   (scales must be >= 0)
- *   scores [n_q, b] float32
+ *   D_i8 [b,   l_d, d] int8, d_scale [b,   l_d] float32   (scales must be >= 0; a nonzero
+ *        scale below 2^-100 may cost the last bit of a negative score)
+ *   scores [n_q, b] float32;  l_q <= 1024, b * l_d < 2^31
  * Per cell: n = exact int32 dot product; v = fl32(n * d_scale[j]); m_i = max_j v;
  * r_i = fl32(q_scale[i] * m_i); score = sum_i r_i carried in fp64 and rounded once to fp32.
  * The result is a pure function of the inputs (bitwise reproducible).
@@ -105,6 +106,17 @@ int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dty
 int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q,
                       const int8_t *D_i8, const float *d_scale, int64_t b, int l_d, int d,
                       float *scores, void *stream);
+
+/*
+ * int8 scoring of a packed ragged corpus (Sec. "Ragged corpora and kernel family" applied to Alg. 4).
+ *   D_i8_packed    [total_tokens, d] int8, d_scale_packed [total_tokens] float32
+ *   doc_offsets    [b + 1] int32 (device), as in maxsim_forward_ragged; total_tokens < 2^31
+ * A document of length 0 gets score -inf.  Arithmetic and other arguments as in maxsim_forward_i8.
+ */
+int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q,
+                             const int8_t *D_i8_packed, const float *d_scale_packed,
+                             const int32_t *doc_offsets, int64_t b, int64_t total_tokens, int d,
+                             float *scores, void *stream);
 
 /*
  * Gradient of the in-batch-negatives cross-entropy on a score matrix (helper for the

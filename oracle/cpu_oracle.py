@@ -128,6 +128,49 @@ def forward_i8(Q_i8, q_scale, D_i8, d_scale, threads=None):
     return scores
 
 
+def _check_offsets(offsets, total):
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    if off[0] != 0 or off[-1] != total or np.any(np.diff(off) < 0):
+        raise ValueError("bad offsets")
+    return off
+
+
+def forward_i8_ragged(Q_i8, q_scale, D_i8_packed, d_scale_packed, offsets, threads=None):
+    """Alg. 4 over a packed corpus (Sec. "Ragged corpora and kernel family"): document j is rows
+    offsets[j]:offsets[j+1] and is scored by the uniform routine on its own; an empty document scores -inf."""
+    Dp = np.ascontiguousarray(D_i8_packed, dtype=np.int8)
+    sp = np.ascontiguousarray(d_scale_packed, dtype=np.float32)
+    off = _check_offsets(offsets, Dp.shape[0])
+    n_q, b = np.asarray(Q_i8).shape[0], off.shape[0] - 1
+    scores = np.full((n_q, b), -np.inf, np.float32)
+    for j in range(b):
+        s, e = int(off[j]), int(off[j + 1])
+        if e > s:
+            scores[:, j] = forward_i8(Q_i8, q_scale, Dp[None, s:e], sp[None, s:e], threads=threads or 1)[:, 0]
+    return scores
+
+
+def backward_ragged(Q, D_packed, dtype: str, offsets, argmax, g):
+    """Eqs. 2-3 over a packed corpus: dQ sums the per-document contributions, dD [T,d] is packed like D.
+    argmax [n_q,b,l_q] is document-local; negative entries (empty documents) are skipped."""
+    Qr, Dr = as_raw(Q, dtype), as_raw(D_packed, dtype)
+    n_q, l_q, d = Qr.shape
+    off = _check_offsets(offsets, Dr.shape[0])
+    b = off.shape[0] - 1
+    A = np.ascontiguousarray(argmax, dtype=np.int32)
+    G = np.ascontiguousarray(g, dtype=np.float64)
+    assert A.shape == (n_q, b, l_q) and G.shape == (n_q, b)
+    dQ = np.zeros((n_q, l_q, d), np.float64)
+    dD = np.zeros((Dr.shape[0], d), np.float64)
+    for j in range(b):
+        s, e = int(off[j]), int(off[j + 1])
+        if e > s:
+            q1, d1 = backward(Qr, Dr[None, s:e], dtype, A[:, j:j + 1], G[:, j:j + 1])
+            dQ += q1
+            dD[s:e] = d1[0]
+    return dQ, dD
+
+
 def dot_i8(Q_i8, D_i8):
     Qi = np.ascontiguousarray(Q_i8, dtype=np.int8)
     Di = np.ascontiguousarray(D_i8, dtype=np.int8)

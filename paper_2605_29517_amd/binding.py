@@ -17,7 +17,7 @@ MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
 SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward",
-           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_ce_grad",
+           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
 _lib = None
@@ -50,6 +50,8 @@ def load():
     L.maxsim_quantize_rows_i8.argtypes = [p, l, i, i, p, p, p]
     L.maxsim_forward_i8.restype = i
     L.maxsim_forward_i8.argtypes = [p, p, i, i, p, p, l, i, i, p, p]
+    L.maxsim_forward_i8_ragged.restype = i
+    L.maxsim_forward_i8_ragged.argtypes = [p, p, i, i, p, p, p, l, l, i, p, p]
     L.maxsim_ce_grad.restype = i
     L.maxsim_ce_grad.argtypes = [p, i, i, f, p, p, p]
     L.maxsim_probe_mfma.restype = i
@@ -184,6 +186,26 @@ def maxsim_forward_i8(Q_i8, q_scale, D_i8, d_scale, scores=None):
                                  _dev(D_i8, "D_i8", torch.int8), _dev(d_scale, "d_scale", torch.float32), b, l_d, d,
                                  _dev(scores, "scores", torch.float32), _stream(Q_i8))
     _check(rc, "maxsim_forward_i8")
+    return scores
+
+
+def maxsim_forward_i8_ragged(Q_i8, q_scale, D_i8_packed, d_scale_packed, doc_offsets, total_tokens=None, scores=None):
+    """int8 scoring of a packed corpus: D_i8_packed [T,d] + d_scale_packed [T], doc_offsets int32 [b+1] -> scores [n_q,b]."""
+    L = load()
+    n_q, l_q, d = Q_i8.shape
+    T = D_i8_packed.shape[0]
+    b = doc_offsets.shape[0] - 1
+    if total_tokens is None:
+        total_tokens = T
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
+    with _on_device(Q_i8, "Q_i8"):
+        rc = L.maxsim_forward_i8_ragged(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
+                                        _dev(D_i8_packed, "D_i8_packed", torch.int8),
+                                        _dev(d_scale_packed, "d_scale_packed", torch.float32),
+                                        _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
+                                        _dev(scores, "scores", torch.float32), _stream(Q_i8))
+    _check(rc, "maxsim_forward_i8_ragged")
     return scores
 
 

@@ -10,7 +10,8 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, int64
                            hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
-                             int64_t b, int l_d, float *scores, int num_cu, hipStream_t stream);
+                             const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
+                             int num_cu, hipStream_t stream);
 hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream);
 hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream);
 hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream);
@@ -141,10 +142,30 @@ int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q
         return MAXSIM_ERR_INVALID;
     if (d != maxsim::D_MODEL)
         return MAXSIM_ERR_UNSUPPORTED;
-    if (b >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24))
+    if (b >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) ||
+        l_q > 1024 || b * (int64_t)l_d >= (int64_t(1) << 31))
         return MAXSIM_ERR_UNSUPPORTED;
-    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, b, l_d, scores, num_cu(),
-                                            static_cast<hipStream_t>(stream)));
+    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, nullptr, b, l_d, b * (int64_t)l_d,
+                                            scores, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q, const int8_t *D_i8_packed,
+                             const float *d_scale_packed, const int32_t *doc_offsets, int64_t b, int64_t total_tokens,
+                             int d, float *scores, void *stream)
+{
+    if (!Q_i8 || !q_scale || !D_i8_packed || !d_scale_packed || !doc_offsets || !scores || n_q < 1 || l_q < 1 || b < 1 ||
+        total_tokens < 1)
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q_i8, 16) || !aligned(D_i8_packed, 16) || !aligned(q_scale, 4) || !aligned(d_scale_packed, 4) ||
+        !aligned(doc_offsets, 4) || !aligned(scores, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (b >= (int64_t(1) << 31) || total_tokens >= (int64_t(1) << 31) ||
+        (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8_packed, d_scale_packed, doc_offsets, b, 0,
+                                            total_tokens, scores, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss, void *stream)

@@ -42,7 +42,7 @@ struct I8Params {
     const char *D;      // [b, l_d, 128] int8
     const float *ds;    // [b, l_d]
     float *scores;      // [n_q, b]
-    FwdParams f;        // sizes and work split (offsets = nullptr)
+    FwdParams f;        // sizes, optional offsets and the work split
 };
 
 template <int W>
@@ -76,6 +76,12 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
     chunk_doc_range(p, chunk, doc0, doc1);
     if (doc0 >= doc1)
         return;
+    if (group == 0 && p.offsets) { // empty documents: score -inf
+        for (int64_t doc = doc0 + tid; doc < doc1; doc += NT)
+            if (p.offsets[doc + 1] == p.offsets[doc])
+                for (int q = 0; q < p.n_q; ++q)
+                    P.scores[(int64_t)q * p.b + doc] = neg_inf();
+    }
 
     const int q_first = group * p.qpg;
     const int nq = min(p.qpg, p.n_q - q_first);
@@ -252,14 +258,215 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// document-stationary kernel for large corpora
+// ---------------------------------------------------------------------------------------
+// The roles are turned around: the query tokens of a group (up to 1024, padded rows, plus
+// their scales) are copied into LDS once per workgroup, and every wavefront works alone on
+// its own run of documents.  A 32-token document tile goes from HBM straight into registers
+// in MFMA operand layout, one tile ahead, and stays there while the wavefront walks over all
+// column blocks of the group, reading the B operands of block k + 1 from LDS during the
+// MFMAs of block k and folding block k - 1 under them.  There is no barrier, no LDS write
+// and no staging copy in the main loop, the per-tile work (scales, loads, iterator) is
+// spread over up to 128 MFMAs instead of 32, and the wavefronts of a SIMD drift apart so
+// that one computes while the other waits.  The token scales of a tile take a detour through
+// 512 bytes of LDS private to the wavefront to get from "one per lane" to "the 16 rows of
+// this lane's accumulator registers".
+constexpr int I8D_WAVES = 8;
+constexpr int I8D_MAX_BLOCKS = 32;                       // column blocks per group (1024 query tokens)
+constexpr int I8D_QSTRIDE = I8_ROW_BYTES + 16;           // padded LDS row of a query token
+
+__global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
+{
+    const FwdParams &p = P.f;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int rho = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int group = blockIdx.x % p.n_groups;
+    const int wg_chunk = blockIdx.x / p.n_groups;
+    const int q_first = group * p.qpg;
+    const int nq = min(p.qpg, p.n_q - q_first);
+    const int gb0 = q_first * p.bpq;
+    const int nb = nq * p.bpq; // column blocks of this group, <= I8D_MAX_BLOCKS
+
+    // LDS: query rows [nb * 32][144 B], query scales [nb * 32] (0 for padding columns), then
+    // per wavefront 32 token scales and 32 biases
+    char *q_tile = smem;
+    float *q_scale = reinterpret_cast<float *>(smem + nb * BLOCK_COLS * I8D_QSTRIDE);
+    float *w_scale = q_scale + nb * BLOCK_COLS + w * 64;
+    float *w_bias = w_scale + 32;
+
+    for (int c = tid; c < nb * BLOCK_COLS * 8; c += I8D_WAVES * 64) { // 16-byte chunks of the group's query rows
+        int col = c >> 3, part = c & 7;
+        int gb = gb0 + col / BLOCK_COLS;
+        int q = gb / p.bpq;
+        int tok = (gb % p.bpq) * BLOCK_COLS + col % BLOCK_COLS;
+        bool valid = tok < p.l_q;
+        if (!valid)
+            tok = p.l_q - 1;
+        const int64_t qrow = (int64_t)q * p.l_q + tok;
+        *reinterpret_cast<uint4 *>(q_tile + col * I8D_QSTRIDE + part * 16) =
+            *reinterpret_cast<const uint4 *>(P.Q + qrow * I8_ROW_BYTES + part * 16);
+        if (part == 0)
+            q_scale[col] = valid ? P.qs[qrow] : 0.0f;
+    }
+    __syncthreads(); // the only barrier: from here on every wavefront is on its own
+
+    int64_t doc0_, doc1_;
+    chunk_doc_range(p, (int64_t)wg_chunk * I8D_WAVES + w, doc0_, doc1_);
+    if (doc0_ >= doc1_)
+        return;
+    const int doc0 = (int)doc0_, doc1 = (int)doc1_;
+    if (group == 0 && p.offsets) { // empty documents of this wavefront's run: score -inf
+        for (int doc = doc0 + lane; doc < doc1; doc += 64)
+            if (p.offsets[doc + 1] == p.offsets[doc])
+                for (int q = 0; q < p.n_q; ++q)
+                    P.scores[(int64_t)q * p.b + doc] = neg_inf();
+    }
+
+    TileIter li, ci; // load iterator: one tile ahead of the compute iterator
+    it_init(li, p, doc0, doc1, lane);
+    ci = li;
+    if (!it_valid(ci))
+        return;
+
+    i32x4 a_n[I8_NU];
+    float s_n = 0.0f;
+    auto gload = [&]() {
+        if (!it_valid(li))
+            return;
+        int row = li.len - li.t0 - 1; // rows past the document re-read its last token
+        row = rho < row ? rho : row;
+        const int64_t grow = (int64_t)li.row0 + row;
+        const char *src = P.D + grow * I8_ROW_BYTES + h * 16;
+#pragma unroll
+        for (int u = 0; u < I8_NU; ++u)
+            a_n[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
+        s_n = P.ds[grow];
+        it_next(li, p, lane);
+    };
+    gload();
+
+    i32x16 seed;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int v = 0x4B000000;
+        asm volatile("" : "+v"(v));
+        seed[r] = v;
+    }
+
+    float m[I8D_MAX_BLOCKS];
+    const int b_off = rho * I8D_QSTRIDE + h * 16; // this lane's B operand chunk 0 inside a block
+
+    while (it_valid(ci)) {
+        // the prefetched tile becomes the current one; its scales go through the wavefront's LDS area
+        i32x4 a[I8_NU];
+#pragma unroll
+        for (int u = 0; u < I8_NU; ++u)
+            a[u] = a_n[u];
+        if (h == 0) {
+            w_scale[rho] = s_n;
+            w_bias[rho] = s_n * -8388608.0f;
+        }
+        gload(); // next tile, in flight during this one
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        float sc[16], bi[16];
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            float4 s4 = *reinterpret_cast<const float4 *>(&w_scale[r4 * 8 + h * 4]);
+            float4 b4 = *reinterpret_cast<const float4 *>(&w_bias[r4 * 8 + h * 4]);
+            sc[r4 * 4 + 0] = s4.x;
+            sc[r4 * 4 + 1] = s4.y;
+            sc[r4 * 4 + 2] = s4.z;
+            sc[r4 * 4 + 3] = s4.w;
+            bi[r4 * 4 + 0] = b4.x;
+            bi[r4 * 4 + 1] = b4.y;
+            bi[r4 * 4 + 2] = b4.z;
+            bi[r4 * 4 + 3] = b4.w;
+        }
+        if (ci.t0 == 0) {
+#pragma unroll
+            for (int blk = 0; blk < I8D_MAX_BLOCKS; ++blk)
+                m[blk] = neg_inf();
+        }
+
+        i32x4 qb[2][I8_NU];
+#pragma unroll
+        for (int u = 0; u < I8_NU; ++u)
+            qb[0][u] = *reinterpret_cast<const i32x4 *>(q_tile + b_off + u * 32);
+        i32x16 acc[2];
+        __builtin_amdgcn_sched_barrier(0);
+        // step (blk, u): MFMA u of block blk, LDS read of chunk u of block blk + 1, a quarter of the
+        // epilogue of block blk - 1
+#pragma unroll
+        for (int blk = 0; blk <= I8D_MAX_BLOCKS; ++blk) {
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u) {
+                if (blk < I8D_MAX_BLOCKS && blk < nb) {
+                    acc[blk & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qb[blk & 1][u], u == 0 ? seed : acc[blk & 1], 0, 0, 0);
+                    if (blk + 1 < nb)
+                        qb[(blk + 1) & 1][u] = *reinterpret_cast<const i32x4 *>(
+                            q_tile + (blk + 1) * (BLOCK_COLS * I8D_QSTRIDE) + b_off + u * 32);
+                }
+                if (blk > 0 && blk <= nb) {
+                    const i32x16 &e = acc[(blk - 1) & 1];
+                    const int r = 4 * u;
+                    float v0 = __builtin_fmaf(__int_as_float(e[r + 0]), sc[r + 0], bi[r + 0]);
+                    float v1 = __builtin_fmaf(__int_as_float(e[r + 1]), sc[r + 1], bi[r + 1]);
+                    float v2 = __builtin_fmaf(__int_as_float(e[r + 2]), sc[r + 2], bi[r + 2]);
+                    float v3 = __builtin_fmaf(__int_as_float(e[r + 3]), sc[r + 3], bi[r + 3]);
+                    float mm = m[blk - 1];
+                    mm = fmaxf(fmaxf(mm, v0), v1);
+                    mm = fmaxf(fmaxf(mm, v2), v3);
+                    m[blk - 1] = mm;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+        if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of the document
+            // per query: lane-local fp64 sum over its blocks, then one butterfly over the 32 columns
+            double dv = 0.0;
+            int iq = 0, j = 0; // block inside the query, query inside the group
+#pragma unroll
+            for (int blk = 0; blk < I8D_MAX_BLOCKS; ++blk) {
+                if (blk >= nb)
+                    continue;
+                float mm = fmaxf(m[blk], __shfl_xor(m[blk], 32));
+                mm = mm < 0.0f ? mm + mm : mm;                     // negative maxima were carried halved
+                float r = q_scale[blk * BLOCK_COLS + rho] * mm;    // one IEEE fp32 multiply per query token
+                dv += (iq * BLOCK_COLS + rho < p.l_q) ? (double)r : 0.0;
+                if (++iq == p.bpq) {
+#pragma unroll
+                    for (int o = 16; o > 0; o >>= 1)
+                        dv += __shfl_xor(dv, o);
+                    if (lane == 0)
+                        P.scores[(int64_t)(q_first + j) * p.b + ci.doc] = (float)dv;
+                    dv = 0.0;
+                    iq = 0;
+                    ++j;
+                }
+            }
+        }
+        it_next(ci, p, lane);
+    }
+}
+
 template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStream_t s)
 {
     hipLaunchKernelGGL((fwd_i8_kernel<W>), dim3(grid), dim3(W * 64), 0, s, P);
     return hipGetLastError();
 }
 
+// offsets == nullptr: uniform corpus [b, l_d, 128]; otherwise packed [total_tokens, 128] with int32 offsets [b + 1]
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
-                             int64_t b, int l_d, float *scores, int num_cu, hipStream_t stream)
+                             const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
+                             int num_cu, hipStream_t stream)
 {
     I8Params P;
     P.Q = reinterpret_cast<const char *>(Q);
@@ -269,13 +476,45 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
     P.scores = scores;
     FwdParams &p = P.f;
     p = FwdParams{};
+    p.offsets = offsets;
+    p.scores = scores;
     p.b = b;
-    p.total_tokens = b * (int64_t)l_d;
+    p.total_tokens = total_tokens;
     p.n_q = n_q;
     p.l_q = l_q;
     p.l_d = l_d;
     p.bpq = (l_q + BLOCK_COLS - 1) / BLOCK_COLS;
+    p.n_pass = 1;
     const int64_t total_blocks = (int64_t)n_q * p.bpq;
+    const int64_t units = offsets ? total_tokens : b; // what is split across chunks
+    if (p.bpq > I8D_MAX_BLOCKS)
+        return hipErrorNotSupported; // l_q > 1024: would need a second pass with an fp64 carry
+
+    // Large corpora: document-stationary kernel, one run of documents per wavefront.
+    if (b >= (int64_t)num_cu * I8D_WAVES * 2) {
+        p.qpg = I8D_MAX_BLOCKS / p.bpq;
+        if (p.qpg > n_q)
+            p.qpg = n_q;
+        p.n_groups = (n_q + p.qpg - 1) / p.qpg;
+        int wgs = num_cu / p.n_groups; // per group; the query copy in LDS allows one workgroup per CU
+        if (wgs < 1)
+            wgs = 1;
+        int64_t n_chunks = (int64_t)wgs * I8D_WAVES;
+        p.unit_per_chunk = (units + n_chunks - 1) / n_chunks;
+        if (!offsets)
+            n_chunks = (units + p.unit_per_chunk - 1) / p.unit_per_chunk;
+        p.n_chunks = (int)n_chunks;
+        wgs = (int)((n_chunks + I8D_WAVES - 1) / I8D_WAVES);
+        const int nb = p.qpg * p.bpq;
+        const size_t lds = (size_t)nb * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        hipLaunchKernelGGL(fwd_i8_doc_kernel, dim3(wgs * p.n_groups), dim3(I8D_WAVES * 64), lds, stream, P);
+        return hipGetLastError();
+    }
+
     int w = 8;
     if (total_blocks <= 1 * I8_NCB)
         w = 1;
@@ -284,18 +523,15 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
     else if (total_blocks <= 4 * I8_NCB)
         w = 4;
     const int group_blocks = w * I8_NCB;
-    if (p.bpq > group_blocks)
-        return hipErrorNotSupported; // l_q > 1024: would need a second pass with an fp64 carry
     p.qpg = group_blocks / p.bpq;
     if (p.qpg > n_q)
         p.qpg = n_q;
     p.n_groups = (n_q + p.qpg - 1) / p.qpg;
-    p.n_pass = 1;
     int64_t n_chunks = ((int64_t)num_cu * 2 + p.n_groups - 1) / p.n_groups;
     if (n_chunks < 8)
         n_chunks = 8;
     n_chunks = (n_chunks + 7) / 8 * 8;
-    p.unit_per_chunk = (b + n_chunks - 1) / n_chunks;
+    p.unit_per_chunk = (units + n_chunks - 1) / n_chunks;
     if (p.unit_per_chunk < 1)
         p.unit_per_chunk = 1;
     p.n_chunks = (int)n_chunks;

@@ -78,3 +78,68 @@ def test_forward_i8_rejects_queries_longer_than_one_group():
     D = torch.zeros((2, 10, 128), dtype=torch.int8, device=DEV)
     with pytest.raises(M.MaxSimError):
         M.maxsim_forward_i8(Q, torch.ones(1, 1100, device=DEV), D, torch.ones(2, 10, device=DEV))
+
+
+def ragged_case(n_q, l_q, lens, seed):
+    """Packed int8 corpus with the given document lengths (GPU quantiser output, checked against the oracle's)."""
+    lens = np.asarray(lens, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(off[-1])
+    Qf = W.unit_rows((n_q, l_q, 128), "f16", seed, DEV)
+    Df = W.unit_rows((T, 128), "f32", seed + 1, DEV)
+    oq, oqs = O.quantize_rows_i8(W.to_raw_numpy(Qf), "f16")
+    od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df), "f32")
+    gq, gqs = M.maxsim_quantize_rows_i8(Qf)
+    gd, gds = M.maxsim_quantize_rows_i8(Df)
+    torch.cuda.synchronize()
+    assert np.array_equal(gd.cpu().numpy(), od) and np.array_equal(bits(gds.cpu().numpy()), bits(ods))
+    assert np.array_equal(gq.cpu().numpy(), oq) and np.array_equal(bits(gqs.cpu().numpy()), bits(oqs))
+    return (gq, gqs, gd, gds, torch.from_numpy(off).to(DEV)), (oq, oqs, od, ods, off)
+
+
+@pytest.mark.parametrize("case", [(1, 32, [5, 0, 64, 65, 1, 130, 0]), (3, 40, [33] * 9 + [0, 200]), (2, 512, [31, 97, 300])])
+def test_forward_i8_ragged_bit_exact_small(case):
+    n_q, l_q, lens = case
+    g, o = ragged_case(n_q, l_q, lens, 23)
+    s = M.maxsim_forward_i8_ragged(*g)
+    torch.cuda.synchronize()
+    ref = O.forward_i8_ragged(*o)
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+
+
+# corpora of >= 4096 documents take the document-stationary kernel (every wavefront on its own run of documents)
+@pytest.mark.parametrize("shape", [(1, 32, 4100, 70), (2, 100, 4200, 33), (1, 1024, 4096, 40), (40, 32, 4500, 20), (3, 200, 4100, 65)])
+def test_forward_i8_large_corpus_bit_exact(shape):
+    n_q, l_q, b, l_d = shape
+    g, o = quantised_case(n_q, l_q, b, l_d, 31)
+    s = M.maxsim_forward_i8(*g)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(*o)
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+
+
+def test_forward_i8_ragged_large_corpus_bit_exact():
+    rng = np.random.default_rng(9)
+    lens = rng.integers(0, 150, 5000)
+    lens[:4] = [0, 1, 32, 33]
+    lens[-1] = 0
+    for n_q, l_q in ((1, 64), (5, 200)):
+        g, o = ragged_case(n_q, l_q, lens, 37)
+        s = M.maxsim_forward_i8_ragged(*g)
+        torch.cuda.synchronize()
+        ref = O.forward_i8_ragged(*o)
+        assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+
+
+def test_forward_i8_large_corpus_negative_maxima():
+    b = 4100
+    Q = torch.full((1, 33, 128), -127, dtype=torch.int8, device=DEV)
+    D = torch.full((b, 35, 128), 127, dtype=torch.int8, device=DEV)
+    D[1::2, 5] = -127
+    qs = torch.rand(1, 33, device=DEV) + 0.5
+    ds = torch.rand(b, 35, device=DEV) + 0.01
+    s = M.maxsim_forward_i8(Q, qs, D, ds)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+    assert float(s[0, 0]) < 0 < float(s[0, 1])

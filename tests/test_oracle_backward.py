@@ -112,3 +112,40 @@ def test_cross_entropy_helper():
     # large scores at the paper-scale temperature stay finite
     l2, g2 = O.ce_grad(np.array([[30.0, 10.0], [5.0, 31.0]]), 0.02)
     assert np.isfinite(l2) and np.all(np.isfinite(g2))
+
+
+def test_ragged_backward_against_the_definition_written_out():
+    """Packed corpus: dQ[q,i] = sum_j g[q,j] D_j[A[q,j,i]], dD_j[t] = sum over edges landing on t of g[q,j] Q[q,i]."""
+    rng = np.random.default_rng(5)
+    n_q, l_q, d = 3, 4, 6
+    lens = np.array([5, 0, 1, 7])
+    off = np.concatenate([[0], np.cumsum(lens)])
+    Q = rng.standard_normal((n_q, l_q, d)).astype(np.float32)
+    Dp = rng.standard_normal((int(off[-1]), d)).astype(np.float32)
+    g = rng.standard_normal((n_q, len(lens)))
+    _, A, _ = O.forward(Q, Dp, "f32", offsets=off)
+    assert np.all(A[:, 1] == -1)
+    dQ, dD = O.backward_ragged(Q, Dp, "f32", off, A, g)
+    rQ = np.zeros((n_q, l_q, d))
+    rD = np.zeros((int(off[-1]), d))
+    for q in range(n_q):
+        for j in range(len(lens)):
+            for i in range(l_q):
+                t = A[q, j, i]
+                if t < 0:
+                    continue
+                rQ[q, i] += g[q, j] * Dp[off[j] + t].astype(np.float64)
+                rD[off[j] + t] += g[q, j] * Q[q, i].astype(np.float64)
+    assert np.allclose(dQ, rQ, rtol=1e-12, atol=1e-12) and np.allclose(dD, rD, rtol=1e-12, atol=1e-12)
+    # Euler identity (the score is homogeneous of degree one in Q and in D)
+    s, _, _ = O.forward(Q, Dp, "f32", offsets=off)
+    fin = np.isfinite(s)
+    total = float((g[fin] * s[fin]).sum())
+    assert abs((dQ * Q).sum() - total) < 1e-9 and abs((dD * Dp).sum() - total) < 1e-9
+    # equal lengths: identical to the uniform routine
+    D = rng.standard_normal((3, 5, d)).astype(np.float32)
+    _, A2, _ = O.forward(Q, D, "f32")
+    g2 = rng.standard_normal((n_q, 3))
+    uQ, uD = O.backward(Q, D, "f32", A2, g2)
+    pQ, pD = O.backward_ragged(Q, D.reshape(15, d), "f32", np.arange(4) * 5, A2, g2)
+    assert np.allclose(pQ, uQ, rtol=0, atol=1e-12) and np.array_equal(pD.reshape(3, 5, d), uD)

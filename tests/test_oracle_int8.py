@@ -84,3 +84,23 @@ def test_quantiser_rounds_half_to_even_and_accepts_16bit():
     Xh = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 3.5]], np.float16)
     ch, sh = O.quantize_rows_i8(Xh, "f16")
     assert sh[0] == 1.0 and ch[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 4]
+
+
+def test_ragged_equals_uniform_when_lengths_are_equal_and_brute_force_otherwise():
+    rng = np.random.default_rng(11)
+    Q = rng.integers(-127, 128, (2, 5, 16), dtype=np.int8)
+    qs = rng.random((2, 5)).astype(np.float32) + 0.1
+    D = rng.integers(-127, 128, (4, 6, 16), dtype=np.int8)
+    ds = rng.random((4, 6)).astype(np.float32) + 0.1
+    off = np.arange(5) * 6
+    s_r = O.forward_i8_ragged(Q, qs, D.reshape(24, 16), ds.reshape(24), off)
+    assert np.array_equal(s_r.view(np.uint32), O.forward_i8(Q, qs, D, ds).view(np.uint32))
+    # unequal lengths incl. an empty document: the definition written out with numpy (float32 per-cell scaling)
+    off = np.array([0, 1, 1, 9, 24])
+    s_r = O.forward_i8_ragged(Q, qs, D.reshape(24, 16), ds.reshape(24), off)
+    assert np.all(np.isneginf(s_r[:, 1]))
+    n = np.einsum("qik,tk->qit", Q.astype(np.int64), D.reshape(24, 16).astype(np.int64))
+    for j in (0, 2, 3):
+        v = (n[:, :, off[j]:off[j + 1]].astype(np.float64) * ds.reshape(24)[off[j]:off[j + 1]].astype(np.float64)).astype(np.float32)
+        r = (qs.astype(np.float64) * v.max(2).astype(np.float64)).astype(np.float32)
+        assert np.array_equal(s_r[:, j], r.astype(np.float64).sum(1).astype(np.float32))

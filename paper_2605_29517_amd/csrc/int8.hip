@@ -276,6 +276,9 @@ constexpr int I8D_WAVES = 8;
 constexpr int I8D_MAX_BLOCKS = 32;                       // column blocks per group (1024 query tokens)
 constexpr int I8D_QSTRIDE = I8_ROW_BYTES + 16;           // padded LDS row of a query token
 
+// NB: column blocks the tile loop walks over (the group's block count rounded up; the surplus
+// blocks multiply zero rows and are never looked at).
+template <int NB>
 __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
 {
     const FwdParams &p = P.f;
@@ -292,26 +295,31 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
     const int gb0 = q_first * p.bpq;
     const int nb = nq * p.bpq; // column blocks of this group, <= I8D_MAX_BLOCKS
 
-    // LDS: query rows [nb * 32][144 B], query scales [nb * 32] (0 for padding columns), then
+    // LDS: query rows [NB * 32][144 B], query scales [NB * 32] (0 for padding columns), then
     // per wavefront 32 token scales and 32 biases
     char *q_tile = smem;
-    float *q_scale = reinterpret_cast<float *>(smem + nb * BLOCK_COLS * I8D_QSTRIDE);
-    float *w_scale = q_scale + nb * BLOCK_COLS + w * 64;
+    float *q_scale = reinterpret_cast<float *>(smem + NB * BLOCK_COLS * I8D_QSTRIDE);
+    float *w_scale = q_scale + NB * BLOCK_COLS + w * 64;
     float *w_bias = w_scale + 32;
 
-    for (int c = tid; c < nb * BLOCK_COLS * 8; c += I8D_WAVES * 64) { // 16-byte chunks of the group's query rows
+    for (int c = tid; c < NB * BLOCK_COLS * 8; c += I8D_WAVES * 64) { // 16-byte chunks of the group's query rows
         int col = c >> 3, part = c & 7;
-        int gb = gb0 + col / BLOCK_COLS;
-        int q = gb / p.bpq;
-        int tok = (gb % p.bpq) * BLOCK_COLS + col % BLOCK_COLS;
-        bool valid = tok < p.l_q;
-        if (!valid)
-            tok = p.l_q - 1;
-        const int64_t qrow = (int64_t)q * p.l_q + tok;
-        *reinterpret_cast<uint4 *>(q_tile + col * I8D_QSTRIDE + part * 16) =
-            *reinterpret_cast<const uint4 *>(P.Q + qrow * I8_ROW_BYTES + part * 16);
+        uint4 chunk = make_uint4(0, 0, 0, 0);
+        float qsv = 0.0f;
+        if (col < nb * BLOCK_COLS) {
+            int gb = gb0 + col / BLOCK_COLS;
+            int q = gb / p.bpq;
+            int tok = (gb % p.bpq) * BLOCK_COLS + col % BLOCK_COLS;
+            bool valid = tok < p.l_q;
+            if (!valid)
+                tok = p.l_q - 1;
+            const int64_t qrow = (int64_t)q * p.l_q + tok;
+            chunk = *reinterpret_cast<const uint4 *>(P.Q + qrow * I8_ROW_BYTES + part * 16);
+            qsv = valid ? P.qs[qrow] : 0.0f;
+        }
+        *reinterpret_cast<uint4 *>(q_tile + col * I8D_QSTRIDE + part * 16) = chunk;
         if (part == 0)
-            q_scale[col] = valid ? P.qs[qrow] : 0.0f;
+            q_scale[col] = qsv;
     }
     __syncthreads(); // the only barrier: from here on every wavefront is on its own
 
@@ -358,7 +366,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
         seed[r] = v;
     }
 
-    float m[I8D_MAX_BLOCKS];
+    float m[NB];
     const int b_off = rho * I8D_QSTRIDE + h * 16; // this lane's B operand chunk 0 inside a block
 
     while (it_valid(ci)) {
@@ -391,7 +399,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
         }
         if (ci.t0 == 0) {
 #pragma unroll
-            for (int blk = 0; blk < I8D_MAX_BLOCKS; ++blk)
+            for (int blk = 0; blk < NB; ++blk)
                 m[blk] = neg_inf();
         }
 
@@ -399,34 +407,38 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
 #pragma unroll
         for (int u = 0; u < I8_NU; ++u)
             qb[0][u] = *reinterpret_cast<const i32x4 *>(q_tile + b_off + u * 32);
-        i32x16 acc[2];
+        i32x16 acc[3];
         __builtin_amdgcn_sched_barrier(0);
-        // step (blk, u): MFMA u of block blk, LDS read of chunk u of block blk + 1, a quarter of the
-        // epilogue of block blk - 1
+        // step t: MFMA (t % 4) of block t / 4, the LDS read of the same chunk of the next block, and a
+        // quarter of the epilogue of the block whose chain ended I8D_LAG steps ago (so that its
+        // results have long left the matrix pipeline); three accumulators rotate
+#ifndef I8D_LAG_STEPS
+#define I8D_LAG_STEPS 2
+#endif
+        constexpr int I8D_LAG = I8D_LAG_STEPS;
 #pragma unroll
-        for (int blk = 0; blk <= I8D_MAX_BLOCKS; ++blk) {
-#pragma unroll
-            for (int u = 0; u < I8_NU; ++u) {
-                if (blk < I8D_MAX_BLOCKS && blk < nb) {
-                    acc[blk & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qb[blk & 1][u], u == 0 ? seed : acc[blk & 1], 0, 0, 0);
-                    if (blk + 1 < nb)
-                        qb[(blk + 1) & 1][u] = *reinterpret_cast<const i32x4 *>(
-                            q_tile + (blk + 1) * (BLOCK_COLS * I8D_QSTRIDE) + b_off + u * 32);
-                }
-                if (blk > 0 && blk <= nb) {
-                    const i32x16 &e = acc[(blk - 1) & 1];
-                    const int r = 4 * u;
-                    float v0 = __builtin_fmaf(__int_as_float(e[r + 0]), sc[r + 0], bi[r + 0]);
-                    float v1 = __builtin_fmaf(__int_as_float(e[r + 1]), sc[r + 1], bi[r + 1]);
-                    float v2 = __builtin_fmaf(__int_as_float(e[r + 2]), sc[r + 2], bi[r + 2]);
-                    float v3 = __builtin_fmaf(__int_as_float(e[r + 3]), sc[r + 3], bi[r + 3]);
-                    float mm = m[blk - 1];
-                    mm = fmaxf(fmaxf(mm, v0), v1);
-                    mm = fmaxf(fmaxf(mm, v2), v3);
-                    m[blk - 1] = mm;
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < NB * I8_NU + I8_NU + I8D_LAG; ++t) {
+            const int blk = t / I8_NU, u = t % I8_NU;
+            if (blk < NB) {
+                acc[blk % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qb[blk & 1][u], u == 0 ? seed : acc[blk % 3], 0, 0, 0);
+                if (blk + 1 < NB)
+                    qb[(blk + 1) & 1][u] = *reinterpret_cast<const i32x4 *>(
+                        q_tile + (blk + 1) * (BLOCK_COLS * I8D_QSTRIDE) + b_off + u * 32);
             }
+            const int te = t - I8_NU - I8D_LAG; // epilogue step
+            if (te >= 0) {
+                const int eb = te / I8_NU, r = 4 * (te % I8_NU);
+                const i32x16 &e = acc[eb % 3];
+                float v0 = __builtin_fmaf(__int_as_float(e[r + 0]), sc[r + 0], bi[r + 0]);
+                float v1 = __builtin_fmaf(__int_as_float(e[r + 1]), sc[r + 1], bi[r + 1]);
+                float v2 = __builtin_fmaf(__int_as_float(e[r + 2]), sc[r + 2], bi[r + 2]);
+                float v3 = __builtin_fmaf(__int_as_float(e[r + 3]), sc[r + 3], bi[r + 3]);
+                float mm = m[eb];
+                mm = fmaxf(fmaxf(mm, v0), v1);
+                mm = fmaxf(fmaxf(mm, v2), v3);
+                m[eb] = mm;
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of the document
@@ -434,7 +446,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
             double dv = 0.0;
             int iq = 0, j = 0; // block inside the query, query inside the group
 #pragma unroll
-            for (int blk = 0; blk < I8D_MAX_BLOCKS; ++blk) {
+            for (int blk = 0; blk < NB; ++blk) {
                 if (blk >= nb)
                     continue;
                 float mm = fmaxf(m[blk], __shfl_xor(m[blk], 32));
@@ -460,6 +472,17 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
 template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStream_t s)
 {
     hipLaunchKernelGGL((fwd_i8_kernel<W>), dim3(grid), dim3(W * 64), 0, s, P);
+    return hipGetLastError();
+}
+
+template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, hipStream_t s)
+{
+    const size_t lds = (size_t)NB * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess)
+        return e;
+    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P);
     return hipGetLastError();
 }
 
@@ -506,13 +529,14 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
         p.n_chunks = (int)n_chunks;
         wgs = (int)((n_chunks + I8D_WAVES - 1) / I8D_WAVES);
         const int nb = p.qpg * p.bpq;
-        const size_t lds = (size_t)nb * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float);
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return e;
-        hipLaunchKernelGGL(fwd_i8_doc_kernel, dim3(wgs * p.n_groups), dim3(I8D_WAVES * 64), lds, stream, P);
-        return hipGetLastError();
+        const int grid = wgs * p.n_groups;
+        if (nb <= 1) return launch_i8_doc<1>(P, grid, stream);
+        if (nb <= 2) return launch_i8_doc<2>(P, grid, stream);
+        if (nb <= 4) return launch_i8_doc<4>(P, grid, stream);
+        if (nb <= 8) return launch_i8_doc<8>(P, grid, stream);
+        if (nb <= 16) return launch_i8_doc<16>(P, grid, stream);
+        if (nb <= 24) return launch_i8_doc<24>(P, grid, stream);
+        return launch_i8_doc<32>(P, grid, stream);
     }
 
     int w = 8;

@@ -85,6 +85,21 @@ int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, i
                     float *dD, void *stream);
 
 /*
+ * Backward over a packed ragged corpus (Eqs. 2-3 with the ragged layout of Sec. "Ragged corpora
+ * and kernel family").
+ *   D_packed, doc_offsets, total_tokens as in maxsim_forward_ragged
+ *   argmax  [n_q, b, l_q] int32   document-local indices as written by maxsim_forward_ragged;
+ *                                 negative entries (empty documents) are skipped
+ *   dQ      [n_q, l_q, d] float32 fully overwritten
+ *   dD_packed [total_tokens, d] float32 fully overwritten, packed like D_packed
+ * Same arithmetic and reproducibility as maxsim_backward.
+ */
+int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed,
+                           const int32_t *doc_offsets, int64_t b, int64_t total_tokens, int d,
+                           maxsim_dtype dtype, const int32_t *argmax, const float *dscore,
+                           float *dQ, float *dD_packed, void *stream);
+
+/*
  * Per-token symmetric absmax quantiser (Sec. "Quantised Scoring").
  *   X      [rows, d] dtype
  *   X_i8   [rows, d] int8    round_half_even(x / scale), clamped to [-127, 127]

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libmaxsim.so")
 MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
-SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward",
+SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward", "maxsim_backward_ragged",
            "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
@@ -46,6 +46,8 @@ def load():
     L.maxsim_forward_ragged.argtypes = [p, i, i, p, p, l, l, i, i, p, p, p]
     L.maxsim_backward.restype = i
     L.maxsim_backward.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p]
+    L.maxsim_backward_ragged.restype = i
+    L.maxsim_backward_ragged.argtypes = [p, i, i, p, p, l, l, i, i, p, p, p, p, p]
     L.maxsim_quantize_rows_i8.restype = i
     L.maxsim_quantize_rows_i8.argtypes = [p, l, i, i, p, p, p]
     L.maxsim_forward_i8.restype = i
@@ -155,6 +157,30 @@ def maxsim_backward(Q, D, argmax, dscore, dQ=None, dD=None):
                                _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
                                _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
     _check(rc, "maxsim_backward")
+    return dQ, dD
+
+
+def maxsim_backward_ragged(Q, D_packed, doc_offsets, argmax, dscore, total_tokens=None, dQ=None, dD=None):
+    """Eqs. 2-3 over a packed corpus: returns (dQ fp32 [n_q,l_q,d], dD fp32 [T,d] packed like D_packed)."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    T = D_packed.shape[0]
+    b = doc_offsets.shape[0] - 1
+    if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
+        raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
+    if total_tokens is None:
+        total_tokens = T
+    if dQ is None:
+        dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
+    if dD is None:
+        dD = torch.empty(T, d, dtype=torch.float32, device=Q.device)
+    with _on_device(Q, "Q"):
+        rc = L.maxsim_backward_ragged(_dev(Q, "Q"), n_q, l_q, _dev(D_packed, "D_packed"),
+                                      _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
+                                      _DTYPE[Q.dtype], _dev(argmax, "argmax", torch.int32),
+                                      _dev(dscore, "dscore", torch.float32), _dev(dQ, "dQ", torch.float32),
+                                      _dev(dD, "dD", torch.float32), _stream(Q))
+    _check(rc, "maxsim_backward_ragged")
     return dQ, dD
 
 

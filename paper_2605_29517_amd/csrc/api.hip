@@ -5,9 +5,9 @@
 
 namespace maxsim {
 hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream);
-hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
-                           const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
-                           hipStream_t stream);
+hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
+                           int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                           float *dD, int num_cu, hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
@@ -115,8 +115,27 @@ int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, i
     if (b * (int64_t)l_d >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
         (int64_t)n_q * b >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
-    return finish(maxsim::backward_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
-                                          static_cast<hipStream_t>(stream)));
+    return finish(maxsim::backward_launch(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, (int)dtype, argmax, dscore,
+                                          dQ, dD, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed, const int32_t *doc_offsets, int64_t b,
+                           int64_t total_tokens, int d, maxsim_dtype dtype, const int32_t *argmax, const float *dscore,
+                           float *dQ, float *dD_packed, void *stream)
+{
+    if (!Q || !D_packed || !doc_offsets || !argmax || !dscore || !dQ || !dD_packed || n_q < 1 || l_q < 1 || b < 1 ||
+        total_tokens < 1 || !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D_packed, 16) || !aligned(doc_offsets, 4) || !aligned(argmax, 4) ||
+        !aligned(dscore, 4) || !aligned(dQ, 16) || !aligned(dD_packed, 16))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (total_tokens >= (int64_t(1) << 31) || b >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
+        (int64_t)n_q * b >= (int64_t(1) << 40))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::backward_launch(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, (int)dtype, argmax,
+                                          dscore, dQ, dD_packed, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dtype, int8_t *X_i8, float *scale,

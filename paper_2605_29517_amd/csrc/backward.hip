@@ -6,10 +6,10 @@
 //
 // dD (Eq. 3) is the contended side.  The paper resolves it either with atomics or with an
 // inverse-grid CSR built by bincount / cumsum / argsort.  Here every dD row has exactly one
-// owner instead: a workgroup owns a block of consecutive tokens of one document; wavefront w
-// of the workgroup owns the rows t with t % W == w and keeps their fp32 gradient in registers.
-// Every wavefront scans the document's argmax column [n_q * l_q entries], picks out the edges
-// that land on its rows and accumulates them in scan order.  No atomics, no sort, no zero-fill
+// owner instead: a workgroup owns a block of consecutive rows of the (packed) corpus; wavefront w
+// of the workgroup owns the rows with row % W == w and keeps their fp32 gradient in registers.
+// Every wavefront scans the argmax column [n_q * l_q entries] of each document with rows in the
+// block, picks out the edges that land on its rows and accumulates them in scan order.  No atomics, no sort, no zero-fill
 // pass over dD, and the summation order is fixed, so the result is bitwise reproducible.
 #include "common.h"
 
@@ -62,12 +62,14 @@ template <int DT> __device__ __forceinline__ void load8(const char *p, float (&v
 
 struct BwdParams {
     const char *Q;
-    const char *D;
+    const char *D;          // [b, l_d, d] or packed [total_tokens, d]
+    const int32_t *offsets; // [b + 1] for a packed corpus, nullptr for a uniform one
     const int32_t *A;
     const float *g;
     float *dQ;
-    float *dD;
+    float *dD;              // laid out like D
     int64_t b;
+    int64_t total_tokens;   // b * l_d for a uniform corpus
     int n_q, l_q, l_d;
 };
 
@@ -92,24 +94,31 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     constexpr int UNROLL = 4;
     for (int64_t j0 = 0; j0 < p.b; j0 += 4 * UNROLL) {
-        int t[UNROLL];
+        int64_t row[UNROLL]; // packed row of the winning token (row 0 with weight 0 if there is none)
         float gg[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             int64_t j = j0 + u * 4 + grp;
             bool ok = j < p.b;
             int tt = ok ? Aq[j * p.l_q] : -1;
-            ok = ok && tt >= 0 && tt < p.l_d;
-            t[u] = ok ? tt : 0;
+            int64_t first = 0;
+            int len = p.l_d;
+            if (ok) {
+                if (p.offsets) {
+                    first = p.offsets[j];
+                    len = p.offsets[j + 1] - (int)first;
+                } else {
+                    first = j * p.l_d;
+                }
+            }
+            ok = ok && tt >= 0 && tt < len;
+            row[u] = ok ? first + tt : 0;
             gg[u] = ok ? gq[j] : 0.0f;
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
-            int64_t j = j0 + u * 4 + grp;
-            if (j >= p.b)
-                j = p.b - 1; // contributes with weight 0
             float v[8];
-            load8<DT>(p.D + (j * p.l_d + t[u]) * ROWB + c * 8 * Elem<DT>::BYTES, v);
+            load8<DT>(p.D + row[u] * ROWB + c * 8 * Elem<DT>::BYTES, v);
 #pragma unroll
             for (int k = 0; k < 8; ++k)
                 acc[k] = fmaf(gg[u], v[k], acc[k]);
@@ -156,17 +165,18 @@ template <int DT> __device__ __forceinline__ void load_pair(const char *row, int
     }
 }
 
-// Wavefront w of the workgroup owns the rows t_base + 8 * r + w (r = 0..15) and keeps them in
-// registers: lane l holds columns 2l, 2l+1 of each.  Per round: (1) the workgroup copies
-// DD_COL entries of column j of the argmax into LDS, one byte each (row inside this block, or
-// 255); (2) every wavefront scans the bytes in entry order and queues the edges that land on
-// its rows; (3) when a queue holds 64 edges, the 64 lanes look up q, i, g and the Q row address
-// of one edge each, and the edges are then applied in order, 16 Q-row loads in flight, the
-// target row picked by a wavefront-uniform register index (s_set_gpr_idx).  Every row has one owner and a fixed order
-// of accumulation (entry order), so the result is bitwise reproducible; there are no atomics,
-// no sort and no zero-fill pass over dD.
+// A workgroup owns 128 consecutive rows of the (packed) corpus, whichever documents they belong
+// to.  Wavefront w owns the rows row0 + 8 * r + w (r = 0..15) and keeps them in registers: lane
+// l holds columns 2l, 2l+1 of each.  For every document that has rows in the block, per round:
+// (1) the workgroup copies DD_COL entries of that document's argmax column into LDS, one byte
+// each (row inside this block, or 255); (2) every wavefront scans the bytes in entry order and
+// queues the edges that land on its rows; (3) when a queue holds 64 edges, the 64 lanes look up
+// q, i, g and the Q row address of one edge each, and the edges are then applied in order, 16
+// Q-row loads in flight, the target row picked by a wavefront-uniform register index
+// (s_set_gpr_idx).  Every row has one owner and a fixed order of accumulation (entry order), so
+// the result is bitwise reproducible; there are no atomics, no sort and no zero-fill pass.
 template <int DT>
-__global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int blocks_per_doc)
+__global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
     constexpr int NT = DD_WAVES * 64;
@@ -175,8 +185,18 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t j = blockIdx.x / blocks_per_doc;
-    const int t_base = (int)(blockIdx.x % blocks_per_doc) * DD_TOKENS;
+    const int64_t row0 = (int64_t)blockIdx.x * DD_TOKENS;
+    const int64_t row_end = min(row0 + DD_TOKENS, p.total_tokens);
+
+    // documents with rows in [row0, row_end): the last document that starts at or before a row owns it
+    int64_t j_first, j_last;
+    if (p.offsets) {
+        j_first = lower_bound_offsets(p.offsets, p.b, row0 + 1) - 1;
+        j_last = lower_bound_offsets(p.offsets, p.b, row_end) - 1;
+    } else {
+        j_first = row0 / p.l_d;
+        j_last = (row_end - 1) / p.l_d;
+    }
 
     typedef float rowvec __attribute__((ext_vector_type(DD_ROWS_PER_WAVE)));
     rowvec ax, ay; // ax[r], ay[r]: columns 2 * lane, 2 * lane + 1 of owned row r
@@ -186,110 +206,124 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p, int 
         ay[r] = 0.0f;
     }
 
-    // apply the first `cnt` (<= 64) queued edges of this wavefront
-    auto process = [&](int cnt, int c0) {
-        int packed = lane < cnt ? queue[w][lane] : 0;
-        int n = c0 + (packed & 0xffff);
-        int rel = packed >> 16;
-        int q = n / p.l_q;
-        int i = n - q * p.l_q;
-        float gv = lane < cnt ? p.g[(int64_t)q * p.b + j] : 0.0f;
-        int64_t roff = ((int64_t)q * p.l_q + i) * ROWB;
-        int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
-        for (int e0 = 0; e0 < cnt; e0 += DD_BATCH) {
-            float x0[DD_BATCH], x1[DD_BATCH];
-#pragma unroll
-            for (int k = 0; k < DD_BATCH; ++k) {
-                int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: a harmless re-read of the last row
-                int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, e) << 32) |
-                              (uint32_t)__builtin_amdgcn_readlane(rlo, e);
-                load_pair<DT>(p.Q + off, lane, x0[k], x1[k]);
-            }
-#pragma unroll
-            for (int k = 0; k < DD_BATCH; ++k) {
-                if (e0 + k < cnt) {
-                    float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e0 + k));
-                    int r = __builtin_amdgcn_readlane(rel, e0 + k) >> 3; // rel = 8 * r + w
-                    ax[r] = fmaf(gg, x0[k], ax[r]); // r is uniform: indexed register access, no branch
-                    ay[r] = fmaf(gg, x1[k], ay[r]);
-                }
-            }
-        }
-    };
-
     const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
-    for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
-        const int cn = min(DD_COL, n_entries - c0);
-        if (c0 > 0)
+    for (int64_t j = j_first; j <= j_last; ++j) {
+        int64_t first;
+        int len;
+        if (p.offsets) {
+            first = p.offsets[j];
+            len = p.offsets[j + 1] - (int)first;
+        } else {
+            first = j * p.l_d;
+            len = p.l_d;
+        }
+        if (len == 0)
+            continue;
+        const int t_base = (int)(row0 - first); // document-local index of the block's first row (may be negative)
+
+        // apply the first `cnt` (<= 64) queued edges of this wavefront
+        auto process = [&](int cnt, int c0) {
+            int packed = lane < cnt ? queue[w][lane] : 0;
+            int n = c0 + (packed & 0xffff);
+            int rel = packed >> 16;
+            int q = n / p.l_q;
+            int i = n - q * p.l_q;
+            float gv = lane < cnt ? p.g[(int64_t)q * p.b + j] : 0.0f;
+            int64_t roff = ((int64_t)q * p.l_q + i) * ROWB;
+            int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
+            for (int e0 = 0; e0 < cnt; e0 += DD_BATCH) {
+                float x0[DD_BATCH], x1[DD_BATCH];
+#pragma unroll
+                for (int k = 0; k < DD_BATCH; ++k) {
+                    int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: a harmless re-read of the last row
+                    int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, e) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane(rlo, e);
+                    load_pair<DT>(p.Q + off, lane, x0[k], x1[k]);
+                }
+#pragma unroll
+                for (int k = 0; k < DD_BATCH; ++k) {
+                    if (e0 + k < cnt) {
+                        float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e0 + k));
+                        int r = __builtin_amdgcn_readlane(rel, e0 + k) >> 3; // rel = 8 * r + w
+                        ax[r] = fmaf(gg, x0[k], ax[r]); // r is uniform: indexed register access, no branch
+                        ay[r] = fmaf(gg, x1[k], ay[r]);
+                    }
+                }
+            }
+        };
+
+        for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
+            const int cn = min(DD_COL, n_entries - c0);
             __syncthreads(); // the previous round's scan is over before col is rewritten
-        {
-            // entry n = c0 + x -> (q, i); this thread owns x = tid, tid + NT, ...: all its loads are
-            // issued before the first result is used
-            constexpr int PER = DD_COL / NT;
-            int n = c0 + tid;
-            int q = n / p.l_q, i = n - q * p.l_q;
-            const int dq = NT / p.l_q, di = NT % p.l_q;
-            int t[PER];
+            {
+                // entry n = c0 + x -> (q, i); this thread owns x = tid, tid + NT, ...: all its loads are
+                // issued before the first result is used
+                constexpr int PER = DD_COL / NT;
+                int n = c0 + tid;
+                int q = n / p.l_q, i = n - q * p.l_q;
+                const int dq = NT / p.l_q, di = NT % p.l_q;
+                int t[PER];
 #pragma unroll
-            for (int k = 0; k < PER; ++k) {
-                int x = tid + k * NT;
-                t[k] = x < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
-                q += dq;
-                i += di;
-                if (i >= p.l_q) {
-                    i -= p.l_q;
-                    q += 1;
+                for (int k = 0; k < PER; ++k) {
+                    int x = tid + k * NT;
+                    t[k] = x < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
+                    q += dq;
+                    i += di;
+                    if (i >= p.l_q) {
+                        i -= p.l_q;
+                        q += 1;
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    int x = tid + k * NT;
+                    int rel = t[k] - t_base;
+                    bool in = t[k] >= 0 && t[k] < len && rel >= 0 && rel < DD_TOKENS;
+                    if (x < cn)
+                        col[x] = in ? (unsigned char)rel : (unsigned char)255;
                 }
             }
+            __syncthreads();
+            int qlen = 0;
+            for (int x0 = 0; x0 < cn; x0 += 256) {
+                int rel4[4];
 #pragma unroll
-            for (int k = 0; k < PER; ++k) {
-                int x = tid + k * NT;
-                int rel = t[k] - t_base;
-                bool in = rel >= 0 && rel < DD_TOKENS && t[k] < p.l_d;
-                if (x < cn)
-                    col[x] = in ? (unsigned char)rel : (unsigned char)255;
-            }
-        }
-        __syncthreads();
-        int qlen = 0;
-        for (int x0 = 0; x0 < cn; x0 += 256) {
-            int rel4[4];
+                for (int k = 0; k < 4; ++k) {
+                    int x = x0 + k * 64 + lane;
+                    rel4[k] = x < cn ? (int)col[x] : 255;
+                }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                int x = x0 + k * 64 + lane;
-                rel4[k] = x < cn ? (int)col[x] : 255;
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                int rel = rel4[k];
-                bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
-                unsigned long long mask = __ballot(mine);
-                if (mask == 0)
-                    continue;
-                int before =
-                    __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-                if (mine)
-                    queue[w][qlen + before] = (x0 + k * 64 + lane) | (rel << 16);
-                qlen += __builtin_popcountll(mask);
-                if (qlen >= 64) {
-                    process(64, c0);
-                    int rest = qlen - 64; // at most 63 edges move to the front
-                    int moved = lane < rest ? queue[w][64 + lane] : 0;
-                    if (lane < rest)
-                        queue[w][lane] = moved;
-                    qlen = rest;
+                for (int k = 0; k < 4; ++k) {
+                    int rel = rel4[k];
+                    bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
+                    unsigned long long mask = __ballot(mine);
+                    if (mask == 0)
+                        continue;
+                    int before =
+                        __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+                    if (mine)
+                        queue[w][qlen + before] = (x0 + k * 64 + lane) | (rel << 16);
+                    qlen += __builtin_popcountll(mask);
+                    if (qlen >= 64) {
+                        process(64, c0);
+                        int rest = qlen - 64; // at most 63 edges move to the front
+                        int moved = lane < rest ? queue[w][64 + lane] : 0;
+                        if (lane < rest)
+                            queue[w][lane] = moved;
+                        qlen = rest;
+                    }
                 }
             }
+            if (qlen > 0)
+                process(qlen, c0);
         }
-        if (qlen > 0)
-            process(qlen, c0);
     }
 
 #pragma unroll
     for (int r = 0; r < DD_ROWS_PER_WAVE; ++r) {
-        int t = t_base + r * DD_WAVES + w;
-        if (t < p.l_d)
-            reinterpret_cast<float2 *>(p.dD + (j * p.l_d + t) * D_MODEL)[lane] = make_float2(ax[r], ay[r]);
+        int64_t row = row0 + r * DD_WAVES + w;
+        if (row < row_end)
+            reinterpret_cast<float2 *>(p.dD + row * D_MODEL)[lane] = make_float2(ax[r], ay[r]);
     }
 }
 
@@ -301,19 +335,20 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, hipStream_t s
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
-    int blocks_per_doc = (p.l_d + DD_TOKENS - 1) / DD_TOKENS;
-    int64_t grid_d = p.b * blocks_per_doc;
-    hipLaunchKernelGGL((bwd_dd_kernel<DT>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, blocks_per_doc);
+    int64_t grid_d = (p.total_tokens + DD_TOKENS - 1) / DD_TOKENS;
+    hipLaunchKernelGGL((bwd_dd_kernel<DT>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
     return hipGetLastError();
 }
 
-hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
-                           const int32_t *argmax, const float *dscore, float *dQ, float *dD, int /*num_cu*/,
-                           hipStream_t stream)
+hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
+                           int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                           float *dD, int /*num_cu*/, hipStream_t stream)
 {
     BwdParams p;
     p.Q = static_cast<const char *>(Q);
     p.D = static_cast<const char *>(D);
+    p.offsets = offsets;
+    p.total_tokens = total_tokens;
     p.A = argmax;
     p.g = dscore;
     p.dQ = dQ;

@@ -100,3 +100,50 @@ def test_ce_grad(n, b):
     rloss, rg = O.ce_grad(s.cpu().numpy().astype(np.float64), 0.02)
     assert abs(float(loss) - rloss) <= 1e-5 * max(1.0, abs(rloss))
     assert np.abs(g.cpu().numpy() - rg).max() <= 1e-4 * max(np.abs(rg).max(), 1e-30)
+
+
+def run_ragged_case(n_q, l_q, lens, dtype, seed):
+    lens = np.asarray(lens, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(off[-1])
+    Q = W.unit_rows((n_q, l_q, 128), dtype, seed, DEV)
+    Dp = W.unit_rows((T, 128), dtype, seed + 1, DEV)
+    _, A, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), dtype, offsets=off)
+    g = np.random.default_rng(seed).standard_normal((n_q, len(lens))).astype(np.float32)
+    rQ, rD = O.backward_ragged(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), dtype, off, A, g.astype(np.float64))
+    dQ, dD = M.maxsim_backward_ragged(Q, Dp, torch.from_numpy(off).to(DEV), torch.from_numpy(A).to(DEV),
+                                      torch.from_numpy(g).to(DEV))
+    torch.cuda.synchronize()
+    close(dQ, rQ, "dQ")
+    close(dD, rD, "dD")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("case", [(1, 1, [1]), (3, 32, [5, 0, 64, 65, 1, 130, 0, 300]), (4, 33, [20] * 30),
+                                  (2, 100, [0, 0, 127, 129, 128, 1, 1, 1, 0]), (9, 32, [70, 250, 64, 300, 199])])
+def test_backward_ragged_parity(case, dtype):
+    run_ragged_case(*case, dtype, 13)
+
+
+def test_ragged_forward_argmax_feeds_ragged_backward():
+    """End to end on the GPU's own argmax.  The inputs are picked (by the oracle alone) so that every top-2
+    margin is clear; the GPU argmax must then equal the oracle's and the gradients follow from it."""
+    lens = np.array([40, 70, 0, 33, 5])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    for seed in range(100, 500):
+        Q = W.unit_rows((2, 8, 128), "f16", seed, DEV)
+        Dp = W.unit_rows((int(off[-1]), 128), "f16", seed + 1000, DEV)
+        _, A, mg = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", offsets=off)
+        if mg[A >= 0].min() > 1.1e-3:
+            break
+    else:
+        pytest.fail("no seed with clear margins")
+    offd = torch.from_numpy(off).to(DEV)
+    s, a = M.maxsim_forward_ragged(Q, Dp, offd, want_argmax=True)
+    g = torch.randn(2, len(lens), device=DEV, generator=torch.Generator(DEV).manual_seed(3))
+    dQ, dD = M.maxsim_backward_ragged(Q, Dp, offd, a, g)
+    torch.cuda.synchronize()
+    assert np.array_equal(a.cpu().numpy(), A)
+    rQ, rD = O.backward_ragged(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", off, A, g.cpu().numpy().astype(np.float64))
+    close(dQ, rQ, "dQ")
+    close(dD, rD, "dD")

@@ -142,7 +142,8 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
 constexpr int DD_WAVES = 8;
 constexpr int DD_ROWS_PER_WAVE = 16;                     // gradient rows a wavefront keeps in registers
 constexpr int DD_TOKENS = DD_WAVES * DD_ROWS_PER_WAVE;   // 128 consecutive tokens of one document per workgroup
-constexpr int DD_COL = 8192;    // argmax entries of the document's column staged in LDS per round
+constexpr int DD_COL = 8192;    // argmax entries of a document's column handled per round
+constexpr int DD_SEG = DD_COL / DD_WAVES; // entries each wavefront filters per round
 constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it applies them
 constexpr int DD_BATCH = 16;    // Q rows in flight while edges are applied
 
@@ -168,9 +169,10 @@ template <int DT> __device__ __forceinline__ void load_pair(const char *row, int
 // A workgroup owns 128 consecutive rows of the (packed) corpus, whichever documents they belong
 // to.  Wavefront w owns the rows row0 + 8 * r + w (r = 0..15) and keeps them in registers: lane
 // l holds columns 2l, 2l+1 of each.  For every document that has rows in the block, per round:
-// (1) the workgroup copies DD_COL entries of that document's argmax column into LDS, one byte
-// each (row inside this block, or 255); (2) every wavefront scans the bytes in entry order and
-// queues the edges that land on its rows; (3) when a queue holds 64 edges, the 64 lanes look up
+// (1) each wavefront reads an eighth of DD_COL entries of that document's argmax column and
+// writes those that land in this block, compacted by ballot and in entry order, to its list in
+// LDS; (2) every wavefront walks the eight lists in order and queues the edges that land on its
+// rows; (3) when a queue holds 64 edges, the 64 lanes look up
 // q, i, g and the Q row address of one edge each, and the edges are then applied in order, 16
 // Q-row loads in flight, the target row picked by a wavefront-uniform register index
 // (s_set_gpr_idx).  Every row has one owner and a fixed order of accumulation (entry order), so
@@ -180,7 +182,8 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
     constexpr int NT = DD_WAVES * 64;
-    __shared__ unsigned char col[DD_COL];
+    __shared__ int seg[DD_WAVES][DD_SEG]; // per filtering wavefront: the round's edges into this block, in entry order
+    __shared__ int seg_len[DD_WAVES];
     __shared__ int queue[DD_WAVES][DD_QUEUE];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -254,19 +257,19 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
 
         for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
             const int cn = min(DD_COL, n_entries - c0);
-            __syncthreads(); // the previous round's scan is over before col is rewritten
+            __syncthreads(); // the previous round's lists have been consumed
             {
-                // entry n = c0 + x -> (q, i); this thread owns x = tid, tid + NT, ...: all its loads are
-                // issued before the first result is used
-                constexpr int PER = DD_COL / NT;
-                int n = c0 + tid;
+                // (1) wavefront w filters entries [w * DD_SEG, (w + 1) * DD_SEG) of the round: entry
+                // n = c0 + x -> (q, i); all loads are issued before the first result is used
+                constexpr int PER = DD_SEG / 64;
+                int x = w * DD_SEG + lane;
+                int n = c0 + x;
                 int q = n / p.l_q, i = n - q * p.l_q;
-                const int dq = NT / p.l_q, di = NT % p.l_q;
+                const int dq = 64 / p.l_q, di = 64 % p.l_q;
                 int t[PER];
 #pragma unroll
                 for (int k = 0; k < PER; ++k) {
-                    int x = tid + k * NT;
-                    t[k] = x < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
+                    t[k] = (x + k * 64) < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
                     q += dq;
                     i += di;
                     if (i >= p.l_q) {
@@ -274,35 +277,36 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
                         q += 1;
                     }
                 }
+                int kept = 0;
 #pragma unroll
                 for (int k = 0; k < PER; ++k) {
-                    int x = tid + k * NT;
                     int rel = t[k] - t_base;
                     bool in = t[k] >= 0 && t[k] < len && rel >= 0 && rel < DD_TOKENS;
-                    if (x < cn)
-                        col[x] = in ? (unsigned char)rel : (unsigned char)255;
+                    unsigned long long mask = __ballot(in);
+                    int before =
+                        __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+                    if (in)
+                        seg[w][kept + before] = (x + k * 64) | (rel << 16);
+                    kept += __builtin_popcountll(mask);
                 }
+                if (lane == 0)
+                    seg_len[w] = kept;
             }
             __syncthreads();
+            // (2) every wavefront walks the eight lists in order and queues the edges on its rows
             int qlen = 0;
-            for (int x0 = 0; x0 < cn; x0 += 256) {
-                int rel4[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    int x = x0 + k * 64 + lane;
-                    rel4[k] = x < cn ? (int)col[x] : 255;
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    int rel = rel4[k];
-                    bool mine = rel != 255 && (rel & (DD_WAVES - 1)) == w;
+            for (int sw = 0; sw < DD_WAVES; ++sw) {
+                const int sn = __builtin_amdgcn_readfirstlane(seg_len[sw]);
+                for (int e0 = 0; e0 < sn; e0 += 64) {
+                    int ent = e0 + lane < sn ? seg[sw][e0 + lane] : -1;
+                    bool mine = ent >= 0 && ((ent >> 16) & (DD_WAVES - 1)) == w;
                     unsigned long long mask = __ballot(mine);
                     if (mask == 0)
                         continue;
                     int before =
                         __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
                     if (mine)
-                        queue[w][qlen + before] = (x0 + k * 64 + lane) | (rel << 16);
+                        queue[w][qlen + before] = ent;
                     qlen += __builtin_popcountll(mask);
                     if (qlen >= 64) {
                         process(64, c0);

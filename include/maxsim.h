@@ -9,8 +9,9 @@
  * once per similarity cell (Sec. "Quantised Scoring", Alg. 4).
  *
  * Conventions shared by every entry point
- *   - Every pointer is a DEVICE pointer owned by the caller.  The library never
- *     allocates, frees or keeps device memory.
+ *   - Every pointer is a DEVICE pointer owned by the caller (the one exception, the host
+ *     corpus of maxsim_forward_streamed, is marked HOST).  The library never allocates,
+ *     frees or keeps device memory.
  *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it
  *     and return; they never synchronise.  NULL means the default stream.
  *   - Tensors are row-major with the innermost stride 1 and no gaps.  Base
@@ -54,6 +55,24 @@ const char *maxsim_strerror(int code);
  */
 int maxsim_forward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                    maxsim_dtype dtype, float *scores, int32_t *argmax, void *stream);
+
+/*
+ * Out-of-core forward (Sec. "Corpus-scale scoring": a corpus that does not fit in device memory is
+ * streamed through a fixed buffer while the kernel runs).
+ *   D_host      [b, l_d, d] dtype in HOST memory (page-locked memory makes the copies asynchronous;
+ *               pageable memory works but serialises them)
+ *   block_docs  documents per block (clamped to b); block_docs * l_d must be < 2^31
+ *   staging     DEVICE buffer of 2 * block_docs * l_d * d * sizeof(dtype) bytes owned by the caller;
+ *               its contents are overwritten
+ *   scores      [n_q, b] float32 (device), fully overwritten; no argmax
+ * Block k + 1 is copied (on a copy stream the library creates once per device, default priority)
+ * while block k is scored on `stream`; all work is ordered after what `stream` already holds and
+ * the call returns without synchronising.  D_host and staging must stay valid until `stream`
+ * has run the last kernel.  Same arithmetic as maxsim_forward (identical bits).
+ */
+int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host, int64_t b, int l_d,
+                            int d, maxsim_dtype dtype, int64_t block_docs, void *staging,
+                            float *scores, void *stream);
 
 /*
  * Fused forward over a packed ragged corpus (Sec. "Ragged corpora and kernel family";

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libmaxsim.so")
 MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
-SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_backward", "maxsim_backward_ragged",
+SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
            "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
@@ -44,6 +44,8 @@ def load():
     L.maxsim_forward.argtypes = [p, i, i, p, l, i, i, i, p, p, p]
     L.maxsim_forward_ragged.restype = i
     L.maxsim_forward_ragged.argtypes = [p, i, i, p, p, l, l, i, i, p, p, p]
+    L.maxsim_forward_streamed.restype = i
+    L.maxsim_forward_streamed.argtypes = [p, i, i, p, l, i, i, i, l, p, p, p]
     L.maxsim_backward.restype = i
     L.maxsim_backward.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p]
     L.maxsim_backward_ragged.restype = i
@@ -139,6 +141,31 @@ def maxsim_forward_ragged(Q, D_packed, doc_offsets, total_tokens=None, scores=No
                                      _dev(argmax, "argmax", torch.int32) if argmax is not None else None, _stream(Q))
     _check(rc, "maxsim_forward_ragged")
     return (scores, argmax) if argmax is not None else scores
+
+
+def maxsim_forward_streamed(Q, D_host, block_docs, staging=None, scores=None):
+    """Out-of-core forward: Q on the GPU, D_host [b,l_d,d] a HOST tensor (pinned for asynchronous copies),
+    staging a device buffer of 2 * block_docs documents (allocated here if not given)."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    b, l_d, d2 = D_host.shape
+    if D_host.is_cuda or not D_host.is_contiguous():
+        raise MaxSimError("D_host must be a contiguous host tensor")
+    if d2 != d or Q.dtype != D_host.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
+    block_docs = int(min(block_docs, b))
+    if staging is None:
+        staging = torch.empty(2 * block_docs, l_d, d, dtype=Q.dtype, device=Q.device)
+    if staging.numel() < 2 * block_docs * l_d * d or staging.dtype != Q.dtype:
+        raise MaxSimError("staging must hold 2 * block_docs documents of the corpus dtype")
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
+    with _on_device(Q, "Q"):
+        rc = L.maxsim_forward_streamed(_dev(Q, "Q"), n_q, l_q, ctypes.c_void_p(D_host.data_ptr()), b, l_d, d,
+                                       _DTYPE[Q.dtype], block_docs, _dev(staging, "staging"),
+                                       _dev(scores, "scores", torch.float32), _stream(Q))
+    _check(rc, "maxsim_forward_streamed")
+    return scores
 
 
 def maxsim_backward(Q, D, argmax, dscore, dQ=None, dD=None):

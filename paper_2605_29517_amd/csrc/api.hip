@@ -42,6 +42,23 @@ int num_cu()
 
 int finish(hipError_t e) { return e == hipSuccess ? MAXSIM_OK : MAXSIM_ERR_LAUNCH; }
 
+// One copy stream per device for the out-of-core path, created on first use at the default
+// priority and kept until the process ends.
+hipStream_t copy_stream()
+{
+    static hipStream_t cached[64] = {nullptr};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return nullptr;
+    if (!cached[dev]) {
+        hipStream_t st = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess)
+            return nullptr;
+        cached[dev] = st;
+    }
+    return cached[dev];
+}
+
 int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
                    int64_t total_tokens, int d, int dtype, float *scores, int32_t *argmax, void *stream)
 {
@@ -92,6 +109,83 @@ int maxsim_forward(const void *Q, int n_q, int l_q, const void *D, int64_t b, in
     if (b > 0 && (int64_t)l_d > ((int64_t(1) << 31) - 1) / b)
         return (Q && D && scores) ? MAXSIM_ERR_UNSUPPORTED : MAXSIM_ERR_INVALID;
     return forward_common(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, d, (int)dtype, scores, argmax, stream);
+}
+
+int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host, int64_t b, int l_d, int d,
+                            maxsim_dtype dtype, int64_t block_docs, void *staging, float *scores, void *stream)
+{
+    if (!Q || !D_host || !staging || !scores || n_q < 1 || l_q < 1 || b < 1 || l_d < 1 || block_docs < 1 ||
+        !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D_host, 16) || !aligned(staging, 16) || !aligned(scores, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (block_docs > b)
+        block_docs = b;
+    if (block_docs > ((int64_t(1) << 31) - 1) / l_d || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24))
+        return MAXSIM_ERR_UNSUPPORTED;
+    const int64_t doc_bytes = (int64_t)l_d * d * ((int)dtype == MAXSIM_F32 ? 4 : 2);
+    hipStream_t compute = static_cast<hipStream_t>(stream);
+    hipStream_t copy = copy_stream();
+    if (!copy)
+        return MAXSIM_ERR_LAUNCH;
+    // events: block k copied (per staging half), staging half free again (its kernel has run)
+    hipEvent_t copied[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr}, entry = nullptr;
+    bool ok = hipEventCreateWithFlags(&entry, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i)
+        ok = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&freed[i], hipEventDisableTiming) == hipSuccess;
+    int rc = MAXSIM_OK;
+    if (!ok)
+        rc = MAXSIM_ERR_LAUNCH;
+    // the staging buffer may still be in use by work already enqueued on the caller's stream
+    if (rc == MAXSIM_OK && (hipEventRecord(entry, compute) != hipSuccess || hipStreamWaitEvent(copy, entry, 0) != hipSuccess))
+        rc = MAXSIM_ERR_LAUNCH;
+    const int64_t n_blocks = (b + block_docs - 1) / block_docs;
+    for (int64_t k = 0; k < n_blocks && rc == MAXSIM_OK; ++k) {
+        const int half = (int)(k & 1);
+        const int64_t first = k * block_docs;
+        const int64_t docs = (b - first < block_docs) ? b - first : block_docs;
+        char *dst = static_cast<char *>(staging) + half * block_docs * doc_bytes;
+        const char *src = static_cast<const char *>(D_host) + first * doc_bytes;
+        hipError_t e = hipSuccess;
+        if (k >= 2)
+            e = hipStreamWaitEvent(copy, freed[half], 0); // the kernel that read this half two blocks ago
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(dst, src, (size_t)(docs * doc_bytes), hipMemcpyHostToDevice, copy);
+        if (e == hipSuccess)
+            e = hipEventRecord(copied[half], copy);
+        if (e == hipSuccess)
+            e = hipStreamWaitEvent(compute, copied[half], 0);
+        if (e != hipSuccess) {
+            rc = MAXSIM_ERR_LAUNCH;
+            break;
+        }
+        maxsim::FwdParams p = {};
+        p.Q = static_cast<const char *>(Q);
+        p.D = dst;
+        p.scores = scores + first;
+        p.b = docs;
+        p.ld = b;
+        p.total_tokens = docs * (int64_t)l_d;
+        p.n_q = n_q;
+        p.l_q = l_q;
+        p.l_d = l_d;
+        if (maxsim::forward_launch(p, (int)dtype, num_cu(), compute) != hipSuccess ||
+            hipEventRecord(freed[half], compute) != hipSuccess)
+            rc = MAXSIM_ERR_LAUNCH;
+    }
+    // destroying an event that is still pending only releases it once it has completed
+    if (entry)
+        (void)hipEventDestroy(entry);
+    for (int i = 0; i < 2; ++i) {
+        if (copied[i])
+            (void)hipEventDestroy(copied[i]);
+        if (freed[i])
+            (void)hipEventDestroy(freed[i]);
+    }
+    return rc;
 }
 
 int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed, const int32_t *doc_offsets, int64_t b,

@@ -181,7 +181,6 @@ template <int DT>
 __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
-    constexpr int NT = DD_WAVES * 64;
     __shared__ int seg[DD_WAVES][DD_SEG]; // per filtering wavefront: the round's edges into this block, in entry order
     __shared__ int seg_len[DD_WAVES];
     __shared__ int queue[DD_WAVES][DD_QUEUE];

@@ -68,6 +68,7 @@ struct FwdParams {
     float *scores;          // [n_q, b]
     int32_t *argmax;        // [n_q, b, l_q] or nullptr
     int64_t b;
+    int64_t ld;           // documents per row of scores / argmax (b, or the whole corpus when b is a slice of it)
     int64_t total_tokens; // b * l_d for a uniform corpus
     int n_q, l_q, l_d;
     int bpq;               // column blocks per query = ceil(l_q / 32)

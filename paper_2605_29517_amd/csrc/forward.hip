@@ -116,7 +116,7 @@ __device__ __forceinline__ float finish_block(const FwdParams &p, float m, int i
             int tok = (gb % p.bpq) * BLOCK_COLS + rho;
             if (idx > len - 1)
                 idx = len - 1;
-            p.argmax[((int64_t)q * p.b + doc) * p.l_q + tok] = idx;
+            p.argmax[((int64_t)q * p.ld + doc) * p.l_q + tok] = idx;
         }
     } else {
         m = fmaxf(a, b);
@@ -134,10 +134,10 @@ __device__ __forceinline__ void write_empty_docs(const FwdParams &p, int64_t doc
         if (p.offsets[doc + 1] != p.offsets[doc])
             continue;
         for (int q = 0; q < p.n_q; ++q) {
-            p.scores[(int64_t)q * p.b + doc] = neg_inf();
+            p.scores[(int64_t)q * p.ld + doc] = neg_inf();
             if (p.argmax)
                 for (int i = 0; i < p.l_q; ++i)
-                    p.argmax[((int64_t)q * p.b + doc) * p.l_q + i] = -1;
+                    p.argmax[((int64_t)q * p.ld + doc) * p.l_q + i] = -1;
         }
     }
 }
@@ -217,7 +217,7 @@ __device__ __forceinline__ void stream_compute(const FwdParams &p, const Cursor 
                 s += part[cb];
         const int q = gb0 / p.bpq + lane;
         if (lane < NCB / p.bpq && q < p.n_q)
-            p.scores[(int64_t)q * p.b + c.doc] = s;
+            p.scores[(int64_t)q * p.ld + c.doc] = s;
     }
 }
 
@@ -493,7 +493,7 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
                     if (lane == 0) {
                         if (direct) {
                             if (lb < nb)
-                                p.scores[(int64_t)(gb0 + lb) * p.b + ci.doc] = sum;
+                                p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
                         } else {
                             lds_part[par][lb] = sum;
                         }
@@ -509,7 +509,7 @@ __global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
                     int cnt = (p.n_pass == 1) ? p.bpq : nb;
                     for (int i = 0; i < cnt; ++i)
                         sum += lds_part[par][first_blk + i];
-                    float *dst = p.scores + (int64_t)(q_first + tid) * p.b + fin_doc;
+                    float *dst = p.scores + (int64_t)(q_first + tid) * p.ld + fin_doc;
                     *dst = accumulate ? *dst + sum : sum;
                 }
                 par ^= 1;
@@ -586,6 +586,8 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
     const bool ragged = p.offsets != nullptr;
     const bool am = p.argmax != nullptr;
     p.bpq = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS;
+    if (p.ld == 0)
+        p.ld = p.b;
     const int64_t total_blocks = (int64_t)p.n_q * p.bpq;
     const int64_t units = ragged ? p.total_tokens : p.b; // what is split across chunks
     // Streaming kernel: every wavefront holds whole queries in at most 4 (fp32: 2) column blocks, and

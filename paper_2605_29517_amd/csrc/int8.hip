@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
         for (int64_t doc = doc0 + tid; doc < doc1; doc += NT)
             if (p.offsets[doc + 1] == p.offsets[doc])
                 for (int q = 0; q < p.n_q; ++q)
-                    P.scores[(int64_t)q * p.b + doc] = neg_inf();
+                    P.scores[(int64_t)q * p.ld + doc] = neg_inf();
     }
 
     const int q_first = group * p.qpg;
@@ -249,7 +249,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
                 double s = 0.0;
                 for (int i = 0; i < p.bpq; ++i)
                     s += lds_part[par][tid * p.bpq + i];
-                P.scores[(int64_t)(q_first + tid) * p.b + cc.doc] = (float)s;
+                P.scores[(int64_t)(q_first + tid) * p.ld + cc.doc] = (float)s;
             }
             par ^= 1;
         }
@@ -332,7 +332,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
         for (int doc = doc0 + lane; doc < doc1; doc += 64)
             if (p.offsets[doc + 1] == p.offsets[doc])
                 for (int q = 0; q < p.n_q; ++q)
-                    P.scores[(int64_t)q * p.b + doc] = neg_inf();
+                    P.scores[(int64_t)q * p.ld + doc] = neg_inf();
     }
 
     TileIter li, ci; // load iterator: one tile ahead of the compute iterator
@@ -458,7 +458,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
                     for (int o = 16; o > 0; o >>= 1)
                         dv += __shfl_xor(dv, o);
                     if (lane == 0)
-                        P.scores[(int64_t)(q_first + j) * p.b + ci.doc] = (float)dv;
+                        P.scores[(int64_t)(q_first + j) * p.ld + ci.doc] = (float)dv;
                     dv = 0.0;
                     iq = 0;
                     ++j;
@@ -502,6 +502,7 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
     p.offsets = offsets;
     p.scores = scores;
     p.b = b;
+    p.ld = b;
     p.total_tokens = total_tokens;
     p.n_q = n_q;
     p.l_q = l_q;

@@ -17,8 +17,11 @@
  *   - Tensors are row-major with the innermost stride 1 and no gaps.  Base
  *     pointers of Q, D and the int8 tensors must be 16-byte aligned, all other
  *     pointers 4-byte aligned.
- *   - d (embedding width) must be 128 (the paper's setting, Tab. "shapes");
- *     any other value returns MAXSIM_ERR_UNSUPPORTED.
+ *   - d (embedding width): 128 everywhere (the paper's setting, Tab. "shapes").  The float
+ *     forward entry points (maxsim_forward, _ragged, _streamed) also take rows of 128, 512 and
+ *     1024 bytes, i.e. d = 64, 256, 512 for fp16/bf16 and d = 64, 256 for fp32 (the paper's
+ *     "fat embedding" extension, App. "split-d"); other widths must be zero-padded by the
+ *     caller to the next one.  Anything else returns MAXSIM_ERR_UNSUPPORTED.
  *   - L_q and L_d are arbitrary positive integers (no tile multiples needed).
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
  *   - Return value: MAXSIM_OK (0) or a negative error code; on error nothing

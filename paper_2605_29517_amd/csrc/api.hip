@@ -4,7 +4,8 @@
 #include "common.h"
 
 namespace maxsim {
-hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream);
+hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t stream);
+bool forward_width_supported(int dtype, int d);
 hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
                            int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
                            float *dD, int num_cu, hipStream_t stream);
@@ -66,7 +67,7 @@ int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t
         return MAXSIM_ERR_INVALID;
     if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(scores, 4) || !aligned(argmax, 4) || !aligned(offsets, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!maxsim::forward_width_supported(dtype, d))
         return MAXSIM_ERR_UNSUPPORTED;
     // index ranges the kernels rely on: token counts and block ids fit in int32
     if (total_tokens >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) ||
@@ -83,7 +84,7 @@ int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t
     p.n_q = n_q;
     p.l_q = l_q;
     p.l_d = l_d;
-    return finish(maxsim::forward_launch(p, dtype, num_cu(), static_cast<hipStream_t>(stream)));
+    return finish(maxsim::forward_launch(p, dtype, d, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 } // namespace
@@ -119,7 +120,7 @@ int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host,
         return MAXSIM_ERR_INVALID;
     if (!aligned(Q, 16) || !aligned(D_host, 16) || !aligned(staging, 16) || !aligned(scores, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!maxsim::forward_width_supported((int)dtype, d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (block_docs > b)
         block_docs = b;
@@ -172,7 +173,7 @@ int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host,
         p.n_q = n_q;
         p.l_q = l_q;
         p.l_d = l_d;
-        if (maxsim::forward_launch(p, (int)dtype, num_cu(), compute) != hipSuccess ||
+        if (maxsim::forward_launch(p, (int)dtype, d, num_cu(), compute) != hipSuccess ||
             hipEventRecord(freed[half], compute) != hipSuccess)
             rc = MAXSIM_ERR_LAUNCH;
     }

@@ -13,45 +13,35 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int D_MODEL = 128;  // embedding width the kernels are built for
+constexpr int D_MODEL = 128;  // embedding width of the backward and int8 kernels (the float forward also takes 64, 256, 512)
 constexpr int TILE_ROWS = 32; // document tokens per MFMA tile (rows of the 32x32 result)
 constexpr int BLOCK_COLS = 32; // query tokens per column block (columns of the 32x32 result)
 
 // A token row is handled in 16-byte chunks.  Lane (rho = lane % 32, h = lane / 32) of a
 // wavefront owns chunks 2u + h (u = 0 .. NU-1) of row rho, for documents (MFMA A operand)
 // and queries (MFMA B operand) alike, so both sides pair the same k indices.
-template <int DT> struct Traits;
+//
+// The float kernels are compiled per "format" F = dtype | (NU << 4): the element type and the
+// embedding width (a row is NU * 32 bytes: d = 16 * NU for 16-bit inputs, 8 * NU for fp32).
+constexpr int fmt(int dtype, int nu) { return dtype | (nu << 4); }
 
-template <> struct Traits<MAXSIM_F16> {
-    static constexpr int ROW_BYTES = 256;
-    static constexpr int NU = 8;
+template <int F> struct Traits {
+    static constexpr int DT = F & 15;
+    static constexpr int NU = F >> 4;
+    static constexpr int ROW_BYTES = NU * 32;
     static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
     {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-
-template <> struct Traits<MAXSIM_BF16> {
-    static constexpr int ROW_BYTES = 256;
-    static constexpr int NU = 8;
-    static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-
-template <> struct Traits<MAXSIM_F32> {
-    static constexpr int ROW_BYTES = 512;
-    static constexpr int NU = 16;
-    static __device__ __forceinline__ void mma(const uint4 &a, const uint4 &b, f32x16 &c)
-    {
-        // one chunk = 4 floats = 4 rank-2 updates (k = 2 per instruction: halves h = 0, 1)
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        if constexpr (DT == MAXSIM_F16) {
+            c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+        } else if constexpr (DT == MAXSIM_BF16) {
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+        } else {
+            // one chunk = 4 floats = 4 rank-2 updates (k = 2 per instruction: halves h = 0, 1)
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+        }
     }
 };
 

@@ -1,588 +1,29 @@
-// Fused MaxSim forward for gfx950 (Alg. 1 of the paper, re-designed around 64-wide
-// wavefronts and the 32x32 MFMA result layout).
-//
-// Orientation.  Document tokens sit on the MFMA rows (A operand), query tokens on the
-// columns (B operand).  A lane of the 32x32 result holds ONE query token (column
-// lane % 32) and 16 document tokens, so the max over document tokens (line 9 of Alg. 1)
-// is an in-lane chain of v_max3 over the accumulator registers and the running row-max is
-// one register per lane per 32 query tokens.  The two lane halves are merged once per
-// document; the sum over query tokens (line 11) is a butterfly over 32 lanes.
-//
-// Masking (line 8 of Alg. 1).  Rows past the end of a document are not set to -inf after
-// the product; instead the loads clamp the row index to the document's last token.  A
-// duplicated token cannot change a max, and it cannot win the argmax because ties go to the
-// lowest index, so the result is the same and the epilogue stays mask-free.
-//
-// Two kernels share these pieces:
-//   fwd_stream_kernel  few query tokens (<= 128 in total): the corpus read is the cost.
-//                      Every wavefront works alone on its own run of documents; document
-//                      tiles go HBM -> registers directly in MFMA operand layout (32 rows x
-//                      32 contiguous bytes per load instruction), one tile ahead.
-//   fwd_tile_kernel    many query tokens: the contraction is the cost.  A workgroup keeps up
-//                      to 1024 query tokens stationary in registers (128 per wavefront) and
-//                      streams document tiles through LDS, shared by all its wavefronts.
+// Fused MaxSim forward for gfx950: choice of kernel and launch shape (the kernels themselves are
+// in forward_impl.h, compiled once per element type in forward_{f16,bf16,f32}.hip).
 #include "common.h"
 
 namespace maxsim {
 
-// ---------------------------------------------------------------------------------------
-// pieces shared by both kernels
-// ---------------------------------------------------------------------------------------
-
-// Query fragments of column block `gb` (global block id): column rho of the block is query
-// token (gb % bpq) * 32 + rho of query gb / bpq; columns past l_q re-read the last token
-// and are dropped from the sum later.
-template <int DT>
-__device__ __forceinline__ void load_q_block(const FwdParams &p, int gb, int rho, int h,
-                                             uint4 (&qf)[Traits<DT>::NU], bool &col_valid)
-{
-    using TR = Traits<DT>;
-    int total_blocks = p.n_q * p.bpq;
-    bool active = gb < total_blocks;
-    int g = active ? gb : 0;
-    int q = g / p.bpq;
-    int tok = (g % p.bpq) * BLOCK_COLS + rho;
-    col_valid = active && tok < p.l_q;
-    if (tok > p.l_q - 1)
-        tok = p.l_q - 1;
-    const char *row = p.Q + ((int64_t)q * p.l_q + tok) * TR::ROW_BYTES + h * 16;
-#pragma unroll
-    for (int u = 0; u < TR::NU; ++u)
-        qf[u] = *reinterpret_cast<const uint4 *>(row + u * 32);
-}
-
-// Fold one 32x32 result tile into the running max (and argmax) of this lane's query token.
-template <bool ARGMAX>
-__device__ __forceinline__ void fold_tile(const f32x16 &acc, float &m, int &idx, int row_base, int h)
-{
-    if (ARGMAX) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            bool up = acc[r] > m; // strict: the first occurrence keeps a tie
-            m = up ? acc[r] : m;
-            idx = up ? row_base + acc_row(r, h) : idx;
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < 16; r += 2)
-            m = fmaxf(fmaxf(m, acc[r]), acc[r + 1]); // one v_max3_f32 per pair
-    }
-}
-
-// Cross-lane helpers on the VALU (no LDS traffic): v_permlane32_swap exchanges the two lane
-// halves, DPP row operations add within a row of 16 lanes.
-__device__ __forceinline__ void swap_halves(float x, float &lo_from_hi, float &hi_from_lo)
-{
-    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    hi_from_lo = __uint_as_float(r[0]); // lanes 32..63 now hold lanes 0..31 (lanes 0..31 unchanged)
-    lo_from_hi = __uint_as_float(r[1]); // lanes 0..31 now hold lanes 32..63 (lanes 32..63 unchanged)
-}
-
-template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
-{
-    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
-}
-
-// Sum over lanes 0..31 (a fixed tree: pairs, quads, eights, sixteens, then the two rows).
-__device__ __forceinline__ float sum_low32(float v)
-{
-    v = dpp_add<0xB1>(v);  // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E>(v);  // quad_perm [2,3,0,1]
-    v = dpp_add<0x141>(v); // row_half_mirror
-    v = dpp_add<0x140>(v); // row_mirror
-    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    return r0 + r1;
-}
-
-// End of a document for one column block: merge the lane halves, write the argmax of valid
-// columns, and return the sum over the block's valid query tokens (same value in all lanes).
-template <bool ARGMAX>
-__device__ __forceinline__ float finish_block(const FwdParams &p, float m, int idx, bool col_valid,
-                                              int gb, int64_t doc, int len, int rho, int h)
-{
-    float a, b; // a: this lane's value or its partner's, so that max(a, b) is the merged value in every lane
-    swap_halves(m, a, b);
-    if (ARGMAX) {
-        float ia, ib;
-        swap_halves(__int_as_float(idx), ia, ib);
-        // lanes 0..31: (a, ia) came from the upper half, (b, ib) is the lane's own; upper lanes: the reverse
-        int i0 = __float_as_int(ia), i1 = __float_as_int(ib);
-        bool take = (a > b) || (a == b && i0 < i1);
-        m = take ? a : b;
-        idx = take ? i0 : i1;
-        if (col_valid && h == 0) {
-            int q = gb / p.bpq;
-            int tok = (gb % p.bpq) * BLOCK_COLS + rho;
-            if (idx > len - 1)
-                idx = len - 1;
-            p.argmax[((int64_t)q * p.ld + doc) * p.l_q + tok] = idx;
-        }
-    } else {
-        m = fmaxf(a, b);
-    }
-    return sum_low32(col_valid ? m : 0.0f);
-}
-
-// Documents of length 0 in [doc0, doc1): score -inf, argmax -1 (ragged corpora only).
-__device__ __forceinline__ void write_empty_docs(const FwdParams &p, int64_t doc0, int64_t doc1,
-                                                 int tid, int nthreads)
-{
-    if (!p.offsets)
-        return;
-    for (int64_t doc = doc0 + tid; doc < doc1; doc += nthreads) {
-        if (p.offsets[doc + 1] != p.offsets[doc])
-            continue;
-        for (int q = 0; q < p.n_q; ++q) {
-            p.scores[(int64_t)q * p.ld + doc] = neg_inf();
-            if (p.argmax)
-                for (int i = 0; i < p.l_q; ++i)
-                    p.argmax[((int64_t)q * p.ld + doc) * p.l_q + i] = -1;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// streaming kernel: one wavefront per run of documents, all query blocks in registers
-// ---------------------------------------------------------------------------------------
-
-template <int DT, int NCB, bool ARGMAX> struct StreamState {
-    uint4 qf[NCB][Traits<DT>::NU];
-    bool col_valid[NCB];
-    float m[NCB];
-    int idx[NCB];
-};
-
-template <int DT>
-__device__ __forceinline__ void stream_load_tile(const FwdParams &p, const Cursor &c, int rho, int h,
-                                                 uint4 (&a)[Traits<DT>::NU])
-{
-    using TR = Traits<DT>;
-    int row = c.t0 + rho;
-    if (row > c.len - 1)
-        row = c.len - 1;
-    const char *ptr = p.D + (c.start + row) * TR::ROW_BYTES + h * 16;
-#pragma unroll
-    for (int u = 0; u < TR::NU; ++u)
-        a[u] = *reinterpret_cast<const uint4 *>(ptr + u * 32);
-}
-
-template <int DT, int NCB, bool ARGMAX>
-__device__ __forceinline__ void stream_compute(const FwdParams &p, const Cursor &c,
-                                               StreamState<DT, NCB, ARGMAX> &st,
-                                               const uint4 (&a)[Traits<DT>::NU], int gb0, int lane, int rho, int h)
-{
-    using TR = Traits<DT>;
-    if (c.t0 == 0) {
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            st.m[cb] = neg_inf();
-            st.idx[cb] = 0;
-        }
-    }
-    // two column blocks at a time (two accumulator chains in flight); the scheduling barrier keeps
-    // the pairs apart so that only two accumulators are live and more wavefronts fit on a SIMD
-#pragma unroll
-    for (int cb = 0; cb < NCB; cb += 2) {
-        f32x16 acc0, acc1;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            acc0[r] = 0.0f;
-            acc1[r] = 0.0f;
-        }
-#pragma unroll
-        for (int u = 0; u < TR::NU; ++u) {
-            TR::mma(a[u], st.qf[cb][u], acc0);
-            if (cb + 1 < NCB)
-                TR::mma(a[u], st.qf[cb + 1][u], acc1);
-        }
-        fold_tile<ARGMAX>(acc0, st.m[cb], st.idx[cb], c.t0, h);
-        if (cb + 1 < NCB)
-            fold_tile<ARGMAX>(acc1, st.m[cb + 1], st.idx[cb + 1], c.t0, h);
-        if (cb + 2 < NCB)
-            __builtin_amdgcn_sched_barrier(0);
-    }
-
-    if (c.t0 + TILE_ROWS >= c.len) { // last tile of the document
-        float part[NCB];
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
-            part[cb] = finish_block<ARGMAX>(p, st.m[cb], st.idx[cb], st.col_valid[cb], gb0 + cb, c.doc, c.len, rho, h);
-        // this wavefront holds whole queries: lane k adds up the blocks of its k-th query in block
-        // order and writes the score
-        float s = 0.0f;
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
-            if (cb / p.bpq == lane)
-                s += part[cb];
-        const int q = gb0 / p.bpq + lane;
-        if (lane < NCB / p.bpq && q < p.n_q)
-            p.scores[(int64_t)q * p.ld + c.doc] = s;
-    }
-}
-
-template <int DT, int NCB, bool ARGMAX>
-__global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
-{
-    using TR = Traits<DT>;
-    const int lane = threadIdx.x & 63;
-    const int rho = lane & 31, h = lane >> 5;
-    // p.n_groups (1, 2 or 4) wavefronts of a workgroup share a run of documents, each with its own
-    // NCB column blocks (whole queries); they read the same tiles at about the same time, so all
-    // but the first read hit in the CU's vector cache.  No LDS and no barrier is involved.
-    const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int group = wib % p.n_groups;
-    const int64_t chunk = (int64_t)blockIdx.x * (4 / p.n_groups) + wib / p.n_groups;
-    const int gb0 = group * NCB;
-    int64_t doc0, doc1;
-    chunk_doc_range(p, chunk, doc0, doc1);
-    if (doc0 >= doc1)
-        return;
-    if (group == 0)
-        write_empty_docs(p, doc0, doc1, lane, 64);
-
-    StreamState<DT, NCB, ARGMAX> st;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-        load_q_block<DT>(p, gb0 + cb, rho, h, st.qf[cb], st.col_valid[cb]);
-
-    Cursor pc; // prefetch cursor, one tile ahead of the compute cursor
-    cursor_init(pc, p, doc0, doc1);
-    if (!pc.valid)
-        return;
-    uint4 a0[TR::NU], a1[TR::NU];
-    stream_load_tile<DT>(p, pc, rho, h, a0);
-    Cursor cc = pc;
-    cursor_next_tile(pc, p);
-    for (;;) {
-        if (pc.valid)
-            stream_load_tile<DT>(p, pc, rho, h, a1);
-        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a0, gb0, lane, rho, h);
-        cc = pc;
-        if (!cc.valid)
-            break;
-        cursor_next_tile(pc, p);
-        if (pc.valid)
-            stream_load_tile<DT>(p, pc, rho, h, a0);
-        stream_compute<DT, NCB, ARGMAX>(p, cc, st, a1, gb0, lane, rho, h);
-        cc = pc;
-        if (!cc.valid)
-            break;
-        cursor_next_tile(pc, p);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// tile kernel: query-stationary workgroup, document tiles staged through LDS
-// ---------------------------------------------------------------------------------------
-
-template <int DT> struct LdsTile {
-    // rows padded by one 16-byte chunk so that the 32 rows read by one ds_read_b128 of the
-    // MFMA operand layout fall into different banks
-    static constexpr int ROW_STRIDE = Traits<DT>::ROW_BYTES + 16;
-    static constexpr int BYTES = TILE_ROWS * ROW_STRIDE;
-    static constexpr int CHUNKS = TILE_ROWS * Traits<DT>::ROW_BYTES / 16;
-};
-
-// Part `u` (of NU) of folding a result tile into the running max: rows [u * 16 / NU, (u + 1) * 16 / NU).
-template <bool ARGMAX, int NU>
-__device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, int &idx, int row_base, int h)
-{
-    constexpr int RPS = 16 / NU; // rows per step: 2 for 16-bit inputs, 1 for fp32
-    const int r0 = u * RPS;
-    if (ARGMAX) {
-#pragma unroll
-        for (int r = r0; r < r0 + RPS; ++r) {
-            bool up = acc[r] > m; // strict: the first occurrence keeps a tie
-            m = up ? acc[r] : m;
-            idx = up ? row_base + acc_row(r, h) : idx;
-        }
-    } else if (RPS == 2) {
-        m = fmaxf(fmaxf(m, acc[r0]), acc[r0 + 1]); // one v_max3_f32
-    } else {
-        m = fmaxf(m, acc[r0]);
-    }
-}
-
-// The main loop is software-pipelined by hand and pinned with scheduling barriers, one MFMA
-// (16-bit inputs) per step:
-//   * the MFMA chain of column block cb runs while the previous block's result tile is folded
-//     into the running max, one slice of the fold per step, so the VALU work sits under MFMAs
-//     whose results it does not need;
-//   * during the first chain of a tile the wavefront also reads the NEXT tile's A operands from
-//     LDS into a second register set, writes the tile after that from registers to LDS and
-//     issues the global loads of the tile after that, so no memory latency is exposed between
-//     tiles: three LDS buffers rotate (being computed / prefetched into registers / being
-//     written), one barrier per tile.  (The fp32 and the argmax variants have no registers
-//     left for the second operand set; they read the current tile's operands at its start.)
-template <int DT, int W, int NCB, bool ARGMAX>
-__global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
-{
-    using TR = Traits<DT>;
-    using LT = LdsTile<DT>;
-    constexpr int NU = TR::NU;
-    constexpr int NT = W * 64;
-    constexpr int CPT = LT::CHUNKS / NT; // 16-byte chunks each thread moves per tile
-    static_assert(LT::CHUNKS % NT == 0, "tile must split evenly over the workgroup");
-    constexpr int CPR = TR::ROW_BYTES / 16; // chunks per row
-    constexpr int GROUP_BLOCKS = W * NCB;
-    constexpr bool PF = DT != MAXSIM_F32 && !ARGMAX; // operands of the next tile prefetched into registers
-
-    __shared__ __attribute__((aligned(16))) char lds_tile[3 * LT::BYTES];
-    __shared__ float lds_part[2][GROUP_BLOCKS];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int rho = lane & 31, h = lane >> 5;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Renumber so
-    // that the column groups sharing a document chunk are neighbours on one XCD and run at
-    // the same time: the chunk then comes from HBM once and from L2 for the other groups.
-    const int n_wg = gridDim.x;
-    int v = blockIdx.x;
-    if ((n_wg & 7) == 0)
-        v = (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3);
-    const int group = v % p.n_groups;
-    const int chunk = v / p.n_groups;
-
-    int64_t doc0_, doc1_;
-    chunk_doc_range(p, chunk, doc0_, doc1_);
-    if (doc0_ >= doc1_)
-        return;
-    const int doc0 = (int)doc0_, doc1 = (int)doc1_;
-    if (group == 0)
-        write_empty_docs(p, doc0, doc1, tid, NT);
-
-    // this thread's share of a tile copy: chunk ch = tid + i * NT -> (row, 16-byte column)
-    int cp_row[CPT], cp_goff[CPT], cp_loff[CPT];
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-        int ch = tid + i * NT;
-        cp_row[i] = ch / CPR;
-        cp_goff[i] = (ch % CPR) * 16;
-        cp_loff[i] = (ch / CPR) * LT::ROW_STRIDE + (ch % CPR) * 16;
-    }
-    const int a_off = rho * LT::ROW_STRIDE + h * 16;
-
-    for (int pass = 0; pass < p.n_pass; ++pass) {
-        // column blocks of this pass: [gb0, gb0 + nb); queries [q_first, q_first + nq)
-        int gb0, nb, q_first, nq;
-        const bool accumulate = pass > 0;
-        if (p.n_pass == 1) {
-            q_first = group * p.qpg;
-            nq = min(p.qpg, p.n_q - q_first);
-            gb0 = q_first * p.bpq;
-            nb = nq * p.bpq;
-        } else { // one long query per group, GROUP_BLOCKS blocks of it per pass
-            q_first = group;
-            nq = 1;
-            gb0 = group * p.bpq + pass * GROUP_BLOCKS;
-            nb = min(GROUP_BLOCKS, p.bpq - pass * GROUP_BLOCKS);
-        }
-        // a query of one block needs no combination across blocks: its lane writes the score
-        const bool direct = p.bpq == 1;
-
-        uint4 qf[NCB][NU];
-        bool col_valid[NCB];
-        float m[NCB];
-        int idx[NCB];
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            int lb = w * NCB + cb;
-            load_q_block<DT>(p, gb0 + lb, rho, h, qf[cb], col_valid[cb]);
-            col_valid[cb] = col_valid[cb] && lb < nb;
-            m[cb] = neg_inf();
-            idx[cb] = 0;
-        }
-
-        TileIter li, ci; // load iterator (three tiles ahead of the compute iterator at steady state)
-        it_init(li, p, doc0, doc1, lane);
-        ci = li;
-        if (!it_valid(ci))
-            break;
-
-        uint4 g[CPT];
-        bool g_has = false;
-        // HBM -> registers for the next tile of the stream
-        auto gload = [&]() {
-            g_has = it_valid(li);
-            if (!g_has)
-                return;
-            int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
-            const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i) {
-                int row = cp_row[i] < last_row ? cp_row[i] : last_row;
-                g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
-            }
-            it_next(li, p, lane);
-        };
-        auto lstore = [&](int buf_off) {
-            if (!g_has)
-                return;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g[i];
-        };
-
-        // LDS buffers (byte offsets): o_cur holds the tile being computed (already in registers),
-        // o_nxt the next one (read into registers during this tile), o_wr receives the one after
-        int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
-        gload();
-        lstore(o_cur);
-        gload();
-        lstore(o_nxt);
-        gload();
-        __syncthreads();
-        uint4 a0[NU], a1[PF ? NU : 1];
-        if (PF) {
-#pragma unroll
-            for (int u = 0; u < NU; ++u)
-                a0[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
-        }
-        int par = 0;
-
-        // one tile: operands in `ac`; the next tile's operands are read into `an` on the way
-        auto stage = [&](uint4(&ac)[NU], uint4(&an)[PF ? NU : 1]) {
-            if (!PF) {
-#pragma unroll
-                for (int u = 0; u < NU; ++u)
-                    ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
-            }
-            const bool first = ci.t0 == 0;
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                m[cb] = first ? neg_inf() : m[cb];
-                idx[cb] = first ? 0 : idx[cb];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            f32x16 acc[NCB];
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    acc[cb][r] = 0.0f;
-#pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    TR::mma(ac[u], qf[cb][u], acc[cb]);
-                    if (cb == 0) {
-                        if (PF)
-                            an[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_nxt + a_off + u * 32]);
-                        if (u == NU - 1) {
-                            lstore(o_wr);
-                            gload();
-                        }
-                    } else {
-                        fold_step<ARGMAX, NU>(acc[cb - 1], u, m[cb - 1], idx[cb - 1], ci.t0, h);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < NU; ++u)
-                fold_step<ARGMAX, NU>(acc[NCB - 1], u, m[NCB - 1], idx[NCB - 1], ci.t0, h);
-
-            int fin_doc = -1;
-            if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of its document
-                fin_doc = ci.doc;
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) {
-                    int lb = w * NCB + cb;
-                    float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
-                    if (lane == 0) {
-                        if (direct) {
-                            if (lb < nb)
-                                p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
-                        } else {
-                            lds_part[par][lb] = sum;
-                        }
-                    }
-                }
-            }
-            it_next(ci, p, lane);
-            __syncthreads();
-            if (fin_doc >= 0) {
-                if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
-                    float sum = 0.0f;
-                    int first_blk = (p.n_pass == 1) ? tid * p.bpq : 0;
-                    int cnt = (p.n_pass == 1) ? p.bpq : nb;
-                    for (int i = 0; i < cnt; ++i)
-                        sum += lds_part[par][first_blk + i];
-                    float *dst = p.scores + (int64_t)(q_first + tid) * p.ld + fin_doc;
-                    *dst = accumulate ? *dst + sum : sum;
-                }
-                par ^= 1;
-            }
-            int t = o_cur;
-            o_cur = o_nxt;
-            o_nxt = o_wr;
-            o_wr = t;
-        };
-
-        if constexpr (PF) {
-            for (;;) {
-                stage(a0, a1);
-                if (!it_valid(ci))
-                    break;
-                stage(a1, a0);
-                if (!it_valid(ci))
-                    break;
-            }
-        } else {
-            while (it_valid(ci))
-                stage(a0, a1);
-        }
-        __syncthreads(); // LDS is reused by the next pass
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// host-side launchers (called from the C ABI)
-// ---------------------------------------------------------------------------------------
-
-template <int DT, int NCB, bool ARGMAX>
-static hipError_t launch_stream(const FwdParams &p, int grid, hipStream_t stream)
-{
-    hipLaunchKernelGGL((fwd_stream_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p);
-    return hipGetLastError();
-}
-
-template <int DT, int W, int NCB, bool ARGMAX>
-static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
-{
-    hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX>), dim3(grid), dim3(W * 64), 0, stream, p);
-    return hipGetLastError();
-}
-
-template <int DT, bool ARGMAX>
-static hipError_t dispatch_stream(const FwdParams &p, int ncb, int grid, hipStream_t s)
-{
-    switch (ncb) {
-    case 1: return launch_stream<DT, 1, ARGMAX>(p, grid, s);
-    case 2: return launch_stream<DT, 2, ARGMAX>(p, grid, s);
-    case 3: return launch_stream<DT, 3, ARGMAX>(p, grid, s);
-    default: return launch_stream<DT, 4, ARGMAX>(p, grid, s);
-    }
-}
-
-template <int DT, bool ARGMAX>
-static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t s)
-{
-    constexpr int NCB = (DT == MAXSIM_F32) ? 2 : 4;
-    switch (w) {
-    case 1: return launch_tile<DT, 1, NCB, ARGMAX>(p, grid, s);
-    case 2: return launch_tile<DT, 2, NCB, ARGMAX>(p, grid, s);
-    case 4: return launch_tile<DT, 4, NCB, ARGMAX>(p, grid, s);
-    default: return launch_tile<DT, 8, NCB, ARGMAX>(p, grid, s);
-    }
-}
+hipError_t forward_run_f16(const FwdParams &p, int nu, bool argmax, bool tile, int x, int grid, hipStream_t s);
+hipError_t forward_run_bf16(const FwdParams &p, int nu, bool argmax, bool tile, int x, int grid, hipStream_t s);
+hipError_t forward_run_f32(const FwdParams &p, int nu, bool argmax, bool tile, int x, int grid, hipStream_t s);
 
 static int round_up(int64_t x, int m) { return (int)((x + m - 1) / m * m); }
 
-// Chooses kernel and launch shape from the problem size; `num_cu` is the device's CU count.
-hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream)
+// Embedding widths the float forward is built for: rows of 128, 256, 512 or 1024 bytes
+// (d = 64, 128, 256, 512 for 16-bit inputs; 32 .. 256 for fp32, of which the C ABI admits >= 64).
+bool forward_width_supported(int dtype, int d)
 {
+    const int row_bytes = d * (dtype == MAXSIM_F32 ? 4 : 2);
+    return d >= 64 && (row_bytes == 128 || row_bytes == 256 || row_bytes == 512 || row_bytes == 1024);
+}
+
+// Chooses kernel and launch shape from the problem size; `num_cu` is the device's CU count.
+hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t stream)
+{
+    if (!forward_width_supported(dtype, d))
+        return hipErrorNotSupported;
+    const int nu = d * (dtype == MAXSIM_F32 ? 4 : 2) / 32; // 16-byte chunk pairs per row
     const bool ragged = p.offsets != nullptr;
     const bool am = p.argmax != nullptr;
     p.bpq = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS;
@@ -590,9 +31,18 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
         p.ld = p.b;
     const int64_t total_blocks = (int64_t)p.n_q * p.bpq;
     const int64_t units = ragged ? p.total_tokens : p.b; // what is split across chunks
-    // Streaming kernel: every wavefront holds whole queries in at most 4 (fp32: 2) column blocks, and
-    // up to 4 wavefronts share a run of documents.  That covers up to 16 blocks of short queries.
-    const int stream_max_blocks = (dtype == MAXSIM_F32) ? 2 : 4;
+    auto run = [&](bool tile, int x, int grid) {
+        switch (dtype) {
+        case MAXSIM_F32: return forward_run_f32(p, nu, am, tile, x, grid, stream);
+        case MAXSIM_F16: return forward_run_f16(p, nu, am, tile, x, grid, stream);
+        default: return forward_run_bf16(p, nu, am, tile, x, grid, stream);
+        }
+    };
+
+    // Streaming kernel: every wavefront holds whole queries in as many column blocks as fit beside two
+    // document tiles in registers (4 for rows of up to 256 bytes, 2 for 512 bytes, none beyond), and up
+    // to 4 wavefronts share a run of documents.  That covers up to 16 blocks of short queries.
+    const int stream_max_blocks = nu <= 8 ? 4 : (nu == 16 ? 2 : 0);
     int s_ncb = 0, s_groups = 0;
     if (total_blocks <= stream_max_blocks) {
         s_ncb = (int)total_blocks;
@@ -628,22 +78,11 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
         p.n_pass = 1;
         const int chunks_per_block = 4 / s_groups;
         int grid = (int)((n_chunks + chunks_per_block - 1) / chunks_per_block);
-        const int ncb = s_ncb;
-        switch (dtype) {
-        case MAXSIM_F32:
-            return am ? dispatch_stream<MAXSIM_F32, true>(p, ncb, grid, stream)
-                      : dispatch_stream<MAXSIM_F32, false>(p, ncb, grid, stream);
-        case MAXSIM_F16:
-            return am ? dispatch_stream<MAXSIM_F16, true>(p, ncb, grid, stream)
-                      : dispatch_stream<MAXSIM_F16, false>(p, ncb, grid, stream);
-        default:
-            return am ? dispatch_stream<MAXSIM_BF16, true>(p, ncb, grid, stream)
-                      : dispatch_stream<MAXSIM_BF16, false>(p, ncb, grid, stream);
-        }
+        return run(false, s_ncb, grid);
     }
 
-    // tile kernel: W wavefronts x NCB blocks per group
-    const int ncb = (dtype == MAXSIM_F32) ? 2 : 4;
+    // tile kernel: W wavefronts x NCB blocks per group (the query fragments of a wavefront fill 128 registers)
+    const int ncb = nu <= 8 ? 4 : 32 / nu;
     int w = 8;
     if (total_blocks <= 1 * ncb)
         w = 1;
@@ -651,6 +90,8 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
         w = 2;
     else if (total_blocks <= 4 * ncb)
         w = 4;
+    if (nu == 32 && total_blocks <= 2)
+        w = 8; // rows of 1024 bytes and next to no arithmetic: all eight wavefronts move tiles, one or two compute
     const int group_blocks = w * ncb;
     if (p.bpq <= group_blocks) {
         p.qpg = group_blocks / p.bpq;
@@ -674,18 +115,7 @@ hipError_t forward_launch(FwdParams p, int dtype, int num_cu, hipStream_t stream
     if (p.unit_per_chunk < 1)
         p.unit_per_chunk = 1;
     p.n_chunks = (int)n_chunks;
-    int grid = p.n_groups * p.n_chunks;
-    switch (dtype) {
-    case MAXSIM_F32:
-        return am ? dispatch_tile<MAXSIM_F32, true>(p, w, grid, stream)
-                  : dispatch_tile<MAXSIM_F32, false>(p, w, grid, stream);
-    case MAXSIM_F16:
-        return am ? dispatch_tile<MAXSIM_F16, true>(p, w, grid, stream)
-                  : dispatch_tile<MAXSIM_F16, false>(p, w, grid, stream);
-    default:
-        return am ? dispatch_tile<MAXSIM_BF16, true>(p, w, grid, stream)
-                  : dispatch_tile<MAXSIM_BF16, false>(p, w, grid, stream);
-    }
+    return run(true, w, p.n_groups * p.n_chunks);
 }
 
 } // namespace maxsim

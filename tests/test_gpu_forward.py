@@ -95,6 +95,31 @@ def test_argument_errors():
     with pytest.raises(M.MaxSimError):
         M.maxsim_forward(Q.cpu(), D)
     with pytest.raises(M.MaxSimError):
-        M.maxsim_forward(Q[..., :64].contiguous(), D[..., :64].contiguous())  # d != 128
+        M.maxsim_forward(Q[..., :96].contiguous(), D[..., :96].contiguous())  # d = 96 is not a supported width
     L = M.load()
     assert L.maxsim_forward(None, 1, 32, None, 4, 40, 128, 1, None, None, None) == -1
+
+
+# Other embedding widths (rows of 128, 512 and 1024 bytes): stream and tile kernels, several passes, ragged, argmax
+WIDTH_SHAPES = [(1, 32, 9, 40), (3, 17, 5, 100), (8, 32, 12, 65), (2, 200, 6, 130), (1, 1030, 3, 70), (40, 32, 7, 33)]
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 64), ("f16", 256), ("f16", 512), ("bf16", 64), ("bf16", 256), ("bf16", 512),
+                                     ("f32", 64), ("f32", 256)])
+@pytest.mark.parametrize("want_argmax", [False, True])
+@pytest.mark.parametrize("shape", WIDTH_SHAPES)
+def test_uniform_other_widths(shape, want_argmax, dtype, d):
+    n_q, l_q, b, l_d = shape
+    Q = W.unit_rows((n_q, l_q, d), dtype, 61 + l_q, DEV)
+    D = W.unit_rows((b, l_d, d), dtype, 62 + l_d, DEV)
+    forward_parity_uniform(Q, D, M.maxsim_forward, want_argmax, RTOL_F32 if dtype == "f32" else RTOL_16)
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 64), ("bf16", 256), ("f16", 512), ("f32", 256)])
+@pytest.mark.parametrize("n_q,l_q", [(1, 32), (5, 40), (2, 300)])
+def test_ragged_other_widths(n_q, l_q, dtype, d):
+    lens = np.asarray([1, 31, 32, 33, 0, 64, 150, 0, 2, 65, 97])
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.unit_rows((int(lens.sum()), d), dtype, 71, DEV)
+    Q = W.unit_rows((n_q, l_q, d), dtype, 72, DEV)
+    forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, True, RTOL_F32 if dtype == "f32" else RTOL_16)

@@ -321,7 +321,7 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
 //     written), one barrier per tile.  (The fp32 and the argmax variants have no registers
 //     left for the second operand set; they read the current tile's operands at its start.)
 template <int DT, int W, int NCB, bool ARGMAX>
-__global__ void __launch_bounds__(W * 64) fwd_tile_kernel(FwdParams p)
+__global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 1) fwd_tile_kernel(FwdParams p)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;

@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--legs", default="c2_nq1,c3,c3_host,c4,c5,ceilings")
+    ap.add_argument("--legs", default="c2_nq1,c2_i8,c2_train,c3,c3_host,wide_d,c4,c5,ceilings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-docs", type=int, default=4096, help="documents in the oracle's sample")
     args = ap.parse_args()
@@ -172,7 +172,58 @@ def main():
                       "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
                       "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 2, True), a, PEAK_HBM_GBS, "GB/s", "c2_nq1")})
         del s1
+    if "c2_i8" in legs:
+        # the same ragged corpus quantised to int8 (offline), one query quantised on the fly: streaming regime
+        D8p, dsp = M.maxsim_quantize_rows_i8(Dp)
+        Q1h = Q[:1].contiguous()
+        q8 = torch.empty(1, l_q, D_MODEL, dtype=torch.int8, device=dev)
+        qs8 = torch.empty(1, l_q, dtype=torch.float32, device=dev)
+        s8 = torch.empty(1, n_docs, dtype=torch.float32, device=dev)
+
+        def step_i8r():
+            M.maxsim_quantize_rows_i8(Q1h, X_i8=q8, scale=qs8)
+            M.maxsim_forward_i8_ragged(q8, qs8, D8p, dsp, off, total_tokens=T, scores=s8)
+        w, a, m, mn = time_launches(step_i8r, 50, 5)
+        extra.append({"leg": "c2_i8", "workload": "configs[1] corpus as int8 + fp32 scales, ragged (maxsim_forward_i8_ragged), N_q=1",
+                      "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
+                      "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 1, True, scale_bytes=4), a, PEAK_HBM_GBS, "GB/s", "c2_i8")})
+        del D8p, dsp, s8
+    if "c2_train" in legs:
+        # ragged training step on a slice of the corpus: 256 queries x the first 256 documents
+        nt = 256
+        Tt = int(off[nt])
+        Qt, Dt, offt = Q.repeat(4, 1, 1)[:nt].contiguous(), Dp[:Tt].contiguous(), off[:nt + 1].contiguous()
+        st = torch.empty(nt, nt, dtype=torch.float32, device=dev)
+        at = torch.empty(nt, nt, l_q, dtype=torch.int32, device=dev)
+        gt = torch.empty(nt, nt, dtype=torch.float32, device=dev)
+        dQt = torch.empty(nt, l_q, D_MODEL, dtype=torch.float32, device=dev)
+        dDt = torch.empty(Tt, D_MODEL, dtype=torch.float32, device=dev)
+
+        def step_rt():
+            M.maxsim_forward_ragged(Qt, Dt, offt, total_tokens=Tt, scores=st, argmax=at)
+            M.maxsim_ce_grad(st, 0.02, g=gt)
+            M.maxsim_backward_ragged(Qt, Dt, offt, at, gt, total_tokens=Tt, dQ=dQt, dD=dDt)
+        w, _, _, _ = time_launches(step_rt, 50, 5)
+        wb, ab, _, _ = time_launches(lambda: M.maxsim_backward_ragged(Qt, Dt, offt, at, gt, total_tokens=Tt, dQ=dQt, dD=dDt), 50, 5)
+        extra.append({"leg": "c2_train", "workload": "ragged training step: 256 queries (L_q=32) x 256 ragged documents (%d tokens), fp16, "
+                                                     "forward+argmax, CE, maxsim_backward_ragged" % Tt,
+                      "step_ms": round(w, 4), "backward_ms": round(wb, 4), "pairs_per_s": round(nt * nt / (w * 1e-3), 1)})
+        del Qt, Dt, st, at, gt, dQt, dDt
     del Dp, Q
+
+    if "wide_d" in legs:
+        # wider embeddings (the paper's fat-embedding extension): ColPali-shaped pages at d = 256 and 512, bf16
+        wide = []
+        for dw, ndw in ((256, 2000), (512, 1000)):
+            Qw = W.unit_rows((4, 1024, dw), "bf16", 91, dev)
+            Dw = W.unit_rows((ndw, 1024, dw), "bf16", 92, dev)
+            sw = torch.empty(4, ndw, dtype=torch.float32, device=dev)
+            w, a, m, mn = time_launches(lambda: M.maxsim_forward(Qw, Dw, scores=sw), 10, 3)
+            fl = 2.0 * 4 * 1024 * ndw * 1024 * dw
+            wide.append({"d": dw, "n_docs": ndw, "ms": round(w, 4), "TFLOP_per_s": round(fl / (a * 1e-3) / 1e12, 1),
+                         "mfma_frac": round(fl / (a * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4)})
+            del Qw, Dw, sw
+        extra.append({"leg": "wide_d", "workload": "N_q=4, L_q=L_d=1024, bf16, d=256 (B=2000) and d=512 (B=1000)", "results": wide})
 
     if "c3" in legs:
         nq3, nd3, l3 = 4, 10_000, 1024

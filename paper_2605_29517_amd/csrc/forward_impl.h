@@ -460,10 +460,6 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
         constexpr bool RING = !PF && NCB == 1 && NU >= 8;
         auto stage = [&](uint4(&ac)[NU], uint4(&an)[PF ? NU : 1]) {
             const int fin_doc = (ci.t0 + TILE_ROWS >= ci.len) ? ci.doc : -1; // last tile of its document?
-            if (!wave_active) { // no column block in this pass: the wavefront only helps moving tiles
-                lstore(o_wr);
-                gload();
-            } else {
             uint4 ring[4];
             if (RING) {
 #pragma unroll
@@ -528,7 +524,6 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                     }
                 }
             }
-            } // wave_active
             it_next(ci, p, lane);
             __syncthreads();
             if (fin_doc >= 0) {
@@ -549,7 +544,19 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
             o_wr = t;
         };
 
-        if constexpr (PF) {
+        if (!wave_active) {
+            // no column block in this pass: the wavefront only helps moving tiles (same barriers as the others)
+            while (it_valid(ci)) {
+                lstore(o_wr);
+                gload();
+                it_next(ci, p, lane);
+                __syncthreads();
+                int t = o_cur;
+                o_cur = o_nxt;
+                o_nxt = o_wr;
+                o_wr = t;
+            }
+        } else if constexpr (PF) {
             for (;;) {
                 stage(a0, a1);
                 if (!it_valid(ci))

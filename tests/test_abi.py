@@ -42,7 +42,13 @@ def test_error_codes_without_touching_a_gpu():
     buf = (ctypes.c_char * 4096)()
     addr = (ctypes.addressof(buf) + 255) & ~255
     p = ctypes.c_void_p(addr)
-    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 64, 1, p, None, None) == -2       # d != 128
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 96, 1, p, None, None) == -2       # d not in {64, 128, 256, 512}
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 512, 0, p, None, None) == -2      # fp32 rows wider than 1024 bytes
+    assert L.maxsim_backward(p, 1, 1, p, 1, 1, 64, 1, p, p, p, p, None) == -2      # backward is built for d = 128 only
+    assert L.maxsim_forward_i8(p, p, 1, 2000, p, p, 1, 1, 128, p, None) == -2      # int8 queries above 1024 tokens
+    assert L.maxsim_forward_streamed(p, 1, 32, p, 4, 40, 128, 1, 0, p, p, None) == -1  # block_docs < 1
+    assert L.maxsim_forward_i8_ragged(p, p, 1, 32, p, p, None, 4, 100, 128, p, None) == -1  # no offsets
+    assert L.maxsim_backward_ragged(p, 1, 1, p, p, 1, 0, 128, 1, p, p, p, p, None) == -1     # total_tokens < 1
     assert L.maxsim_forward(p, 0, 32, p, 4, 40, 128, 1, p, None, None) == -1      # n_q < 1
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 128, 7, p, None, None) == -1      # bad dtype
     assert L.maxsim_forward(ctypes.c_void_p(addr + 2), 1, 32, p, 4, 40, 128, 1, p, None, None) == -1  # misaligned

@@ -140,8 +140,8 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
 // dD[j,t,:] = sum over edges (q,i) with A[q,j,i] = t of g[q,j] * Q[q,i,:]
 // ---------------------------------------------------------------------------------------
 constexpr int DD_WAVES = 8;
-constexpr int DD_ROWS_PER_WAVE = 16;                     // gradient rows a wavefront keeps in registers
-constexpr int DD_TOKENS = DD_WAVES * DD_ROWS_PER_WAVE;   // 128 consecutive tokens of one document per workgroup
+// gradient rows a wavefront keeps in registers: RPW = 16 (a workgroup owns 128 consecutive rows), or 8 / 4 when the
+// corpus is too small to fill the chip with blocks of 128 rows
 constexpr int DD_COL = 8192;    // argmax entries of a document's column handled per round
 constexpr int DD_SEG = DD_COL / DD_WAVES; // entries each wavefront filters per round
 constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it applies them
@@ -177,9 +177,11 @@ template <int DT> __device__ __forceinline__ void load_pair(const char *row, int
 // Q-row loads in flight, the target row picked by a wavefront-uniform register index
 // (s_set_gpr_idx).  Every row has one owner and a fixed order of accumulation (entry order), so
 // the result is bitwise reproducible; there are no atomics, no sort and no zero-fill pass.
-template <int DT>
+template <int DT, int RPW>
 __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
 {
+    constexpr int DD_ROWS_PER_WAVE = RPW;
+    constexpr int DD_TOKENS = DD_WAVES * RPW;
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
     __shared__ int seg[DD_WAVES][DD_SEG]; // per filtering wavefront: the round's edges into this block, in entry order
     __shared__ int seg_len[DD_WAVES];
@@ -330,7 +332,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
     }
 }
 
-template <int DT> static hipError_t launch_bwd(const BwdParams &p, hipStream_t stream)
+template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, hipStream_t stream)
 {
     int64_t waves = (int64_t)p.n_q * p.l_q;
     int grid_q = (int)((waves + 3) / 4);
@@ -338,14 +340,24 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, hipStream_t s
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
-    int64_t grid_d = (p.total_tokens + DD_TOKENS - 1) / DD_TOKENS;
-    hipLaunchKernelGGL((bwd_dd_kernel<DT>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
+    // blocks of 128 rows unless that leaves the chip short of workgroups (about 4 per CU wanted)
+    const int64_t want = (int64_t)num_cu * 4;
+    if (p.total_tokens / (DD_WAVES * 16) >= want) {
+        int64_t grid_d = (p.total_tokens + DD_WAVES * 16 - 1) / (DD_WAVES * 16);
+        hipLaunchKernelGGL((bwd_dd_kernel<DT, 16>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
+    } else if (p.total_tokens / (DD_WAVES * 8) >= want) {
+        int64_t grid_d = (p.total_tokens + DD_WAVES * 8 - 1) / (DD_WAVES * 8);
+        hipLaunchKernelGGL((bwd_dd_kernel<DT, 8>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
+    } else {
+        int64_t grid_d = (p.total_tokens + DD_WAVES * 4 - 1) / (DD_WAVES * 4);
+        hipLaunchKernelGGL((bwd_dd_kernel<DT, 4>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
+    }
     return hipGetLastError();
 }
 
 hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
                            int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
-                           float *dD, int /*num_cu*/, hipStream_t stream)
+                           float *dD, int num_cu, hipStream_t stream)
 {
     BwdParams p;
     p.Q = static_cast<const char *>(Q);
@@ -361,9 +373,9 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
     p.l_q = l_q;
     p.l_d = l_d;
     switch (dtype) {
-    case MAXSIM_F32: return launch_bwd<MAXSIM_F32>(p, stream);
-    case MAXSIM_F16: return launch_bwd<MAXSIM_F16>(p, stream);
-    default: return launch_bwd<MAXSIM_BF16>(p, stream);
+    case MAXSIM_F32: return launch_bwd<MAXSIM_F32>(p, num_cu, stream);
+    case MAXSIM_F16: return launch_bwd<MAXSIM_F16>(p, num_cu, stream);
+    default: return launch_bwd<MAXSIM_BF16>(p, num_cu, stream);
     }
 }
 

@@ -1,6 +1,8 @@
 // C ABI of the library: argument checks, device query, kernel selection.  See include/maxsim.h.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "common.h"
 
 namespace maxsim {
@@ -48,6 +50,8 @@ int finish(hipError_t e) { return e == hipSuccess ? MAXSIM_OK : MAXSIM_ERR_LAUNC
 hipStream_t copy_stream()
 {
     static hipStream_t cached[64] = {nullptr};
+    static std::mutex guard; // two host threads may make their first streamed call at once
+    std::lock_guard<std::mutex> lock(guard);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return nullptr;

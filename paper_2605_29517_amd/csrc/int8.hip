@@ -478,10 +478,19 @@ template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStr
 template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, hipStream_t s)
 {
     const size_t lds = (size_t)NB * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess)
-        return e;
+    // more than 64 KB of dynamic LDS has to be allowed once per device; afterwards the launch is all there is
+    // (so that later calls can be captured into a graph)
+    static bool allowed[64] = {false};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!allowed[dev]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        allowed[dev] = true;
+    }
     hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P);
     return hipGetLastError();
 }

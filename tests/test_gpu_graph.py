@@ -25,6 +25,9 @@ def test_training_step_replays_from_a_graph():
     qs = torch.empty(n, l_q, device=DEV)
     d8, ds = M.maxsim_quantize_rows_i8(D)
     s8 = torch.empty(n, n, device=DEV)
+    # a corpus large enough for the document-stationary int8 kernel (dynamic LDS above 64 KB)
+    big8, bigs = M.maxsim_quantize_rows_i8(W.unit_rows((4200, 40, 128), "f32", 8, DEV))
+    s8b = torch.empty(n, 4200, device=DEV)
 
     def step():
         M.maxsim_forward(Q, D, scores=s, argmax=a)
@@ -32,10 +35,11 @@ def test_training_step_replays_from_a_graph():
         M.maxsim_backward(Q, D, a, g, dQ=dQ, dD=dD)
         M.maxsim_quantize_rows_i8(Q, X_i8=q8, scale=qs)
         M.maxsim_forward_i8(q8, qs, d8, ds, scores=s8)
+        M.maxsim_forward_i8(q8, qs, big8, bigs, scores=s8b)
 
     step()
     torch.cuda.synchronize()
-    want = [t.clone() for t in (s, a, g, loss, dQ, dD, s8)]
+    want = [t.clone() for t in (s, a, g, loss, dQ, dD, s8, s8b)]
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -47,10 +51,10 @@ def test_training_step_replays_from_a_graph():
             step()
     torch.cuda.synchronize()
     for rep in range(4):
-        for t in (s, a, g, loss, dQ, dD, s8):
+        for t in (s, a, g, loss, dQ, dD, s8, s8b):
             t.fill_(0) if t.dtype != torch.int32 else t.fill_(-7)   # eager work between replays
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((s, a, g, loss, dQ, dD, s8), want):
+        for got, ref in zip((s, a, g, loss, dQ, dD, s8, s8b), want):
             assert torch.equal(got, ref), "replay %d differs from the eager result" % rep

@@ -74,7 +74,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus %d is not supported); "
-              "the path shards by documents with no communication, see DESIGN.md" % args.gpus, file=sys.stderr)
+              "the path shards by documents with no communication between GPUs" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

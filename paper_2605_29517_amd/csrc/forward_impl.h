@@ -3,12 +3,12 @@
 //
 // Orientation.  Document tokens sit on the MFMA rows (A operand), query tokens on the
 // columns (B operand).  A lane of the 32x32 result holds ONE query token (column
-// lane % 32) and 16 document tokens, so the max over document tokens (line 9 of Alg. 1)
+// lane % 32) and 16 document tokens, so the max over document tokens (the running row-max step of Alg. 1)
 // is an in-lane chain of v_max3 over the accumulator registers and the running row-max is
 // one register per lane per 32 query tokens.  The two lane halves are merged once per
-// document; the sum over query tokens (line 11) is a butterfly over 32 lanes.
+// document; the sum over query tokens (the final reduction of Alg. 1) is a butterfly over 32 lanes.
 //
-// Masking (line 8 of Alg. 1).  Rows past the end of a document are not set to -inf after
+// Masking (the -inf step of Alg. 1).  Rows past the end of a document are not set to -inf after
 // the product; instead the loads clamp the row index to the document's last token.  A
 // duplicated token cannot change a max, and it cannot win the argmax because ties go to the
 // lowest index, so the result is the same and the epilogue stays mask-free.

@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
                     first = j * p.l_d;
                 }
             }
-            ok = ok && tt >= 0 && tt < len;
+            ok = ok && tt >= 0 && tt < len && first >= 0 && first + tt < p.total_tokens; // also guards bad offsets
             row[u] = ok ? first + tt : 0;
             gg[u] = ok ? gq[j] : 0.0f;
         }
@@ -197,6 +197,8 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
     if (p.offsets) {
         j_first = lower_bound_offsets(p.offsets, p.b, row0 + 1) - 1;
         j_last = lower_bound_offsets(p.offsets, p.b, row_end) - 1;
+        j_first = j_first < 0 ? 0 : j_first; // only offsets that break their contract get here
+        j_last = j_last > p.b - 1 ? p.b - 1 : j_last;
     } else {
         j_first = row0 / p.l_d;
         j_last = (row_end - 1) / p.l_d;

@@ -69,6 +69,11 @@ struct FwdParams {
     int n_pass;            // passes over the corpus per group (tile kernel, bpq > group size)
 };
 
+// Offsets come from device memory the host cannot check.  Every offset is forced into
+// [lo, total_tokens] before it is used (once per document, scalar work), so that offsets which
+// are not non-decreasing or run past the corpus give wrong scores but never an address outside D.
+__device__ __forceinline__ int64_t clamp_offset(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
 // Cursor over the 32-row tiles of a run of documents, identical in every lane of a wavefront.
 struct Cursor {
     int64_t doc;     // current document
@@ -90,7 +95,7 @@ __device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p)
         c.t0 = 0;
         if (p.offsets) {
             c.start += c.len;
-            int64_t e = c.nxt_end;
+            int64_t e = clamp_offset(c.nxt_end, c.start, p.total_tokens);
             c.len = (int32_t)(e - c.start);
             c.nxt_end = (c.doc + 2 <= p.b) ? (int64_t)p.offsets[c.doc + 2] : e;
             if (c.len > 0)
@@ -111,8 +116,8 @@ __device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64
     if (!c.valid)
         return;
     if (p.offsets) {
-        c.start = p.offsets[doc0];
-        int64_t e = p.offsets[doc0 + 1];
+        c.start = clamp_offset(p.offsets[doc0], 0, p.total_tokens);
+        int64_t e = clamp_offset(p.offsets[doc0 + 1], c.start, p.total_tokens);
         c.len = (int32_t)(e - c.start);
         c.nxt_end = (doc0 + 2 <= p.b) ? (int64_t)p.offsets[doc0 + 2] : e;
         if (c.len == 0)
@@ -200,8 +205,9 @@ __device__ __forceinline__ void it_enter_doc(TileIter &it, const FwdParams &p, i
                 it.offv = p.offsets[i < p.b ? i : p.b];
                 k = 0;
             }
-            int s = __builtin_amdgcn_readlane(it.offv, k);
-            int e = __builtin_amdgcn_readlane(it.offv, k + 1);
+            const int t_all = (int)p.total_tokens; // < 2^31; offsets are forced into [0, T] and made non-decreasing
+            int s = min(max(__builtin_amdgcn_readlane(it.offv, k), 0), t_all);
+            int e = min(max(__builtin_amdgcn_readlane(it.offv, k + 1), s), t_all);
             it.row0 = s;
             it.len = e - s;
         } else {

@@ -143,3 +143,23 @@ def test_forward_i8_large_corpus_negative_maxima():
     ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
     assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
     assert float(s[0, 0]) < 0 < float(s[0, 1])
+
+
+@pytest.mark.parametrize("b", [7, 4100])
+def test_forward_i8_tiny_huge_and_zero_scales(b):
+    """Scales far from 1 (but above 2^-100) and all-zero rows: still bit-exact, negative maxima included."""
+    rng = np.random.default_rng(77)
+    Q = torch.from_numpy(rng.integers(-127, 128, (2, 40, 128), dtype=np.int8)).to(DEV)
+    D = torch.from_numpy(rng.integers(-127, 128, (b, 35, 128), dtype=np.int8)).to(DEV)
+    D[1] = -Q[0, :35].abs().clamp(min=1)          # mostly negative dot products against query 0 ...
+    Q[0] = Q[0].abs().clamp(min=1)                # ... whose rows are made positive
+    qs = torch.from_numpy(10.0 ** rng.uniform(-2, 2, (2, 40)).astype(np.float32)).to(DEV)  # row values within 19 binades
+    ds = torch.from_numpy(10.0 ** rng.uniform(-25, 10, (b, 35)).astype(np.float32)).to(DEV)
+    ds[2] = 0.0
+    D[2] = 0
+    qs[1, 3] = 0.0
+    s = M.maxsim_forward_i8(Q, qs, D, ds)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+    assert float(s[0, 1]) < 0

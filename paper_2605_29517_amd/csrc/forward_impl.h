@@ -114,8 +114,12 @@ __device__ __forceinline__ float finish_block(const FwdParams &p, float m, int i
         m = take ? a : b;
         idx = take ? i0 : i1;
         if (col_valid && h == 0) {
+            // the address is formed here, at the end of a document, from an opaque copy of the lane's
+            // column: hoisted out of the tile loop its per-lane 64-bit parts would cost registers there
+            int col = rho;
+            asm volatile("" : "+v"(col));
             int q = gb / p.bpq;
-            int tok = (gb % p.bpq) * BLOCK_COLS + rho;
+            int tok = (gb % p.bpq) * BLOCK_COLS + col;
             if (idx > len - 1)
                 idx = len - 1;
             p.argmax[((int64_t)q * p.ld + doc) * p.l_q + tok] = idx;
@@ -320,7 +324,9 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
 //     tiles: three LDS buffers rotate (being computed / prefetched into registers / being
 //     written), one barrier per tile.  (The fp32 and the argmax variants have no registers
 //     left for the second operand set; they read the current tile's operands at its start.)
-template <int DT, int W, int NCB, bool ARGMAX>
+//   * with one or two column blocks per wavefront a tile takes too little time for a load issued
+//     one tile ahead to have arrived: PFD tiles are then in flight in a ring of registers.
+template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
 __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 1) fwd_tile_kernel(FwdParams p)
 {
     using TR = Traits<DT>;
@@ -409,12 +415,15 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
         if (!it_valid(ci))
             break;
 
-        uint4 g[CPT];
-        bool g_has = false;
-        // HBM -> registers for the next tile of the stream
+        uint4 g[PFD][CPT]; // tiles in flight from HBM: g[0] is the oldest (next to be stored to LDS)
+        bool g_has[PFD];
+#pragma unroll
+        for (int s = 0; s < PFD; ++s)
+            g_has[s] = false;
+        // HBM -> registers (newest ring slot) for the next tile of the stream
         auto gload = [&]() {
-            g_has = it_valid(li);
-            if (!g_has)
+            g_has[PFD - 1] = it_valid(li);
+            if (!g_has[PFD - 1])
                 return;
             if (!copies) {
                 it_next(li, p, lane);
@@ -425,26 +434,43 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 int row = cp_row[i] < last_row ? cp_row[i] : last_row;
-                g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
+                g[PFD - 1][i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
             }
             it_next(li, p, lane);
         };
+        // oldest ring slot -> LDS
         auto lstore = [&](int buf_off) {
-            if (!g_has || !copies)
+            if (!g_has[0] || !copies)
                 return;
 #pragma unroll
             for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g[i];
+                *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g[0][i];
+        };
+        auto rotate = [&]() {
+#pragma unroll
+            for (int s = 0; s + 1 < PFD; ++s) {
+                g_has[s] = g_has[s + 1];
+#pragma unroll
+                for (int i = 0; i < CPT; ++i)
+                    g[s][i] = g[s + 1][i];
+            }
         };
 
         // LDS buffers (byte offsets): o_cur holds the tile being computed (already in registers),
         // o_nxt the next one (read into registers during this tile), o_wr receives the one after
         int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
-        gload();
-        lstore(o_cur);
-        gload();
-        lstore(o_nxt);
-        gload();
+        // tiles 0 and 1 go straight to LDS, the next PFD tiles into the ring
+#pragma unroll
+        for (int s = 0; s < PFD + 2; ++s) {
+            rotate();
+            gload();
+            if (s < 2) { // the tile just loaded sits in the newest slot: pull it to the front and store it
+#pragma unroll
+                for (int r = 0; r + 1 < PFD; ++r)
+                    rotate();
+                lstore(s == 0 ? o_cur : o_nxt);
+            }
+        }
         __syncthreads();
         uint4 a0[NU], a1[PF ? NU : 1]; // (a0 stays unused when the operand ring is in use)
         if (PF) {
@@ -497,6 +523,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                             an[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_nxt + a_off + u * 32]);
                         if (u == NU - 1) {
                             lstore(o_wr);
+                            rotate();
                             gload();
                         }
                     } else {
@@ -548,6 +575,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
             // no column block in this pass: the wavefront only helps moving tiles (same barriers as the others)
             while (it_valid(ci)) {
                 lstore(o_wr);
+                rotate();
                 gload();
                 it_next(ci, p, lane);
                 __syncthreads();
@@ -584,10 +612,10 @@ static hipError_t launch_stream(const FwdParams &p, int grid, hipStream_t stream
     return hipGetLastError();
 }
 
-template <int DT, int W, int NCB, bool ARGMAX>
+template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
 static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX>), dim3(grid), dim3(W * 64), 0, stream, p);
+    hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX, PFD>), dim3(grid), dim3(W * 64), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -614,6 +642,12 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
 {
     constexpr int NU = Traits<DT>::NU;
     constexpr int NCB = NU <= 8 ? 4 : 32 / NU; // query fragments fill 128 registers
+    if constexpr (NCB == 4) { // few column blocks: eight wavefronts with one or two blocks each
+        if (w == 81)
+            return launch_tile<DT, 8, 1, ARGMAX, 6>(p, grid, s);
+        if (w == 82)
+            return launch_tile<DT, 8, 2, ARGMAX, 3>(p, grid, s);
+    }
     switch (w) {
     case 1: return launch_tile<DT, 1, NCB, ARGMAX>(p, grid, s);
     case 2: return launch_tile<DT, 2, NCB, ARGMAX>(p, grid, s);

@@ -147,3 +147,34 @@ def test_ragged_forward_argmax_feeds_ragged_backward():
     rQ, rD = O.backward_ragged(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", off, A, g.cpu().numpy().astype(np.float64))
     close(dQ, rQ, "dQ")
     close(dD, rD, "dD")
+
+
+def test_autograd_wrapper_matches_the_oracle():
+    """loss = sum(w * maxsim(Q, D)) through torch.autograd: gradients equal the oracle's for dscore = w."""
+    from paper_2605_29517_amd.autograd import maxsim
+    lens = np.array([40, 70, 0, 33, 5])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    for seed in range(100, 500):  # inputs with clear top-2 margins, chosen by the oracle alone
+        Q = W.unit_rows((2, 8, 128), "f16", seed, DEV)
+        Dp = W.unit_rows((int(off[-1]), 128), "f16", seed + 1000, DEV)
+        _, A, mg = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", offsets=off)
+        if mg[A >= 0].min() > 1.1e-3:
+            break
+    w = torch.randn(2, len(lens), device=DEV, generator=torch.Generator(DEV).manual_seed(5))
+    Qg, Dg = Q.clone().requires_grad_(True), Dp.clone().requires_grad_(True)
+    s = maxsim(Qg, Dg, torch.from_numpy(off).to(DEV))
+    keep = torch.isfinite(s)
+    (torch.where(keep, s, torch.zeros_like(s)) * w).sum().backward()
+    rQ, rD = O.backward_ragged(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", off, A, w.cpu().numpy().astype(np.float64))
+    # gradients come back in the input dtype (fp16): compare at fp16 resolution
+    assert np.abs(Qg.grad.float().cpu().numpy() - rQ).max() <= 2e-3 * np.abs(rQ).max()
+    assert np.abs(Dg.grad.float().cpu().numpy() - rD).max() <= 2e-3 * np.abs(rD).max()
+    # uniform path, fp32
+    Qf = W.unit_rows((3, 16, 128), "f32", 7, DEV).requires_grad_(True)
+    Df = W.unit_rows((4, 50, 128), "f32", 8, DEV).requires_grad_(True)
+    wf = torch.randn(3, 4, device=DEV, generator=torch.Generator(DEV).manual_seed(6))
+    (maxsim(Qf, Df) * wf).sum().backward()
+    _, A2, _ = O.forward(W.to_raw_numpy(Qf.detach()), W.to_raw_numpy(Df.detach()), "f32")
+    rQ, rD = O.backward(W.to_raw_numpy(Qf.detach()), W.to_raw_numpy(Df.detach()), "f32", A2, wf.cpu().numpy().astype(np.float64))
+    close(Qf.grad, rQ, "dQ")
+    close(Df.grad, rD, "dD")

@@ -120,7 +120,7 @@ def main():
         lambda: M.maxsim_forward_ragged(Q, Dp, off, total_tokens=T, scores=scores), args.steps, args.warmup)
     pairs_per_s = n_q * n_docs / (wall_ms * 1e-3)
     out = {
-        "metric": "docs scored/sec per query",
+        "metric": "docs scored/sec per query + % MFMA peak (L_q=1024) / % HBM BW (L_q=32)",
         "value": round(pairs_per_s, 1),
         "unit": "docs/s (each query's documents counted: N_q*B/t)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 4),
@@ -326,6 +326,13 @@ def main():
         del big, dst
 
     out["legs"] = extra
+    # the two fractions the metric names, lifted out of the legs: % of MFMA peak at L_q = L_d = 1024 (config 3)
+    # and % of HBM bandwidth at L_q = 32 (single-query slice of config 2)
+    by_leg = {l["leg"]: l for l in extra}
+    out["metric_fractions"] = {
+        "mfma_frac_lq1024": by_leg["c3"]["roofline"]["frac"] if "c3" in by_leg else None,
+        "hbm_frac_lq32": by_leg["c2_nq1"]["roofline"]["frac"] if "c2_nq1" in by_leg else None,
+    }
     print(json.dumps(out))
 
 

@@ -333,6 +333,17 @@ def main():
         "mfma_frac_lq1024": by_leg["c3"]["roofline"]["frac"] if "c3" in by_leg else None,
         "hbm_frac_lq32": by_leg["c2_nq1"]["roofline"]["frac"] if "c2_nq1" in by_leg else None,
     }
+    # context only (another machine, the authors' Triton kernels): figures the paper prints for an A100-40GB
+    # (Tab. "mem", Fig. 1 caption, Sec. 1) and for the ColPali shape on an A100-80GB (Tab. "fwd_abs", inference frontier)
+    out["paper_context"] = {
+        "a100_40gb_peak_memory_gb_colpali_1024x1024": {"fused_B10K": 2.9, "fused_B20K": 5.2, "fused_B50K": 13.1, "fused_B100K": 26.2,
+                                                       "naive_fp16_B10K": 23.9, "naive_fp16_B20K": "OOM"},
+        "a100_40gb_largest_dense_corpus_docs": 175000,
+        "unfused_similarity_tensor_gb_per_query_B10K": {"fp16": 21, "fp32": 42},
+        "a100_80gb_fused_ms_colpali_B10K_one_query": 16.2,
+        "here_device_memory_gb_config3": round((10_000 * 1024 * 128 * 2 + 4 * 1024 * 128 * 2 + 4 * 10_000 * 4) / 1e9, 2),
+        "note": "the library allocates nothing: device memory is the caller's inputs and outputs",
+    }
     print(json.dumps(out))
 
 

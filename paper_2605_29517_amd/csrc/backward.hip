@@ -431,24 +431,49 @@ __global__ void __launch_bounds__(256) ce_grad_kernel(const float *s, int n, int
     }
 }
 
-// Loss: a single block; 16 lanes per row, 64 rows at a time, partial sums combined in a fixed order.
+// Loss: a single block (fixed summation order); 16 lanes per row, 64 rows at a time.  The scaled
+// scores of a lane are fetched once into registers (all loads of a row in flight together) when the
+// row has at most 16 * CE_KEEP columns; wider rows are re-read from memory for each of the three sweeps.
+constexpr int CE_KEEP = 32;
+
 __global__ void __launch_bounds__(1024) ce_loss_kernel(const float *s, int n, int b, float inv_tau, float *loss)
 {
     __shared__ float part[64];
     const int sub = threadIdx.x & 15;
     const int slot = threadIdx.x >> 4;
+    const bool keep = b <= 16 * CE_KEEP;
     float local = 0.0f;
     for (int i = slot; i < n; i += 64) {
         const float *row = s + (int64_t)i * b;
+        float v[CE_KEEP];
+        if (keep) {
+#pragma unroll
+            for (int k = 0; k < CE_KEEP; ++k) {
+                int j = sub + 16 * k;
+                v[k] = j < b ? scaled(row[j], inv_tau) : neg_inf();
+            }
+        }
         float mx = neg_inf();
-        for (int j = sub; j < b; j += 16)
-            mx = fmaxf(mx, scaled(row[j], inv_tau));
+        if (keep) {
+#pragma unroll
+            for (int k = 0; k < CE_KEEP; ++k)
+                mx = fmaxf(mx, v[k]);
+        } else {
+            for (int j = sub; j < b; j += 16)
+                mx = fmaxf(mx, scaled(row[j], inv_tau));
+        }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1)
             mx = fmaxf(mx, __shfl_xor(mx, o));
         float z = 0.0f;
-        for (int j = sub; j < b; j += 16)
-            z += expf(scaled(row[j], inv_tau) - mx);
+        if (keep) {
+#pragma unroll
+            for (int k = 0; k < CE_KEEP; ++k)
+                z += (sub + 16 * k < b) ? expf(v[k] - mx) : 0.0f; // same order as the sweep over memory
+        } else {
+            for (int j = sub; j < b; j += 16)
+                z += expf(scaled(row[j], inv_tau) - mx);
+        }
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1)
             z += __shfl_xor(z, o);

@@ -92,7 +92,7 @@ def test_contrastive_step_small():
     close(dD2, rD, "dD")
 
 
-@pytest.mark.parametrize("n,b", [(1, 1), (4, 6), (37, 50), (256, 256)])
+@pytest.mark.parametrize("n,b", [(1, 1), (4, 6), (37, 50), (256, 256), (40, 700)])
 def test_ce_grad(n, b):
     s = (torch.randn(n, b, device=DEV, generator=torch.Generator(DEV).manual_seed(n * 1000 + b)) * 3 + 10).contiguous()
     g, loss = M.maxsim_ce_grad(s, 0.02)

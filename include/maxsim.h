@@ -10,7 +10,7 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer is a DEVICE pointer owned by the caller (the one exception, the host
- *     corpus of maxsim_forward_streamed, is marked HOST).  The library never allocates,
+ *     corpus of the *_streamed entry points, is marked HOST).  The library never allocates,
  *     frees or keeps device memory.
  *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it
  *     and return; they never synchronise.  NULL means the default stream.
@@ -154,6 +154,18 @@ int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, 
                              const int8_t *D_i8_packed, const float *d_scale_packed,
                              const int32_t *doc_offsets, int64_t b, int64_t total_tokens, int d,
                              float *scores, void *stream);
+
+/*
+ * Out-of-core int8 scoring: maxsim_forward_i8 with codes and scales in HOST memory, streamed like
+ * maxsim_forward_streamed.
+ *   D_i8_host [b, l_d, d] int8 and d_scale_host [b, l_d] float32 in HOST memory
+ *   staging_codes  DEVICE, 2 * block_docs * l_d * d bytes;  staging_scales  DEVICE, 2 * block_docs * l_d floats
+ * Other arguments, limits and arithmetic as in maxsim_forward_i8 (identical bits).
+ */
+int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q,
+                               const int8_t *D_i8_host, const float *d_scale_host, int64_t b, int l_d,
+                               int d, int64_t block_docs, int8_t *staging_codes, float *staging_scales,
+                               float *scores, void *stream);
 
 /*
  * Gradient of the in-batch-negatives cross-entropy on a score matrix (helper for the

@@ -17,7 +17,7 @@ MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
 SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
-           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_ce_grad",
+           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_forward_i8_streamed", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
 _lib = None
@@ -56,6 +56,8 @@ def load():
     L.maxsim_forward_i8.argtypes = [p, p, i, i, p, p, l, i, i, p, p]
     L.maxsim_forward_i8_ragged.restype = i
     L.maxsim_forward_i8_ragged.argtypes = [p, p, i, i, p, p, p, l, l, i, p, p]
+    L.maxsim_forward_i8_streamed.restype = i
+    L.maxsim_forward_i8_streamed.argtypes = [p, p, i, i, p, p, l, i, i, l, p, p, p, p]
     L.maxsim_ce_grad.restype = i
     L.maxsim_ce_grad.argtypes = [p, i, i, f, p, p, p]
     L.maxsim_probe_mfma.restype = i
@@ -259,6 +261,31 @@ def maxsim_forward_i8_ragged(Q_i8, q_scale, D_i8_packed, d_scale_packed, doc_off
                                         _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
                                         _dev(scores, "scores", torch.float32), _stream(Q_i8))
     _check(rc, "maxsim_forward_i8_ragged")
+    return scores
+
+
+def maxsim_forward_i8_streamed(Q_i8, q_scale, D_i8_host, d_scale_host, block_docs, scores=None):
+    """Out-of-core int8 scoring: codes [b,l_d,d] and scales [b,l_d] are HOST tensors (pinned for asynchronous copies)."""
+    L = load()
+    n_q, l_q, d = Q_i8.shape
+    b, l_d, _ = D_i8_host.shape
+    if D_i8_host.is_cuda or d_scale_host.is_cuda or not D_i8_host.is_contiguous() or not d_scale_host.is_contiguous():
+        raise MaxSimError("D_i8_host and d_scale_host must be contiguous host tensors")
+    if D_i8_host.dtype != torch.int8 or d_scale_host.dtype != torch.float32 or tuple(d_scale_host.shape) != (b, l_d):
+        raise MaxSimError("D_i8_host must be int8 [b,l_d,d] and d_scale_host float32 [b,l_d]")
+    block_docs = int(min(block_docs, b))
+    st_c = torch.empty(2 * block_docs, l_d, d, dtype=torch.int8, device=Q_i8.device)
+    st_s = torch.empty(2 * block_docs, l_d, dtype=torch.float32, device=Q_i8.device)
+    if scores is None:
+        scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
+    with _on_device(Q_i8, "Q_i8"):
+        rc = L.maxsim_forward_i8_streamed(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
+                                          ctypes.c_void_p(D_i8_host.data_ptr()), ctypes.c_void_p(d_scale_host.data_ptr()),
+                                          b, l_d, d, block_docs, _dev(st_c, "staging_codes"), _dev(st_s, "staging_scales"),
+                                          _dev(scores, "scores", torch.float32), _stream(Q_i8))
+    _check(rc, "maxsim_forward_i8_streamed")
+    # the staging buffers allocated here may be recycled by torch only for later work on this same stream,
+    # which runs after the last kernel and hence after the last copy
     return scores
 
 

@@ -14,7 +14,7 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
-                             int num_cu, hipStream_t stream);
+                             int64_t ld, int num_cu, hipStream_t stream);
 hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream);
 hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream);
 hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream);
@@ -91,6 +91,59 @@ int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t
     return finish(maxsim::forward_launch(p, dtype, d, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
+// Out-of-core driver shared by the streamed entry points: block k + 1 is copied on the copy stream while
+// block k is scored on the caller's stream; two staging halves, events in both directions.
+// copy(half, first, docs, copy_stream) enqueues the host-to-device copies of a block,
+// launch(half, first, docs) enqueues its kernel on the caller's stream.
+template <typename Copy, typename Launch>
+int stream_blocks(hipStream_t compute, int64_t b, int64_t block_docs, Copy copy_block, Launch launch_block)
+{
+    hipStream_t copy = copy_stream();
+    if (!copy)
+        return MAXSIM_ERR_LAUNCH;
+    // events: block k copied (per staging half), staging half free again (its kernel has run)
+    hipEvent_t copied[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr}, entry = nullptr;
+    bool ok = hipEventCreateWithFlags(&entry, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i)
+        ok = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&freed[i], hipEventDisableTiming) == hipSuccess;
+    int rc = ok ? MAXSIM_OK : MAXSIM_ERR_LAUNCH;
+    // the staging buffer may still be in use by work already enqueued on the caller's stream
+    if (rc == MAXSIM_OK && (hipEventRecord(entry, compute) != hipSuccess || hipStreamWaitEvent(copy, entry, 0) != hipSuccess))
+        rc = MAXSIM_ERR_LAUNCH;
+    const int64_t n_blocks = (b + block_docs - 1) / block_docs;
+    for (int64_t k = 0; k < n_blocks && rc == MAXSIM_OK; ++k) {
+        const int half = (int)(k & 1);
+        const int64_t first = k * block_docs;
+        const int64_t docs = (b - first < block_docs) ? b - first : block_docs;
+        hipError_t e = hipSuccess;
+        if (k >= 2)
+            e = hipStreamWaitEvent(copy, freed[half], 0); // the kernel that read this half two blocks ago
+        if (e == hipSuccess)
+            e = copy_block(half, first, docs, copy);
+        if (e == hipSuccess)
+            e = hipEventRecord(copied[half], copy);
+        if (e == hipSuccess)
+            e = hipStreamWaitEvent(compute, copied[half], 0);
+        if (e == hipSuccess)
+            e = launch_block(half, first, docs);
+        if (e == hipSuccess)
+            e = hipEventRecord(freed[half], compute);
+        if (e != hipSuccess)
+            rc = MAXSIM_ERR_LAUNCH;
+    }
+    // destroying an event that is still pending only releases it once it has completed
+    if (entry)
+        (void)hipEventDestroy(entry);
+    for (int i = 0; i < 2; ++i) {
+        if (copied[i])
+            (void)hipEventDestroy(copied[i]);
+        if (freed[i])
+            (void)hipEventDestroy(freed[i]);
+    }
+    return rc;
+}
+
 } // namespace
 
 extern "C" {
@@ -132,65 +185,63 @@ int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host,
         return MAXSIM_ERR_UNSUPPORTED;
     const int64_t doc_bytes = (int64_t)l_d * d * ((int)dtype == MAXSIM_F32 ? 4 : 2);
     hipStream_t compute = static_cast<hipStream_t>(stream);
-    hipStream_t copy = copy_stream();
-    if (!copy)
-        return MAXSIM_ERR_LAUNCH;
-    // events: block k copied (per staging half), staging half free again (its kernel has run)
-    hipEvent_t copied[2] = {nullptr, nullptr}, freed[2] = {nullptr, nullptr}, entry = nullptr;
-    bool ok = hipEventCreateWithFlags(&entry, hipEventDisableTiming) == hipSuccess;
-    for (int i = 0; i < 2 && ok; ++i)
-        ok = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&freed[i], hipEventDisableTiming) == hipSuccess;
-    int rc = MAXSIM_OK;
-    if (!ok)
-        rc = MAXSIM_ERR_LAUNCH;
-    // the staging buffer may still be in use by work already enqueued on the caller's stream
-    if (rc == MAXSIM_OK && (hipEventRecord(entry, compute) != hipSuccess || hipStreamWaitEvent(copy, entry, 0) != hipSuccess))
-        rc = MAXSIM_ERR_LAUNCH;
-    const int64_t n_blocks = (b + block_docs - 1) / block_docs;
-    for (int64_t k = 0; k < n_blocks && rc == MAXSIM_OK; ++k) {
-        const int half = (int)(k & 1);
-        const int64_t first = k * block_docs;
-        const int64_t docs = (b - first < block_docs) ? b - first : block_docs;
-        char *dst = static_cast<char *>(staging) + half * block_docs * doc_bytes;
-        const char *src = static_cast<const char *>(D_host) + first * doc_bytes;
-        hipError_t e = hipSuccess;
-        if (k >= 2)
-            e = hipStreamWaitEvent(copy, freed[half], 0); // the kernel that read this half two blocks ago
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(dst, src, (size_t)(docs * doc_bytes), hipMemcpyHostToDevice, copy);
-        if (e == hipSuccess)
-            e = hipEventRecord(copied[half], copy);
-        if (e == hipSuccess)
-            e = hipStreamWaitEvent(compute, copied[half], 0);
-        if (e != hipSuccess) {
-            rc = MAXSIM_ERR_LAUNCH;
-            break;
-        }
-        maxsim::FwdParams p = {};
-        p.Q = static_cast<const char *>(Q);
-        p.D = dst;
-        p.scores = scores + first;
-        p.b = docs;
-        p.ld = b;
-        p.total_tokens = docs * (int64_t)l_d;
-        p.n_q = n_q;
-        p.l_q = l_q;
-        p.l_d = l_d;
-        if (maxsim::forward_launch(p, (int)dtype, d, num_cu(), compute) != hipSuccess ||
-            hipEventRecord(freed[half], compute) != hipSuccess)
-            rc = MAXSIM_ERR_LAUNCH;
-    }
-    // destroying an event that is still pending only releases it once it has completed
-    if (entry)
-        (void)hipEventDestroy(entry);
-    for (int i = 0; i < 2; ++i) {
-        if (copied[i])
-            (void)hipEventDestroy(copied[i]);
-        if (freed[i])
-            (void)hipEventDestroy(freed[i]);
-    }
-    return rc;
+    const int cus = num_cu();
+    return stream_blocks(
+        compute, b, block_docs,
+        [&](int half, int64_t first, int64_t docs, hipStream_t copy) {
+            return hipMemcpyAsync(static_cast<char *>(staging) + half * block_docs * doc_bytes,
+                                  static_cast<const char *>(D_host) + first * doc_bytes, (size_t)(docs * doc_bytes),
+                                  hipMemcpyHostToDevice, copy);
+        },
+        [&](int half, int64_t first, int64_t docs) {
+            maxsim::FwdParams p = {};
+            p.Q = static_cast<const char *>(Q);
+            p.D = static_cast<const char *>(staging) + half * block_docs * doc_bytes;
+            p.scores = scores + first;
+            p.b = docs;
+            p.ld = b;
+            p.total_tokens = docs * (int64_t)l_d;
+            p.n_q = n_q;
+            p.l_q = l_q;
+            p.l_d = l_d;
+            return maxsim::forward_launch(p, (int)dtype, d, cus, compute);
+        });
+}
+
+int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q, const int8_t *D_i8_host,
+                               const float *d_scale_host, int64_t b, int l_d, int d, int64_t block_docs,
+                               int8_t *staging_codes, float *staging_scales, float *scores, void *stream)
+{
+    if (!Q_i8 || !q_scale || !D_i8_host || !d_scale_host || !staging_codes || !staging_scales || !scores || n_q < 1 ||
+        l_q < 1 || b < 1 || l_d < 1 || block_docs < 1)
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q_i8, 16) || !aligned(D_i8_host, 16) || !aligned(staging_codes, 16) || !aligned(q_scale, 4) ||
+        !aligned(d_scale_host, 4) || !aligned(staging_scales, 4) || !aligned(scores, 4))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (block_docs > b)
+        block_docs = b;
+    if (block_docs > ((int64_t(1) << 31) - 1) / l_d || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
+        return MAXSIM_ERR_UNSUPPORTED;
+    const int64_t doc_bytes = (int64_t)l_d * d;
+    hipStream_t compute = static_cast<hipStream_t>(stream);
+    const int cus = num_cu();
+    return stream_blocks(
+        compute, b, block_docs,
+        [&](int half, int64_t first, int64_t docs, hipStream_t copy) {
+            hipError_t e = hipMemcpyAsync(staging_codes + half * block_docs * doc_bytes, D_i8_host + first * doc_bytes,
+                                          (size_t)(docs * doc_bytes), hipMemcpyHostToDevice, copy);
+            if (e != hipSuccess)
+                return e;
+            return hipMemcpyAsync(staging_scales + half * block_docs * l_d, d_scale_host + first * l_d,
+                                  (size_t)(docs * l_d) * sizeof(float), hipMemcpyHostToDevice, copy);
+        },
+        [&](int half, int64_t first, int64_t docs) {
+            return maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, staging_codes + half * block_docs * doc_bytes,
+                                             staging_scales + half * block_docs * l_d, nullptr, docs, l_d,
+                                             docs * (int64_t)l_d, scores + first, b, cus, compute);
+        });
 }
 
 int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed, const int32_t *doc_offsets, int64_t b,
@@ -264,7 +315,7 @@ int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q
         l_q > 1024 || b * (int64_t)l_d >= (int64_t(1) << 31))
         return MAXSIM_ERR_UNSUPPORTED;
     return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, nullptr, b, l_d, b * (int64_t)l_d,
-                                            scores, num_cu(), static_cast<hipStream_t>(stream)));
+                                            scores, b, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q, const int8_t *D_i8_packed,
@@ -283,7 +334,7 @@ int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, 
         (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
         return MAXSIM_ERR_UNSUPPORTED;
     return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8_packed, d_scale_packed, doc_offsets, b, 0,
-                                            total_tokens, scores, num_cu(), static_cast<hipStream_t>(stream)));
+                                            total_tokens, scores, b, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss, void *stream)

@@ -498,7 +498,7 @@ template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, h
 // offsets == nullptr: uniform corpus [b, l_d, 128]; otherwise packed [total_tokens, 128] with int32 offsets [b + 1]
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
-                             int num_cu, hipStream_t stream)
+                             int64_t ld, int num_cu, hipStream_t stream)
 {
     I8Params P;
     P.Q = reinterpret_cast<const char *>(Q);
@@ -511,7 +511,7 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
     p.offsets = offsets;
     p.scores = scores;
     p.b = b;
-    p.ld = b;
+    p.ld = ld; // documents per row of `scores` (the whole corpus when b is a block of it)
     p.total_tokens = total_tokens;
     p.n_q = n_q;
     p.l_q = l_q;

@@ -48,6 +48,7 @@ def test_error_codes_without_touching_a_gpu():
     assert L.maxsim_forward_i8(p, p, 1, 2000, p, p, 1, 1, 128, p, None) == -2      # int8 queries above 1024 tokens
     assert L.maxsim_forward_streamed(p, 1, 32, p, 4, 40, 128, 1, 0, p, p, None) == -1  # block_docs < 1
     assert L.maxsim_forward_i8_ragged(p, p, 1, 32, p, p, None, 4, 100, 128, p, None) == -1  # no offsets
+    assert L.maxsim_forward_i8_streamed(p, p, 1, 32, p, p, 4, 10, 128, 2, None, p, p, None) == -1  # no staging buffer
     assert L.maxsim_backward_ragged(p, 1, 1, p, p, 1, 0, 128, 1, p, p, p, p, None) == -1     # total_tokens < 1
     assert L.maxsim_forward(p, 0, 32, p, 4, 40, 128, 1, p, None, None) == -1      # n_q < 1
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 128, 7, p, None, None) == -1      # bad dtype

@@ -48,3 +48,25 @@ def test_streamed_rejects_device_corpus():
     D = W.unit_rows((4, 10, 128), "f16", 46, DEV)
     with pytest.raises(M.MaxSimError):
         M.maxsim_forward_streamed(Q, D, 2)
+
+
+@pytest.mark.parametrize("case", [(1, 64, 300, 70, 64), (3, 200, 4500, 20, 4200), (2, 32, 9, 33, 100)])
+def test_int8_streamed_equals_resident(case):
+    """Blocks of >= 4096 documents take the document-stationary kernel, smaller ones the query-stationary one."""
+    n_q, l_q, b, l_d, block_docs = case
+    Qf = W.unit_rows((n_q, l_q, 128), "f16", 51, DEV)
+    Df = W.unit_rows((b, l_d, 128), "f32", 52, DEV)
+    q8, qs = M.maxsim_quantize_rows_i8(Qf)
+    d8, ds = M.maxsim_quantize_rows_i8(Df)
+    resident = M.maxsim_forward_i8(q8, qs, d8, ds)
+    d8h = torch.empty(d8.shape, dtype=torch.int8, pin_memory=True)
+    dsh = torch.empty(ds.shape, dtype=torch.float32, pin_memory=True)
+    d8h.copy_(d8)
+    dsh.copy_(ds)
+    s = M.maxsim_forward_i8_streamed(q8, qs, d8h, dsh, block_docs)
+    torch.cuda.synchronize()
+    assert torch.equal(s, resident)
+    oq, oqs = O.quantize_rows_i8(W.to_raw_numpy(Qf), "f16")
+    od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df[:50].contiguous()), "f32")
+    ref = O.forward_i8(oq, oqs, od, ods)
+    assert np.array_equal(s[:, :50].cpu().numpy().view(np.uint32), ref[:, :min(50, b)].view(np.uint32))

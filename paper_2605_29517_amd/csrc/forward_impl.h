@@ -290,11 +290,16 @@ template <int DT> struct LdsTile {
     static constexpr int CHUNKS = TILE_ROWS * Traits<DT>::ROW_BYTES / 16;
 };
 
-// Part `u` (of NU) of folding a result tile into the running max: rows [16 u / NU, 16 (u + 1) / NU).
+// Part `u` (of NU) of folding a result tile into the running max.  The first LAG steps do nothing, so
+// that the MFMA chain which produced the tile has left the matrix pipeline before its results are read
+// (no wait states); the 16 rows are spread over the remaining steps in even-sized pieces.
 template <bool ARGMAX, int NU>
 __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, int &idx, int row_base, int h)
 {
-    const int lo = 16 * u / NU, hi = 16 * (u + 1) / NU;
+    constexpr int LAG = NU >= 4 ? 2 : NU / 2;
+    if (u < LAG)
+        return;
+    const int lo = 2 * (8 * (u - LAG) / (NU - LAG)), hi = 2 * (8 * (u - LAG + 1) / (NU - LAG));
     if (ARGMAX) {
 #pragma unroll
         for (int r = lo; r < hi; ++r) {
@@ -304,12 +309,8 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
         }
     } else {
 #pragma unroll
-        for (int r = lo; r < hi; r += 2) {
-            if (r + 1 < hi)
-                m = fmaxf(fmaxf(m, acc[r]), acc[r + 1]); // one v_max3_f32
-            else
-                m = fmaxf(m, acc[r]);
-        }
+        for (int r = lo; r < hi; r += 2)
+            m = fmaxf(fmaxf(m, acc[r]), acc[r + 1]); // one v_max3_f32
     }
 }
 

@@ -26,6 +26,8 @@ SHAPES = [
     (64, 32, 33, 150), (1, 1024, 6, 260), (3, 700, 5, 95), (1, 1100, 4, 70), (2, 2100, 3, 40),
     # several wavefronts of the streaming kernel sharing a run of documents (2, 3 and 4 groups)
     (12, 32, 45, 130), (3, 64, 21, 77), (4, 96, 17, 140), (7, 50, 30, 33), (6, 1, 9, 5),
+    # one long query of 5-16 blocks: tile kernel with one or two blocks per wavefront and a ring of tiles in flight
+    (1, 200, 7, 90), (1, 256, 5, 64), (1, 300, 4, 100), (1, 512, 3, 70), (2, 160, 9, 45),
 ]
 
 

@@ -18,10 +18,13 @@
  *     pointers of Q, D and the int8 tensors must be 16-byte aligned, all other
  *     pointers 4-byte aligned.
  *   - d (embedding width): 128 everywhere (the paper's setting, Tab. "shapes").  The float
- *     forward entry points (maxsim_forward, _ragged, _streamed) also take rows of 128, 512 and
- *     1024 bytes, i.e. d = 64, 256, 512 for fp16/bf16 and d = 64, 256 for fp32 (the paper's
- *     "fat embedding" extension, App. "split-d"); other widths must be zero-padded by the
- *     caller to the next one.  Anything else returns MAXSIM_ERR_UNSUPPORTED.
+ *     forward entry points (maxsim_forward, _ragged, _streamed) also take any width whose rows are
+ *     a multiple of 64 bytes, from d = 32 up to rows of 16 KB: d = 32, 64, 96, ... , 8192 for
+ *     fp16/bf16 and d = 32, 48, 64, ... , 4096 for fp32 (the paper's "fat embedding" extension,
+ *     App. "split-d").  Rows of 128, 256, 512 and 1024 bytes keep the queries in registers; every
+ *     other width streams both operands in slabs of the embedding dimension (the paper's inner loop
+ *     over d).  Other widths must be zero-padded by the caller; they, and any width other than 128
+ *     at the backward and int8 entry points, return MAXSIM_ERR_UNSUPPORTED.
  *   - L_q and L_d are arbitrary positive integers (no tile multiples needed).
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
  *   - Return value: MAXSIM_OK (0) or a negative error code; on error nothing
@@ -38,7 +41,7 @@ extern "C" {
 
 #define MAXSIM_OK 0
 #define MAXSIM_ERR_INVALID (-1)     /* null pointer, non-positive size, misaligned pointer, bad enum */
-#define MAXSIM_ERR_UNSUPPORTED (-2) /* d != 128, or a size beyond what the kernels index */
+#define MAXSIM_ERR_UNSUPPORTED (-2) /* an embedding width or a size that the kernels are not built for */
 #define MAXSIM_ERR_LAUNCH (-3)      /* the HIP runtime reported an error at launch */
 
 typedef enum { MAXSIM_F32 = 0, MAXSIM_F16 = 1, MAXSIM_BF16 = 2 } maxsim_dtype;

@@ -178,7 +178,7 @@ __device__ __forceinline__ void chunk_doc_range(const FwdParams &p, int64_t chun
     }
 }
 
-// Walks the 32-token tiles of documents [doc, doc_end), the same in every lane.  All state is
+// Walks the tiles (32 tokens unless told otherwise) of documents [doc, doc_end), the same in every lane.  All state is
 // 32-bit and lives in scalar registers; for ragged corpora a vector register holds 64
 // consecutive offsets (one coalesced load per 63 documents) and v_readlane picks from it, so
 // stepping to the next document costs no memory latency.
@@ -231,10 +231,10 @@ __device__ __forceinline__ void it_init(TileIter &it, const FwdParams &p, int do
     it_enter_doc(it, p, lane);
 }
 
-__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, int lane)
+__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, int lane, int rows = TILE_ROWS)
 {
-    it.t0 += TILE_ROWS;
-    it.row0 += TILE_ROWS;
+    it.t0 += rows;
+    it.row0 += rows;
     if (it.t0 >= it.len) {
         it.doc += 1;
         it_enter_doc(it, p, lane);

@@ -10,12 +10,22 @@ hipError_t forward_run_f32(const FwdParams &p, int nu, bool argmax, bool tile, i
 
 static int round_up(int64_t x, int m) { return (int)((x + m - 1) / m * m); }
 
-// Embedding widths the float forward is built for: rows of 128, 256, 512 or 1024 bytes
-// (d = 64, 128, 256, 512 for 16-bit inputs; 32 .. 256 for fp32, of which the C ABI admits >= 64).
+hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_cu, hipStream_t stream);
+
+constexpr int MAX_ROW_BYTES = 16384; // d = 8192 (16-bit) or 4096 (fp32)
+
+// Rows of 128, 256, 512 or 1024 bytes have kernels that keep the queries in registers.
+static bool register_stationary_width(int row_bytes)
+{
+    return row_bytes == 128 || row_bytes == 256 || row_bytes == 512 || row_bytes == 1024;
+}
+
+// Embedding widths the float forward takes: rows that are a multiple of 64 bytes (d a multiple of 32 for
+// 16-bit inputs, of 16 for fp32), from d = 32 up to MAX_ROW_BYTES.
 bool forward_width_supported(int dtype, int d)
 {
-    const int row_bytes = d * (dtype == MAXSIM_F32 ? 4 : 2);
-    return d >= 64 && (row_bytes == 128 || row_bytes == 256 || row_bytes == 512 || row_bytes == 1024);
+    const int64_t row_bytes = (int64_t)d * (dtype == MAXSIM_F32 ? 4 : 2);
+    return d >= 32 && row_bytes % 64 == 0 && row_bytes <= MAX_ROW_BYTES;
 }
 
 // Chooses kernel and launch shape from the problem size; `num_cu` is the device's CU count.
@@ -23,7 +33,10 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
 {
     if (!forward_width_supported(dtype, d))
         return hipErrorNotSupported;
-    const int nu = d * (dtype == MAXSIM_F32 ? 4 : 2) / 32; // 16-byte chunk pairs per row
+    const int row_bytes = d * (dtype == MAXSIM_F32 ? 4 : 2);
+    if (!register_stationary_width(row_bytes)) // any other width: both operands stream through LDS in slabs of the width
+        return forward_splitd_launch(p, dtype, row_bytes, num_cu, stream);
+    const int nu = row_bytes / 32; // 16-byte chunk pairs per row
     const bool ragged = p.offsets != nullptr;
     const bool am = p.argmax != nullptr;
     p.bpq = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS;

@@ -42,8 +42,9 @@ def test_error_codes_without_touching_a_gpu():
     buf = (ctypes.c_char * 4096)()
     addr = (ctypes.addressof(buf) + 255) & ~255
     p = ctypes.c_void_p(addr)
-    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 96, 1, p, None, None) == -2       # d not in {64, 128, 256, 512}
-    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 512, 0, p, None, None) == -2      # fp32 rows wider than 1024 bytes
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 100, 1, p, None, None) == -2      # rows must be a multiple of 64 bytes
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 16, 1, p, None, None) == -2       # d < 32
+    assert L.maxsim_forward(p, 1, 32, p, 4, 40, 16384, 1, p, None, None) == -2    # rows above 16 KB
     assert L.maxsim_backward(p, 1, 1, p, 1, 1, 64, 1, p, p, p, p, None) == -2      # backward is built for d = 128 only
     assert L.maxsim_forward_i8(p, p, 1, 2000, p, p, 1, 1, 128, p, None) == -2      # int8 queries above 1024 tokens
     assert L.maxsim_forward_streamed(p, 1, 32, p, 4, 40, 128, 1, 0, p, p, None) == -1  # block_docs < 1

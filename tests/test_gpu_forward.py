@@ -97,7 +97,7 @@ def test_argument_errors():
     with pytest.raises(M.MaxSimError):
         M.maxsim_forward(Q.cpu(), D)
     with pytest.raises(M.MaxSimError):
-        M.maxsim_forward(Q[..., :96].contiguous(), D[..., :96].contiguous())  # d = 96 is not a supported width
+        M.maxsim_forward(Q[..., :100].contiguous(), D[..., :100].contiguous())  # rows of 200 bytes: not a multiple of 64
     L = M.load()
     assert L.maxsim_forward(None, 1, 32, None, 4, 40, 128, 1, None, None, None) == -1
 
@@ -124,4 +124,33 @@ def test_ragged_other_widths(n_q, l_q, dtype, d):
     off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
     Dp = W.unit_rows((int(lens.sum()), d), dtype, 71, DEV)
     Q = W.unit_rows((n_q, l_q, d), dtype, 72, DEV)
+    forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, True, RTOL_F32 if dtype == "f32" else RTOL_16)
+
+
+# Widths without a register-stationary kernel go through the slab-streaming ("split-d") kernel: rows that are any
+# multiple of 64 bytes.  Shapes: one block, ragged column tail, more than one group of 16 blocks (several queries),
+# a query of more than 16 blocks (two passes), documents shorter and longer than a macro tile of 128 tokens.
+SPLITD_SHAPES = [(1, 32, 9, 40), (3, 17, 5, 300), (8, 32, 12, 65), (2, 200, 6, 130), (1, 1030, 3, 70), (40, 32, 7, 33),
+                 (3, 600, 4, 257)]
+SPLITD_WIDTHS = [("f16", 32), ("f16", 96), ("bf16", 160), ("f16", 384), ("bf16", 768), ("f16", 1024), ("bf16", 2048),
+                 ("f32", 48), ("f32", 80), ("f32", 512)]
+
+
+@pytest.mark.parametrize("dtype,d", SPLITD_WIDTHS)
+@pytest.mark.parametrize("want_argmax", [False, True])
+@pytest.mark.parametrize("shape", SPLITD_SHAPES)
+def test_uniform_split_d(shape, want_argmax, dtype, d):
+    n_q, l_q, b, l_d = shape
+    Q = W.unit_rows((n_q, l_q, d), dtype, 81 + l_q, DEV)
+    D = W.unit_rows((b, l_d, d), dtype, 82 + l_d, DEV)
+    forward_parity_uniform(Q, D, M.maxsim_forward, want_argmax, RTOL_F32 if dtype == "f32" else RTOL_16)
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 96), ("bf16", 768), ("f16", 1024), ("f32", 48)])
+@pytest.mark.parametrize("n_q,l_q", [(1, 32), (5, 40), (2, 300), (1, 700)])
+def test_ragged_split_d(n_q, l_q, dtype, d):
+    lens = np.asarray([1, 31, 32, 33, 0, 64, 150, 0, 2, 65, 97, 128, 129, 300])
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.unit_rows((int(lens.sum()), d), dtype, 91, DEV)
+    Q = W.unit_rows((n_q, l_q, d), dtype, 92, DEV)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, True, RTOL_F32 if dtype == "f32" else RTOL_16)

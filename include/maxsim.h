@@ -21,7 +21,7 @@
  *     forward entry points (maxsim_forward, _ragged, _streamed) also take any width whose rows are
  *     a multiple of 64 bytes, from d = 32 up to rows of 16 KB: d = 32, 64, 96, ... , 8192 for
  *     fp16/bf16 and d = 32, 48, 64, ... , 4096 for fp32 (the paper's "fat embedding" extension,
- *     App. "split-d").  Rows of 128, 256, 512 and 1024 bytes keep the queries in registers; every
+ *     App. "split-d").  Rows of 128, 256 and 512 bytes can keep the queries in registers; every
  *     other width streams both operands in slabs of the embedding dimension (the paper's inner loop
  *     over d).  Other widths must be zero-padded by the caller; they, and any width other than 128
  *     at the backward and int8 entry points, return MAXSIM_ERR_UNSUPPORTED.

@@ -14,10 +14,12 @@ hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_
 
 constexpr int MAX_ROW_BYTES = 16384; // d = 8192 (16-bit) or 4096 (fp32)
 
-// Rows of 128, 256, 512 or 1024 bytes have kernels that keep the queries in registers.
+// Rows of 128, 256 or 512 bytes have kernels that keep the queries in registers.  (Such kernels for rows of
+// 1024 bytes were measured slower than the slab-streaming kernel at every shape: one column block per
+// wavefront leaves one MFMA per LDS operand read.)
 static bool register_stationary_width(int row_bytes)
 {
-    return row_bytes == 128 || row_bytes == 256 || row_bytes == 512 || row_bytes == 1024;
+    return row_bytes == 128 || row_bytes == 256 || row_bytes == 512;
 }
 
 // Embedding widths the float forward takes: rows that are a multiple of 64 bytes (d a multiple of 32 for
@@ -34,7 +36,10 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     if (!forward_width_supported(dtype, d))
         return hipErrorNotSupported;
     const int row_bytes = d * (dtype == MAXSIM_F32 ? 4 : 2);
-    if (!register_stationary_width(row_bytes)) // any other width: both operands stream through LDS in slabs of the width
+    // any other width: both operands stream through LDS in slabs of the width; so do rows of 512 bytes from 8 column
+    // blocks on (two blocks per wavefront in the register-stationary kernel: measured 3-11 % slower there)
+    const int64_t all_blocks = (int64_t)p.n_q * ((p.l_q + BLOCK_COLS - 1) / BLOCK_COLS);
+    if (!register_stationary_width(row_bytes) || (row_bytes == 512 && all_blocks >= 8))
         return forward_splitd_launch(p, dtype, row_bytes, num_cu, stream);
     const int nu = row_bytes / 32; // 16-byte chunk pairs per row
     const bool ragged = p.offsets != nullptr;
@@ -53,9 +58,9 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     };
 
     // Streaming kernel: every wavefront holds whole queries in as many column blocks as fit beside two
-    // document tiles in registers (4 for rows of up to 256 bytes, 2 for 512 bytes, none beyond), and up
+    // document tiles in registers (4 for rows of up to 256 bytes, 2 for 512 bytes), and up
     // to 4 wavefronts share a run of documents.  That covers up to 16 blocks of short queries.
-    const int stream_max_blocks = nu <= 8 ? 4 : (nu == 16 ? 2 : 0);
+    const int stream_max_blocks = nu <= 8 ? 4 : 2;
     int s_ncb = 0, s_groups = 0;
     if (total_blocks <= stream_max_blocks) {
         s_ncb = (int)total_blocks;
@@ -108,8 +113,6 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
         w = 2;
     else if (total_blocks <= 4 * ncb)
         w = 4;
-    if (nu == 32 && total_blocks <= 2)
-        w = 8; // rows of 1024 bytes and next to no arithmetic: all eight wavefronts move tiles, one or two compute
     int shape = w, wave_blocks = ncb;
     if (ncb == 4 && total_blocks <= 16) { // eight wavefronts with one or two column blocks each (shape code 81 / 82)
         wave_blocks = total_blocks <= 8 ? 1 : 2;

@@ -483,7 +483,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 
         // one tile: operands in `ac`; the next tile's operands are read into `an` on the way
         // a wavefront with a single column block uses every operand chunk once: a ring of four
-        // registers, read three steps ahead, replaces the full operand set (rows of 1024 bytes)
+        // registers, read three steps ahead, replaces the full operand set (the argmax variant with one block of 256-byte rows per wavefront)
         constexpr bool RING = !PF && NCB == 1 && NU >= 8;
         auto stage = [&](uint4(&ac)[NU], uint4(&an)[PF ? NU : 1]) {
             const int fin_doc = (ci.t0 + TILE_ROWS >= ci.len) ? ci.doc : -1; // last tile of its document?
@@ -631,10 +631,8 @@ static hipError_t dispatch_stream(const FwdParams &p, int ncb, int grid, hipStre
         case 3: return launch_stream<DT, 3, ARGMAX>(p, grid, s);
         default: return launch_stream<DT, 4, ARGMAX>(p, grid, s);
         }
-    } else if constexpr (NU == 16) {
-        return ncb == 1 ? launch_stream<DT, 1, ARGMAX>(p, grid, s) : launch_stream<DT, 2, ARGMAX>(p, grid, s);
     } else {
-        return hipErrorNotSupported; // never chosen: see stream_max_blocks
+        return ncb == 1 ? launch_stream<DT, 1, ARGMAX>(p, grid, s) : launch_stream<DT, 2, ARGMAX>(p, grid, s);
     }
 }
 
@@ -676,7 +674,6 @@ static hipError_t run_dtype(const FwdParams &p, int nu, bool argmax, bool tile, 
     case 4: return run_format<fmt(DTYPE, 4)>(p, argmax, tile, x, grid, s);
     case 8: return run_format<fmt(DTYPE, 8)>(p, argmax, tile, x, grid, s);
     case 16: return run_format<fmt(DTYPE, 16)>(p, argmax, tile, x, grid, s);
-    case 32: return run_format<fmt(DTYPE, 32)>(p, argmax, tile, x, grid, s);
     default: return hipErrorNotSupported;
     }
 }

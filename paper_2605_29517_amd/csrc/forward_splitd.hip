@@ -3,7 +3,7 @@
 // reduction of Alg. 1 unchanged), for gfx950.
 //
 // The register-stationary kernels of forward_impl.h hold a query block's fragments for the whole
-// embedding width, which stops at rows of 1024 bytes.  Here neither operand is stationary: a workgroup
+// embedding width, which pays up to rows of 512 bytes.  Here neither operand is stationary: a workgroup
 // of eight wavefronts (two per SIMD) computes the similarities of a MACRO TILE of 128 document tokens x
 // 512 query tokens, every wavefront a 128 x 64 piece of it in eight 32x32 accumulators (128 registers),
 // while both operands stream through LDS in slabs of 64 bytes per row:
@@ -266,22 +266,23 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
                 fb0[c] = *reinterpret_cast<const i32x4 *>(&lds[o_cur + b_base + rd0 + c * TILE_BYTES]);
 
             // one slab: `gs` holds the slab two ahead (to be stored), and is refilled with the slab four ahead
+            constexpr int COPIES0 = SD_MT * SD_NCB - (SD_MT + SD_NCB); // copies placed in the first half of a slab
             auto iter = [&](auto gs) {
-                gaddr();
-                __builtin_amdgcn_sched_barrier(0);
                 // first half of the slab (chunks h): meanwhile read the second half's operands, then store and reload
 #pragma unroll
                 for (int i = 0; i < SD_MT * SD_NCB; ++i) {
                     const int t = i / SD_NCB, c = i % SD_NCB;
                     sd_mma<DT>(fa0[t], fb0[c], acc[t][c]);
+                    if (i == 0)
+                        gaddr(); // scalar work for this slab's loads, under the first MFMA
                     if (i < SD_MT)
                         fa1[i] = *reinterpret_cast<const i32x4 *>(&lds[o_cur + rd1 + i * TILE_BYTES]);
                     else if (i < SD_MT + SD_NCB)
                         fb1[i - SD_MT] = *reinterpret_cast<const i32x4 *>(&lds[o_cur + b_base + rd1 + (i - SD_MT) * TILE_BYTES]);
-                    constexpr int FIRST_COPY = SD_MT * SD_NCB - SD_NG;
-                    if (i >= FIRST_COPY) {
-                        lstore1(gs, i - FIRST_COPY, o_wr);
-                        gload1(gs, i - FIRST_COPY);
+                    // the slots without an operand read take the copies (one LDS instruction per slot)
+                    if (i >= SD_MT + SD_NCB) {
+                        lstore1(gs, i - (SD_MT + SD_NCB), o_wr);
+                        gload1(gs, i - (SD_MT + SD_NCB));
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -290,11 +291,16 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
                 for (int i = 0; i < SD_MT * SD_NCB; ++i) {
                     const int t = i / SD_NCB, c = i % SD_NCB;
                     sd_mma<DT>(fa1[t], fb1[c], acc[t][c]);
-                    const int k = i - 2;
+                    const int k = i;
                     if (k >= 0 && k < SD_MT)
                         fa0[k] = *reinterpret_cast<const i32x4 *>(&lds[o_nxt + rd0 + k * TILE_BYTES]);
                     else if (k >= SD_MT && k < SD_MT + SD_NCB)
                         fb0[k - SD_MT] = *reinterpret_cast<const i32x4 *>(&lds[o_nxt + b_base + rd0 + (k - SD_MT) * TILE_BYTES]);
+                    constexpr int FIRST1 = SD_MT * SD_NCB - (SD_NG - COPIES0); // the remaining copies end with the slab
+                    if (i >= FIRST1) {
+                        lstore1(gs, COPIES0 + i - FIRST1, o_wr);
+                        gload1(gs, COPIES0 + i - FIRST1);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
 

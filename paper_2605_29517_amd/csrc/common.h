@@ -74,6 +74,11 @@ struct FwdParams {
 // are not non-decreasing or run past the corpus give wrong scores but never an address outside D.
 __device__ __forceinline__ int64_t clamp_offset(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
+// A kernel that walks a ragged corpus takes the offsets a second time, as a `const int32_t *__restrict__`
+// parameter of its own: only then does the compiler know that no store of the kernel can change them and
+// reads offsets[uniform index] through the scalar cache, apart from the vector loads in flight.
+typedef const int32_t *__restrict__ OffsetsPtr;
+
 // Cursor over the 32-row tiles of a run of documents, identical in every lane of a wavefront.
 struct Cursor {
     int64_t doc;     // current document
@@ -85,7 +90,7 @@ struct Cursor {
     bool valid;
 };
 
-__device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p)
+__device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p, OffsetsPtr off)
 {
     for (;;) {
         c.doc += 1;
@@ -97,7 +102,7 @@ __device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p)
             c.start += c.len;
             int64_t e = clamp_offset(c.nxt_end, c.start, p.total_tokens);
             c.len = (int32_t)(e - c.start);
-            c.nxt_end = (c.doc + 2 <= p.b) ? (int64_t)p.offsets[c.doc + 2] : e;
+            c.nxt_end = (int64_t)off[(c.doc + 2 <= p.b) ? c.doc + 2 : p.b]; // no branch around the load: it stays a scalar load
             if (c.len > 0)
                 return;
         } else {
@@ -107,7 +112,7 @@ __device__ __forceinline__ void cursor_next_doc(Cursor &c, const FwdParams &p)
     }
 }
 
-__device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64_t doc0, int64_t doc1)
+__device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, OffsetsPtr off, int64_t doc0, int64_t doc1)
 {
     c.doc = doc0;
     c.doc_end = doc1;
@@ -116,12 +121,12 @@ __device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64
     if (!c.valid)
         return;
     if (p.offsets) {
-        c.start = clamp_offset(p.offsets[doc0], 0, p.total_tokens);
-        int64_t e = clamp_offset(p.offsets[doc0 + 1], c.start, p.total_tokens);
+        c.start = clamp_offset(off[doc0], 0, p.total_tokens);
+        int64_t e = clamp_offset(off[doc0 + 1], c.start, p.total_tokens);
         c.len = (int32_t)(e - c.start);
-        c.nxt_end = (doc0 + 2 <= p.b) ? (int64_t)p.offsets[doc0 + 2] : e;
+        c.nxt_end = (int64_t)off[(doc0 + 2 <= p.b) ? doc0 + 2 : p.b];
         if (c.len == 0)
-            cursor_next_doc(c, p);
+            cursor_next_doc(c, p, off);
     } else {
         c.start = doc0 * (int64_t)p.l_d;
         c.len = p.l_d;
@@ -129,11 +134,11 @@ __device__ __forceinline__ void cursor_init(Cursor &c, const FwdParams &p, int64
     }
 }
 
-__device__ __forceinline__ void cursor_next_tile(Cursor &c, const FwdParams &p, int rows = TILE_ROWS)
+__device__ __forceinline__ void cursor_next_tile(Cursor &c, const FwdParams &p, OffsetsPtr off, int rows = TILE_ROWS)
 {
     c.t0 += rows;
     if (c.t0 >= c.len)
-        cursor_next_doc(c, p);
+        cursor_next_doc(c, p, off);
 }
 
 // Documents [doc0, doc1) of work chunk `chunk`.  Uniform corpus: equal document counts.
@@ -178,42 +183,39 @@ __device__ __forceinline__ void chunk_doc_range(const FwdParams &p, int64_t chun
     }
 }
 
-// Walks the tiles (32 tokens unless told otherwise) of documents [doc, doc_end), the same in every lane.  All state is
-// 32-bit and lives in scalar registers; for ragged corpora a vector register holds 64
-// consecutive offsets (one coalesced load per 63 documents) and v_readlane picks from it, so
-// stepping to the next document costs no memory latency.
+// Walks the tiles (32 tokens unless told otherwise) of documents [doc, doc_end), the same in every lane.  All
+// state is 32-bit and uniform (scalar registers).  For ragged corpora the end of the NEXT document is
+// fetched while the current one is walked, so that stepping to the next document waits for no memory.
 struct TileIter {
     int doc, doc_end;
     int row0; // packed row of the current tile's first token
     int t0;   // document-local index of that token
     int len;  // tokens in the current document
-    int base; // document whose offset sits in lane 0 of offv
-    int offv; // offsets[min(base + lane, b)]
+    int end;  // packed row one past the current document (ragged only)
+    int nxt;  // offsets[doc + 2], unclamped, fetched one document ahead (ragged only)
 };
 
 __device__ __forceinline__ bool it_valid(const TileIter &it) { return it.doc < it.doc_end; }
 
-__device__ __forceinline__ void it_enter_doc(TileIter &it, const FwdParams &p, int lane)
+__device__ __forceinline__ int it_offset(OffsetsPtr off, const FwdParams &p, int i)
 {
-    // position on document it.doc, skipping empty documents
+    const int64_t j = i < p.b ? (int64_t)i : p.b;
+    return off[j];
+}
+
+// Enters document it.doc (whose first row is it.end of the previous one and whose unclamped end is it.nxt),
+// skipping empty documents.  Offsets are forced into [previous end, T], so that offsets which are not
+// non-decreasing or run past the corpus give wrong scores but never an address outside D.
+__device__ __forceinline__ void it_enter_ragged(TileIter &it, const FwdParams &p, OffsetsPtr off)
+{
+    const int t_all = (int)p.total_tokens; // < 2^31
     while (it.doc < it.doc_end) {
-        if (p.offsets) {
-            int k = it.doc - it.base;
-            if (k < 0 || k >= 63) {
-                it.base = it.doc;
-                int64_t i = (int64_t)it.doc + lane;
-                it.offv = p.offsets[i < p.b ? i : p.b];
-                k = 0;
-            }
-            const int t_all = (int)p.total_tokens; // < 2^31; offsets are forced into [0, T] and made non-decreasing
-            int s = min(max(__builtin_amdgcn_readlane(it.offv, k), 0), t_all);
-            int e = min(max(__builtin_amdgcn_readlane(it.offv, k + 1), s), t_all);
-            it.row0 = s;
-            it.len = e - s;
-        } else {
-            it.row0 = it.doc * p.l_d;
-            it.len = p.l_d;
-        }
+        const int s = it.end;
+        const int e = min(max(it.nxt, s), t_all);
+        it.nxt = it_offset(off, p, it.doc + 2);
+        it.row0 = s;
+        it.end = e;
+        it.len = e - s;
         it.t0 = 0;
         if (it.len > 0)
             return;
@@ -221,23 +223,35 @@ __device__ __forceinline__ void it_enter_doc(TileIter &it, const FwdParams &p, i
     }
 }
 
-__device__ __forceinline__ void it_init(TileIter &it, const FwdParams &p, int doc0, int doc1, int lane)
+__device__ __forceinline__ void it_init(TileIter &it, const FwdParams &p, OffsetsPtr off, int doc0, int doc1)
 {
     it.doc = doc0;
     it.doc_end = doc1;
-    it.base = -1000;
-    it.offv = 0;
-    it.row0 = it.t0 = it.len = 0;
-    it_enter_doc(it, p, lane);
+    it.row0 = it.t0 = it.len = it.end = it.nxt = 0;
+    if (doc0 >= doc1)
+        return;
+    if (p.offsets) {
+        it.end = min(max(it_offset(off, p, doc0), 0), (int)p.total_tokens);
+        it.nxt = it_offset(off, p, doc0 + 1);
+        it_enter_ragged(it, p, off);
+    } else {
+        it.row0 = doc0 * p.l_d;
+        it.len = p.l_d;
+    }
 }
 
-__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, int lane, int rows = TILE_ROWS)
+__device__ __forceinline__ void it_next(TileIter &it, const FwdParams &p, OffsetsPtr off, int rows = TILE_ROWS)
 {
     it.t0 += rows;
     it.row0 += rows;
     if (it.t0 >= it.len) {
         it.doc += 1;
-        it_enter_doc(it, p, lane);
+        if (p.offsets) {
+            it_enter_ragged(it, p, off);
+        } else {
+            it.row0 = it.doc * p.l_d;
+            it.t0 = 0;
+        }
     }
 }
 

@@ -228,7 +228,7 @@ __device__ __forceinline__ void stream_compute(const FwdParams &p, const Cursor 
 }
 
 template <int DT, int NCB, bool ARGMAX>
-__global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
+__global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
     const int lane = threadIdx.x & 63;
@@ -253,13 +253,13 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
         load_q_block<DT>(p, gb0 + cb, rho, h, st.qf[cb], st.col_valid[cb]);
 
     Cursor pc; // prefetch cursor, one tile ahead of the compute cursor
-    cursor_init(pc, p, doc0, doc1);
+    cursor_init(pc, p, off, doc0, doc1);
     if (!pc.valid)
         return;
     uint4 a0[TR::NU], a1[TR::NU];
     stream_load_tile<DT>(p, pc, rho, h, a0);
     Cursor cc = pc;
-    cursor_next_tile(pc, p);
+    cursor_next_tile(pc, p, off);
     for (;;) {
         if (pc.valid)
             stream_load_tile<DT>(p, pc, rho, h, a1);
@@ -267,14 +267,14 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p)
         cc = pc;
         if (!cc.valid)
             break;
-        cursor_next_tile(pc, p);
+        cursor_next_tile(pc, p, off);
         if (pc.valid)
             stream_load_tile<DT>(p, pc, rho, h, a0);
         stream_compute<DT, NCB, ARGMAX>(p, cc, st, a1, gb0, lane, rho, h);
         cc = pc;
         if (!cc.valid)
             break;
-        cursor_next_tile(pc, p);
+        cursor_next_tile(pc, p, off);
     }
 }
 
@@ -328,7 +328,7 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
 //   * with one or two column blocks per wavefront a tile takes too little time for a load issued
 //     one tile ahead to have arrived: PFD tiles are then in flight in a ring of registers.
 template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
-__global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 1) fwd_tile_kernel(FwdParams p)
+__global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 1) fwd_tile_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
@@ -411,7 +411,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 
         const bool wave_active = w * NCB < nb;
         TileIter li, ci; // load iterator (three tiles ahead of the compute iterator at steady state)
-        it_init(li, p, doc0, doc1, lane);
+        it_init(li, p, off, doc0, doc1);
         ci = li;
         if (!it_valid(ci))
             break;
@@ -427,7 +427,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
             if (!g_has[PFD - 1])
                 return;
             if (!copies) {
-                it_next(li, p, lane);
+                it_next(li, p, off);
                 return;
             }
             int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
@@ -437,7 +437,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                 int row = cp_row[i] < last_row ? cp_row[i] : last_row;
                 g[PFD - 1][i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
             }
-            it_next(li, p, lane);
+            it_next(li, p, off);
         };
         // oldest ring slot -> LDS
         auto lstore = [&](int buf_off) {
@@ -552,7 +552,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                     }
                 }
             }
-            it_next(ci, p, lane);
+            it_next(ci, p, off);
             __syncthreads();
             if (fin_doc >= 0) {
                 if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
@@ -578,7 +578,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                 lstore(o_wr);
                 rotate();
                 gload();
-                it_next(ci, p, lane);
+                it_next(ci, p, off);
                 __syncthreads();
                 int t = o_cur;
                 o_cur = o_nxt;
@@ -609,14 +609,14 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 template <int DT, int NCB, bool ARGMAX>
 static hipError_t launch_stream(const FwdParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_stream_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((fwd_stream_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 
 template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
 static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX, PFD>), dim3(grid), dim3(W * 64), 0, stream, p);
+    hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX, PFD>), dim3(grid), dim3(W * 64), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 

@@ -52,7 +52,7 @@ template <int DT> __device__ __forceinline__ void sd_mma(const i32x4 &a, const i
 }
 
 template <int DT, bool ARGMAX>
-__global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int row_bytes)
+__global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, OffsetsPtr off, int row_bytes)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     float *lds_part = reinterpret_cast<float *>(lds + 3 * SD_BUF); // [2][SD_GROUP_BLOCKS]
@@ -141,7 +141,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
 
         TileIter li, ci; // loader (four slabs ahead at steady state) and compute position
         int lks = 0, cks = 0;
-        it_init(li, p, doc0, doc1, lane);
+        it_init(li, p, off, doc0, doc1);
         ci = li;
         if (!it_valid(ci))
             break;
@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
                 s_ks = lks;
                 if (++lks == n_slabs) {
                     lks = 0;
-                    it_next(li, p, lane, SD_ROWS_A);
+                    it_next(li, p, off, SD_ROWS_A);
                 }
             }
             a_base = p.D + s_row0 * row_bytes + s_ks * SD_SLAB + cc * 16;
@@ -235,7 +235,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
                     gload1(gs, k);
                 }
                 if (advance_compute())
-                    it_next(ci, p, lane, SD_ROWS_A);
+                    it_next(ci, p, off, SD_ROWS_A);
                 __syncthreads();
                 rotate_buffers();
             };
@@ -335,7 +335,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, int 
                             idx[cb] = 0;
                         }
                     }
-                    it_next(ci, p, lane, SD_ROWS_A);
+                    it_next(ci, p, off, SD_ROWS_A);
                 }
                 __syncthreads();
                 if (fin_doc >= 0) {
@@ -383,7 +383,7 @@ hipError_t launch_splitd(const FwdParams &p, int row_bytes, int grid, hipStream_
             return e;
         allowed[dev] = true;
     }
-    hipLaunchKernelGGL((fwd_splitd_kernel<DT, ARGMAX>), dim3(grid), dim3(SD_W * 64), SD_LDS, stream, p, row_bytes);
+    hipLaunchKernelGGL((fwd_splitd_kernel<DT, ARGMAX>), dim3(grid), dim3(SD_W * 64), SD_LDS, stream, p, p.offsets, row_bytes);
     return hipGetLastError();
 }
 

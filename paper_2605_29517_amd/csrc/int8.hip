@@ -46,7 +46,7 @@ struct I8Params {
 };
 
 template <int W>
-__global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
+__global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P, OffsetsPtr off)
 {
     const FwdParams &p = P.f;
     constexpr int NT = W * 64;
@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
     }
 
     Cursor lc;
-    cursor_init(lc, p, doc0, doc1);
+    cursor_init(lc, p, off, doc0, doc1);
     uint4 g[CPT];
     float gs = 0.0f;
     auto gload = [&](const Cursor &c) {
@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
     gload(lc);
     lstore(0);
     Cursor cc = lc;
-    cursor_next_tile(lc, p, I8_TILE_ROWS);
+    cursor_next_tile(lc, p, off, I8_TILE_ROWS);
     if (lc.valid)
         gload(lc);
     __syncthreads();
@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P)
         Cursor cnext = lc;
         if (lc.valid) {
             lstore(cur ^ 1);
-            cursor_next_tile(lc, p, I8_TILE_ROWS);
+            cursor_next_tile(lc, p, off, I8_TILE_ROWS);
             if (lc.valid)
                 gload(lc);
         }
@@ -279,7 +279,7 @@ constexpr int I8D_QSTRIDE = I8_ROW_BYTES + 16;           // padded LDS row of a 
 // NB: column blocks the tile loop walks over (the group's block count rounded up; the surplus
 // blocks multiply zero rows and are never looked at).
 template <int NB>
-__global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
+__global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, OffsetsPtr off)
 {
     const FwdParams &p = P.f;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -336,7 +336,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
     }
 
     TileIter li, ci; // load iterator: one tile ahead of the compute iterator
-    it_init(li, p, doc0, doc1, lane);
+    it_init(li, p, off, doc0, doc1);
     ci = li;
     if (!it_valid(ci))
         return;
@@ -354,7 +354,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
         for (int u = 0; u < I8_NU; ++u)
             a_n[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
         s_n = P.ds[grow];
-        it_next(li, p, lane);
+        it_next(li, p, off);
     };
     gload();
 
@@ -465,13 +465,13 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P)
                 }
             }
         }
-        it_next(ci, p, lane);
+        it_next(ci, p, off);
     }
 }
 
 template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStream_t s)
 {
-    hipLaunchKernelGGL((fwd_i8_kernel<W>), dim3(grid), dim3(W * 64), 0, s, P);
+    hipLaunchKernelGGL((fwd_i8_kernel<W>), dim3(grid), dim3(W * 64), 0, s, P, P.f.offsets);
     return hipGetLastError();
 }
 
@@ -491,7 +491,7 @@ template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, h
             return e;
         allowed[dev] = true;
     }
-    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P);
+    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P, P.f.offsets);
     return hipGetLastError();
 }
 

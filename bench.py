@@ -222,9 +222,10 @@ def main():
     del Dp, Q
 
     if "wide_d" in legs:
-        # wider embeddings (the paper's fat-embedding extension): ColPali-shaped pages at d = 256 and 512, bf16
+        # wider embeddings (the paper's fat-embedding extension, App. "split-d"): ColPali-shaped pages, bf16;
+        # d = 256 keeps the queries in registers, every wider row streams both operands in slabs of d
         wide = []
-        for dw, ndw in ((256, 2000), (512, 1000)):
+        for dw, ndw in ((256, 2000), (512, 1000), (768, 700), (1024, 500), (2048, 250)):
             Qw = W.unit_rows((4, 1024, dw), "bf16", 91, dev)
             Dw = W.unit_rows((ndw, 1024, dw), "bf16", 92, dev)
             sw = torch.empty(4, ndw, dtype=torch.float32, device=dev)
@@ -233,7 +234,20 @@ def main():
             wide.append({"d": dw, "n_docs": ndw, "ms": round(w, 4), "TFLOP_per_s": round(fl / (a * 1e-3) / 1e12, 1),
                          "mfma_frac": round(fl / (a * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4)})
             del Qw, Dw, sw
-        extra.append({"leg": "wide_d", "workload": "N_q=4, L_q=L_d=1024, bf16, d=256 (B=2000) and d=512 (B=1000)", "results": wide})
+        # the shape of the paper's split-d table: one query page against 128 document pages
+        small = []
+        for dw in (768, 1024, 2048):
+            Qw = W.unit_rows((1, 1024, dw), "bf16", 93, dev)
+            Dw = W.unit_rows((128, 1024, dw), "bf16", 94, dev)
+            sw = torch.empty(1, 128, dtype=torch.float32, device=dev)
+            w, a, m, mn = time_launches(lambda: M.maxsim_forward(Qw, Dw, scores=sw), 20, 5)
+            small.append({"d": dw, "ms": round(w, 4)})
+            del Qw, Dw, sw
+        extra.append({"leg": "wide_d", "workload": "N_q=4, L_q=L_d=1024, bf16, d=256 .. 2048 at about 2 GB of documents each; "
+                                                   "and B=128, N_q=1 (the paper's split-d table)",
+                      "results": wide, "b128_single_query": small,
+                      "paper_context": {"split_d_ms_A100": {"768": 2.43, "1024": 2.60, "2048": 4.91},
+                                        "split_d_ms_H100": {"768": 0.76, "1024": 1.07, "2048": 2.06}}})
 
     if "c3" in legs or "c3_host" in legs:
         nq3, nd3, l3 = 4, 10_000, 1024

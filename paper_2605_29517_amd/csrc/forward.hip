@@ -119,6 +119,10 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
         w = 8;
         shape = 80 + wave_blocks;
     }
+    // a ragged corpus scored by many queries of one block: 32-row windows over the packed rows (no padded tiles
+    // at the ends of documents)
+    if (ragged && !am && ncb == 4 && p.bpq == 1 && total_blocks > 16)
+        shape = 90;
     const int group_blocks = w * wave_blocks;
     if (p.bpq <= group_blocks) {
         p.qpg = group_blocks / p.bpq;

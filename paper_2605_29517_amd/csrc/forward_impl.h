@@ -24,6 +24,8 @@
 #pragma once
 #include "common.h"
 
+#include <type_traits>
+
 namespace maxsim {
 namespace {
 
@@ -603,6 +605,344 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 }
 
 // ---------------------------------------------------------------------------------------
+// packed-window kernel: the tile kernel for ragged corpora and queries of one column block
+// ---------------------------------------------------------------------------------------
+//
+// With documents of 64-300 tokens a sixth of the 32-row tiles is the ragged end of a document, and
+// half of such a tile is padding.  Here a 32-row window may hold the last rows of document A and, from
+// the next multiple of 8 rows on, the first rows of the next (non-empty) document B; it is cut short
+// only where a third document would begin.  The MFMAs are the same.  The boundary sits on a multiple of
+// 8 rows because the 32x32 result keeps rows 8q .. 8q+7 in accumulator registers 4q .. 4q+3 of every
+// lane: a group of four registers then belongs to one document in all lanes, and a window with a boundary
+// folds each group into A's or B's maximum by a wavefront-uniform choice (no per-lane masks).  Such a
+// window finishes A and carries B's maximum on.  Everything else (rotating LDS buffers, pinned pipeline)
+// is fwd_tile_kernel's.  Queries have one column block here (L_q <= 32), so a wavefront's lane writes a
+// score directly and no partial sums are combined.
+
+struct WinIter {
+    int doc, doc_end; // document that owns the window's first row; end of the run
+    int row0;         // packed row of the window's first token
+    int rem;          // tokens of `doc` from row0 on (> 0 while the iterator is valid)
+    int end;          // packed row one past `doc`
+    int nxt;          // offsets[doc + 2], unclamped, fetched while `doc` is walked
+};
+
+struct Window {
+    int n_a;   // rows of document A = it.doc
+    int pa;    // window row at which B starts: n_a rounded up to a multiple of 8 (rows n_a .. pa-1 repeat A's last)
+    int n_b;   // rows of document B (0: no boundary inside the window)
+    int doc_b; // next non-empty document (doc_end if there is none); only known when A ends in the window
+    int len_b, end_b;
+    bool fin_a, fin_b; // A / B end inside this window
+};
+
+__device__ __forceinline__ bool win_valid(const WinIter &it) { return it.doc < it.doc_end; }
+
+// First non-empty document after it.doc within the run: d (doc_end if none) and its end e.  Offsets are
+// forced into [previous end, T], so malformed offsets give wrong scores but no address outside D.
+// The common case costs no memory access (it.nxt was fetched ahead); only empty documents take the loop,
+// whose loads are made scalar values by hand so that the state stays in scalar registers.
+__device__ __forceinline__ void win_find_next(const WinIter &it, const FwdParams &p, OffsetsPtr off, int &d, int &e)
+{
+    const int t_all = (int)p.total_tokens;
+    d = it.doc + 1;
+    e = min(max(it.nxt, it.end), t_all); // offsets[d + 1]
+    if (d < it.doc_end && e == it.end) {
+        do {
+            ++d;
+            if (d >= it.doc_end)
+                break;
+            const int raw = __builtin_amdgcn_readfirstlane(p.offsets[d + 1]);
+            e = min(max(raw, it.end), t_all);
+        } while (e == it.end);
+    }
+    if (d > it.doc_end)
+        d = it.doc_end;
+}
+
+// Makes d (with end e, `used` of its rows already consumed) the current document; no branch around the
+// read of the offset after next, so that it stays a scalar load
+__device__ __forceinline__ void win_enter(WinIter &it, const FwdParams &p, OffsetsPtr off, int d, int e, int used)
+{
+    const bool ok = d < it.doc_end;
+    it.doc = d;
+    it.nxt = it_offset(off, p, d + 2);
+    it.rem = ok ? e - it.end - used : 0;
+    it.end = ok ? e : it.end;
+}
+
+__device__ __forceinline__ void win_init(WinIter &it, const FwdParams &p, OffsetsPtr off, int doc0, int doc1)
+{
+    it.doc = doc0 - 1; // a virtual empty document before the run: its successor is the first real one
+    it.doc_end = doc1;
+    it.rem = 0;
+    it.end = min(max(it_offset(off, p, doc0), 0), (int)p.total_tokens);
+    it.row0 = it.end;
+    it.nxt = it_offset(off, p, doc0 + 1);
+    int d, e;
+    win_find_next(it, p, off, d, e);
+    win_enter(it, p, off, d, e, 0);
+}
+
+__device__ __forceinline__ Window win_describe(const WinIter &it, const FwdParams &p, OffsetsPtr off)
+{
+    Window w;
+    w.n_a = min(TILE_ROWS, it.rem);
+    w.fin_a = w.n_a == it.rem;
+    w.pa = (w.n_a + 7) & ~7;
+    w.n_b = 0;
+    w.doc_b = it.doc_end;
+    w.len_b = 0;
+    w.end_b = it.end;
+    w.fin_b = false;
+    if (w.fin_a) {
+        win_find_next(it, p, off, w.doc_b, w.end_b);
+        if (w.doc_b < it.doc_end) {
+            w.len_b = w.end_b - it.end;
+            w.n_b = min(w.len_b, TILE_ROWS - w.pa);
+            w.fin_b = w.n_b > 0 && w.n_b == w.len_b;
+        }
+    }
+    return w;
+}
+
+__device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const FwdParams &p, OffsetsPtr off)
+{
+    it.row0 += w.n_a + w.n_b;
+    if (!w.fin_a) {
+        it.rem -= TILE_ROWS;
+        return;
+    }
+    win_enter(it, p, off, w.doc_b, w.end_b, w.n_b);
+    if (win_valid(it) && it.rem == 0) { // B lay inside the window whole: on to the document after it
+        int d, e;
+        win_find_next(it, p, off, d, e);
+        win_enter(it, p, off, d, e, 0);
+    }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPtr off)
+{
+    using TR = Traits<DT>;
+    using LT = LdsTile<DT>;
+    constexpr int NU = TR::NU;
+    constexpr int W = 8, NCB = 4, NT = W * 64;
+    static_assert(NU <= 8, "the operand prefetch needs rows of at most 256 bytes");
+    constexpr int CPT = (LT::CHUNKS + NT - 1) / NT;
+    static_assert(LT::CHUNKS % NT == 0 || LT::CHUNKS < NT, "tile must split evenly over the workgroup");
+    const bool copies = LT::CHUNKS >= NT || (int)threadIdx.x < LT::CHUNKS;
+    constexpr int CPR = TR::ROW_BYTES / 16;
+    constexpr int GROUP_BLOCKS = W * NCB;
+
+    __shared__ __attribute__((aligned(16))) char lds_tile[3 * LT::BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int rho = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int n_wg = gridDim.x;
+    int v = blockIdx.x;
+    if ((n_wg & 7) == 0)
+        v = (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3);
+    const int group = v % p.n_groups;
+    const int chunk = v / p.n_groups;
+
+    int64_t doc0_, doc1_;
+    chunk_doc_range(p, chunk, doc0_, doc1_);
+    if (doc0_ >= doc1_)
+        return;
+    const int doc0 = (int)doc0_, doc1 = (int)doc1_;
+    if (group == 0)
+        write_empty_docs(p, doc0, doc1, tid, NT);
+
+    // this thread's share of a tile copy: chunk ch = tid + i * NT -> (row, 16-byte column); recomputed where it
+    // is used (a handful of shifts) rather than kept in registers, which are all taken
+    auto cp_row = [&](int i) { return (tid + i * NT) / CPR; };
+    auto cp_goff = [&](int i) { return ((tid + i * NT) % CPR) * 16; };
+    auto cp_loff = [&](int i) { return ((tid + i * NT) / CPR) * LT::ROW_STRIDE + ((tid + i * NT) % CPR) * 16; };
+    const int a_off = rho * LT::ROW_STRIDE + h * 16;
+
+    // one column block = one query: blocks [gb0, gb0 + nb) of this group
+    const int gb0 = group * GROUP_BLOCKS;
+    const int nb = min(GROUP_BLOCKS, p.n_q - gb0);
+    uint4 qf[NCB][NU];
+    bool col_valid[NCB];
+    float m[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        int lb = w * NCB + cb;
+        load_q_block<DT>(p, gb0 + lb, rho, h, qf[cb], col_valid[cb]);
+        col_valid[cb] = col_valid[cb] && lb < nb;
+        m[cb] = neg_inf();
+    }
+    const bool wave_active = w * NCB < nb;
+
+    WinIter li, ci;
+    win_init(li, p, off, doc0, doc1);
+    ci = li;
+    if (!win_valid(ci))
+        return;
+
+    uint4 g[CPT];
+    bool g_has = false;
+    auto gload = [&]() {
+        g_has = win_valid(li);
+        if (!g_has)
+            return;
+        const Window lw = win_describe(li, p, off);
+        if (copies) {
+            // window row i holds A's row min(i, n_a - 1) below pa and B's row min(i - pa, n_b - 1) from pa on
+            // (without a B that is A's last row again); A and B are neighbours in the packed corpus
+            const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int wr = cp_row(i);
+                const int row = wr < lw.pa ? min(wr, lw.n_a - 1) : lw.n_a + min(wr - lw.pa, lw.n_b - 1);
+                g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff(i));
+            }
+        }
+        win_advance(li, lw, p, off);
+    };
+    auto lstore = [&](int buf_off) {
+        if (!g_has || !copies)
+            return;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i)
+            *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff(i)]) = g[i];
+    };
+
+    int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
+    gload();
+    lstore(o_cur);
+    gload();
+    lstore(o_nxt);
+    gload();
+    __syncthreads();
+    // One operand set: during the LAST chain of a window every operand chunk is replaced, right after the
+    // MFMA that used it last, by the next window's (the second set of fwd_tile_kernel would not fit beside
+    // the two maxima of a boundary window).
+    uint4 ac[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+        ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
+
+    // BND: the window holds rows of two documents
+    auto stage = [&](auto bnd_tag, const Window &cw) {
+        constexpr bool BND = decltype(bnd_tag)::value;
+        constexpr int LAG = NU >= 4 ? 2 : NU / 2;
+        float mb[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+            mb[cb] = neg_inf();
+        // part u (of NU) of folding a result tile; nothing in the first LAG steps (see fold_step)
+        auto fold = [&](const f32x16 &acc, int u, float &ma, float &mbv) {
+            if (u < LAG)
+                return;
+            if (BND) { // register groups 4q .. 4q+3 (rows 8q .. 8q+7) go to A below the boundary, to B from it on
+                const int q0 = 4 * (u - LAG) / (NU - LAG), q1 = 4 * (u - LAG + 1) / (NU - LAG);
+#pragma unroll
+                for (int q = q0; q < q1; ++q) {
+                    const float qm = fmaxf(fmaxf(fmaxf(acc[4 * q], acc[4 * q + 1]), acc[4 * q + 2]), acc[4 * q + 3]);
+                    const bool in_a = 8 * q < cw.pa; // the same in every lane
+                    ma = fmaxf(ma, in_a ? qm : neg_inf());
+                    mbv = fmaxf(mbv, in_a ? neg_inf() : qm);
+                }
+            } else {
+                const int lo = 2 * (8 * (u - LAG) / (NU - LAG)), hi = 2 * (8 * (u - LAG + 1) / (NU - LAG));
+#pragma unroll
+                for (int r = lo; r < hi; r += 2)
+                    ma = fmaxf(fmaxf(ma, acc[r]), acc[r + 1]);
+            }
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 acc[NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[cb][r] = 0.0f;
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                TR::mma(ac[u], qf[cb][u], acc[cb]);
+                if (cb == NCB - 1)
+                    ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_nxt + a_off + u * 32]);
+                if (cb == 0) {
+                    if (u == NU - 1) {
+                        lstore(o_wr);
+                        gload();
+                    }
+                } else {
+                    fold(acc[cb - 1], u, m[cb - 1], mb[cb - 1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NU; ++u)
+            fold(acc[NCB - 1], u, m[NCB - 1], mb[NCB - 1]);
+
+        if (cw.fin_a) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                int lb = w * NCB + cb;
+                float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, ci.doc, 0, rho, h);
+                if (lane == 0 && lb < nb)
+                    p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
+                m[cb] = BND ? mb[cb] : neg_inf();
+            }
+            if (BND && cw.fin_b) {
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+                    int lb = w * NCB + cb;
+                    float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, cw.doc_b, 0, rho, h);
+                    if (lane == 0 && lb < nb)
+                        p.scores[(int64_t)(gb0 + lb) * p.ld + cw.doc_b] = sum;
+                    m[cb] = neg_inf();
+                }
+            }
+        }
+        win_advance(ci, cw, p, off);
+        __syncthreads();
+        int t = o_cur;
+        o_cur = o_nxt;
+        o_nxt = o_wr;
+        o_wr = t;
+    };
+
+    if (!wave_active) {
+        // fewer than 32 queries in this group: the wavefront only helps moving tiles (same barriers as the others)
+        while (win_valid(ci)) {
+            const Window cw = win_describe(ci, p, off);
+            lstore(o_wr);
+            gload();
+            win_advance(ci, cw, p, off);
+            __syncthreads();
+            int t = o_cur;
+            o_cur = o_nxt;
+            o_nxt = o_wr;
+            o_wr = t;
+        }
+    } else {
+        // runs of plain windows, each ended by one boundary window
+        Window cw = win_describe(ci, p, off);
+        for (;;) {
+            while (cw.n_b == 0) {
+                stage(std::false_type{}, cw);
+                if (!win_valid(ci))
+                    return;
+                cw = win_describe(ci, p, off);
+            }
+            stage(std::true_type{}, cw);
+            if (!win_valid(ci))
+                return;
+            cw = win_describe(ci, p, off);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // host-side launchers (called from the C ABI)
 // ---------------------------------------------------------------------------------------
 
@@ -617,6 +957,13 @@ template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
 static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
 {
     hipLaunchKernelGGL((fwd_tile_kernel<DT, W, NCB, ARGMAX, PFD>), dim3(grid), dim3(W * 64), 0, stream, p, p.offsets);
+    return hipGetLastError();
+}
+
+template <int DT>
+static hipError_t launch_pack(const FwdParams &p, int grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL((fwd_pack_kernel<DT>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 
@@ -646,6 +993,10 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
             return launch_tile<DT, 8, 1, ARGMAX, 6>(p, grid, s);
         if (w == 82)
             return launch_tile<DT, 8, 2, ARGMAX, 3>(p, grid, s);
+        if constexpr (!ARGMAX) {
+            if (w == 90) // ragged corpus, queries of one block: windows over the packed rows
+                return launch_pack<DT>(p, grid, s);
+        }
     }
     switch (w) {
     case 1: return launch_tile<DT, 1, NCB, ARGMAX>(p, grid, s);

@@ -154,3 +154,36 @@ def test_ragged_split_d(n_q, l_q, dtype, d):
     Dp = W.unit_rows((int(lens.sum()), d), dtype, 91, DEV)
     Q = W.unit_rows((n_q, l_q, d), dtype, 92, DEV)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, True, RTOL_F32 if dtype == "f32" else RTOL_16)
+
+
+# Ragged corpora scored by more than 16 queries of one column block take 32-row windows over the packed rows (a window
+# may hold the end of one document and the start of the next).  Length mixes: runs of tiny documents (several
+# boundaries close together, a document that lies inside one window whole), empty documents at the start, in a row
+# and at the end, lengths around the window size, and long documents.
+PACK_LENGTHS = {
+    "tiny": [1, 1, 1, 2, 1, 3, 1, 1, 5, 1, 1, 1, 40, 1, 1],
+    "empties": [0, 0, 7, 0, 33, 0, 0, 0, 31, 1, 0, 64, 0],
+    "window": [32, 32, 31, 33, 1, 63, 64, 65, 32, 16, 16, 16, 16],
+    "long": [300, 64, 129, 5, 700, 31, 257],
+}
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("f32", 64)])
+@pytest.mark.parametrize("n_q,l_q", [(17, 32), (40, 20), (64, 32), (33, 1)])
+@pytest.mark.parametrize("mix", sorted(PACK_LENGTHS))
+def test_ragged_packed_windows(mix, n_q, l_q, dtype, d):
+    lens = np.asarray(PACK_LENGTHS[mix] * 3)
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.unit_rows((int(lens.sum()), d), dtype, 101, DEV)
+    Q = W.unit_rows((n_q, l_q, d), dtype, 102, DEV)
+    forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, False, RTOL_F32 if dtype == "f32" else RTOL_16)
+
+
+def test_ragged_packed_windows_many_chunks():
+    # enough documents that every workgroup gets its own chunk, with chunk borders inside runs of short documents
+    rng = np.random.default_rng(7)
+    lens = rng.integers(0, 90, size=6000)
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.unit_rows((int(lens.sum()), 128), "f16", 103, DEV)
+    Q = W.unit_rows((48, 32, 128), "f16", 104, DEV)
+    forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, False, RTOL_16)

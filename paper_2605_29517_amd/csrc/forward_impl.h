@@ -326,7 +326,8 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
 //     issues the global loads of the tile after that, so no memory latency is exposed between
 //     tiles: three LDS buffers rotate (being computed / prefetched into registers / being
 //     written), one barrier per tile.  (The fp32 and the argmax variants have no registers
-//     left for the second operand set; they read the current tile's operands at its start.)
+//     left for the second operand set; there each operand chunk is replaced by the next tile's
+//     right after its last MFMA, during the last chain of the tile.)
 //   * with one or two column blocks per wavefront a tile takes too little time for a load issued
 //     one tile ahead to have arrived: PFD tiles are then in flight in a ring of registers.
 template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>
@@ -475,8 +476,14 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
             }
         }
         __syncthreads();
+        // a wavefront with a single column block uses every operand chunk once: a ring of four
+        // registers, read three steps ahead, replaces the full operand set (the argmax variant with one block of 256-byte rows per wavefront)
+        constexpr bool RING = !PF && NCB == 1 && NU >= 8;
+        // no registers for a second operand set (fp32, argmax): each chunk is replaced by the next tile's
+        // right after its last MFMA, during the last chain
+        constexpr bool INPLACE = !PF && !RING;
         uint4 a0[NU], a1[PF ? NU : 1]; // (a0 stays unused when the operand ring is in use)
-        if (PF) {
+        if (PF || INPLACE) {
 #pragma unroll
             for (int u = 0; u < NU; ++u)
                 a0[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
@@ -484,9 +491,6 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
         int par = 0;
 
         // one tile: operands in `ac`; the next tile's operands are read into `an` on the way
-        // a wavefront with a single column block uses every operand chunk once: a ring of four
-        // registers, read three steps ahead, replaces the full operand set (the argmax variant with one block of 256-byte rows per wavefront)
-        constexpr bool RING = !PF && NCB == 1 && NU >= 8;
         auto stage = [&](uint4(&ac)[NU], uint4(&an)[PF ? NU : 1]) {
             const int fin_doc = (ci.t0 + TILE_ROWS >= ci.len) ? ci.doc : -1; // last tile of its document?
             uint4 ring[4];
@@ -494,10 +498,6 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 #pragma unroll
                 for (int u = 0; u < 3; ++u)
                     ring[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
-            } else if (!PF) {
-#pragma unroll
-                for (int u = 0; u < NU; ++u)
-                    ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
             }
             const bool first = ci.t0 == 0;
 #pragma unroll
@@ -520,6 +520,8 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                         TR::mma(ring[u & 3], qf[cb][u], acc[cb]);
                     } else {
                         TR::mma(ac[u], qf[cb][u], acc[cb]);
+                        if (INPLACE && cb == NCB - 1)
+                            ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_nxt + a_off + u * 32]);
                     }
                     if (cb == 0) {
                         if (PF)

@@ -121,8 +121,14 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     }
     // a ragged corpus scored by many queries of one block: 32-row windows over the packed rows (no padded tiles
     // at the ends of documents)
-    if (ragged && !am && ncb == 4 && p.bpq == 1 && total_blocks > 16)
-        shape = 90;
+    if (ragged && !am && ncb == 4 && p.bpq == 1 && total_blocks > 16) {
+        // as many workgroups per chunk as 32 queries each would need, then 3 or 4 queries per wavefront so that the
+        // queries are spread evenly (48 queries: two workgroups of 24 rather than 32 + 16)
+        const int64_t groups = (total_blocks + 31) / 32;
+        const int64_t per_group = (total_blocks + groups - 1) / groups;
+        wave_blocks = per_group <= 24 ? 3 : 4;
+        shape = 90 + wave_blocks;
+    }
     const int group_blocks = w * wave_blocks;
     if (p.bpq <= group_blocks) {
         p.qpg = group_blocks / p.bpq;

@@ -723,13 +723,14 @@ __device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const 
     }
 }
 
-template <int DT>
+// NCB: column blocks (queries) per wavefront, 3 or 4: a workgroup holds 24 or 32 queries
+template <int DT, int NCB>
 __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
     constexpr int NU = TR::NU;
-    constexpr int W = 8, NCB = 4, NT = W * 64;
+    constexpr int W = 8, NT = W * 64;
     static_assert(NU <= 8, "the operand prefetch needs rows of at most 256 bytes");
     constexpr int CPT = (LT::CHUNKS + NT - 1) / NT;
     static_assert(LT::CHUNKS % NT == 0 || LT::CHUNKS < NT, "tile must split evenly over the workgroup");
@@ -962,10 +963,10 @@ static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int DT>
+template <int DT, int NCB>
 static hipError_t launch_pack(const FwdParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_pack_kernel<DT>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
+    hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 
@@ -996,8 +997,10 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
         if (w == 82)
             return launch_tile<DT, 8, 2, ARGMAX, 3>(p, grid, s);
         if constexpr (!ARGMAX) {
-            if (w == 90) // ragged corpus, queries of one block: windows over the packed rows
-                return launch_pack<DT>(p, grid, s);
+            if (w == 93) // ragged corpus, queries of one block: windows over the packed rows; 24 or 32 queries per workgroup
+                return launch_pack<DT, 3>(p, grid, s);
+            if (w == 94)
+                return launch_pack<DT, 4>(p, grid, s);
         }
     }
     switch (w) {

@@ -161,8 +161,14 @@ template <int DT, int NCB, bool ARGMAX> struct StreamState {
     int idx[NCB];
 };
 
+// The position of a tile: first packed row of its document, the document's length, first row of the tile
+struct TilePos {
+    int64_t start;
+    int32_t len, t0;
+};
+
 template <int DT>
-__device__ __forceinline__ void stream_load_tile(const FwdParams &p, const Cursor &c, int rho, int h,
+__device__ __forceinline__ void stream_load_tile(const FwdParams &p, const TilePos &c, int rho, int h,
                                                  uint4 (&a)[Traits<DT>::NU])
 {
     using TR = Traits<DT>;
@@ -259,19 +265,28 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p, OffsetsPtr
     if (!pc.valid)
         return;
     uint4 a0[TR::NU], a1[TR::NU];
-    stream_load_tile<DT>(p, pc, rho, h, a0);
+    TilePos lp = {pc.start, pc.len, pc.t0}; // where the prefetch reads: pc while it is valid, else the last valid tile
+    auto follow = [&]() { // (field by field: a select between whole cursors would put them into memory)
+        lp.start = pc.valid ? pc.start : lp.start;
+        lp.len = pc.valid ? pc.len : lp.len;
+        lp.t0 = pc.valid ? pc.t0 : lp.t0;
+    };
+    stream_load_tile<DT>(p, lp, rho, h, a0);
     Cursor cc = pc;
+    // The prefetch is issued without a condition: past the end of the run the last tile is loaded once more
+    // (in bounds, never used).  With `if (pc.valid)` around the loads the compiler has to assume, where the two
+    // paths meet, that no load was issued, and makes every MFMA wait for the tile that was only just requested.
     cursor_next_tile(pc, p, off);
     for (;;) {
-        if (pc.valid)
-            stream_load_tile<DT>(p, pc, rho, h, a1);
+        follow();
+        stream_load_tile<DT>(p, lp, rho, h, a1);
         stream_compute<DT, NCB, ARGMAX>(p, cc, st, a0, gb0, lane, rho, h);
         cc = pc;
         if (!cc.valid)
             break;
         cursor_next_tile(pc, p, off);
-        if (pc.valid)
-            stream_load_tile<DT>(p, pc, rho, h, a0);
+        follow();
+        stream_load_tile<DT>(p, lp, rho, h, a0);
         stream_compute<DT, NCB, ARGMAX>(p, cc, st, a1, gb0, lane, rho, h);
         cc = pc;
         if (!cc.valid)

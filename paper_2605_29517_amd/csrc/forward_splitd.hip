@@ -185,29 +185,37 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
         };
 
         int o_cur = 0, o_nxt = SD_BUF, o_wr = 2 * SD_BUF;
-        // slabs 0 and 1 go to LDS, slabs 2 and 3 stay in flight
+        // slabs 0 and 1 go to LDS, slabs 2 and 3 stay in flight.  The order of the loads is pinned: the wait
+        // counts of the main loop are derived from the order in which the loop is entered, and if the compiler
+        // moves the last two groups of loads the loop waits for loads it has only just issued.
         gaddr();
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             gload1(g0, k);
+        __builtin_amdgcn_sched_barrier(0);
         gaddr();
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             gload1(g1, k);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             lstore1(g0, k, o_cur);
         gaddr();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             gload1(g0, k);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             lstore1(g1, k, o_nxt);
         gaddr();
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < SD_NG; ++k)
             gload1(g1, k);
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
 
         int par = 0;

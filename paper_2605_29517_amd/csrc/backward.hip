@@ -431,53 +431,69 @@ __global__ void __launch_bounds__(256) ce_grad_kernel(const float *s, int n, int
     }
 }
 
-// Loss: a single block (fixed summation order); 16 lanes per row, 64 rows at a time.  The scaled
-// scores of a lane are fetched once into registers (all loads of a row in flight together) when the
-// row has at most 16 * CE_KEEP columns; wider rows are re-read from memory for each of the three sweeps.
-constexpr int CE_KEEP = 32;
-
+// Loss: a single block (fixed summation order); 16 lanes per row, 64 rows at a time.  When a row has at most
+// 16 * KEEP columns (KEEP = 16 or 32) the scaled scores of a lane live in registers, and the loads of two to four
+// rows are issued together before any of them is reduced: the kernel is a chain of memory latencies, not
+// of arithmetic.  Wider rows (KEEP = 0) are re-read from memory for each of the sweeps.
+template <int KEEP>
 __global__ void __launch_bounds__(1024) ce_loss_kernel(const float *s, int n, int b, float inv_tau, float *loss)
 {
     __shared__ float part[64];
     const int sub = threadIdx.x & 15;
     const int slot = threadIdx.x >> 4;
-    const bool keep = b <= 16 * CE_KEEP;
     float local = 0.0f;
-    for (int i = slot; i < n; i += 64) {
-        const float *row = s + (int64_t)i * b;
-        float v[CE_KEEP];
-        if (keep) {
+    if constexpr (KEEP > 0) {
+        constexpr int ROWS = 64 / KEEP; // rows of a slot in flight together (64 registers)
+        for (int i0 = slot; i0 < n; i0 += 64 * ROWS) {
+            float v[ROWS][KEEP];
 #pragma unroll
-            for (int k = 0; k < CE_KEEP; ++k) {
-                int j = sub + 16 * k;
-                v[k] = j < b ? scaled(row[j], inv_tau) : neg_inf();
+            for (int r = 0; r < ROWS; ++r) {
+                const int i = i0 + 64 * r;
+                const float *row = s + (int64_t)(i < n ? i : i0) * b;
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k) {
+                    const int j = sub + 16 * k;
+                    v[r][k] = j < b ? scaled(row[j], inv_tau) : neg_inf();
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int i = i0 + 64 * r;
+                float mx = neg_inf();
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k)
+                    mx = fmaxf(mx, v[r][k]);
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1)
+                    mx = fmaxf(mx, __shfl_xor(mx, o));
+                float z = 0.0f;
+#pragma unroll
+                for (int k = 0; k < KEEP; ++k)
+                    z += (sub + 16 * k < b) ? expf(v[r][k] - mx) : 0.0f; // same order as the sweep over memory
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1)
+                    z += __shfl_xor(z, o);
+                if (i < n)
+                    local += logf(z) + mx - scaled(s[(int64_t)i * b + i], inv_tau);
             }
         }
-        float mx = neg_inf();
-        if (keep) {
-#pragma unroll
-            for (int k = 0; k < CE_KEEP; ++k)
-                mx = fmaxf(mx, v[k]);
-        } else {
+    } else {
+        for (int i = slot; i < n; i += 64) {
+            const float *row = s + (int64_t)i * b;
+            float mx = neg_inf();
             for (int j = sub; j < b; j += 16)
                 mx = fmaxf(mx, scaled(row[j], inv_tau));
-        }
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1)
-            mx = fmaxf(mx, __shfl_xor(mx, o));
-        float z = 0.0f;
-        if (keep) {
-#pragma unroll
-            for (int k = 0; k < CE_KEEP; ++k)
-                z += (sub + 16 * k < b) ? expf(v[k] - mx) : 0.0f; // same order as the sweep over memory
-        } else {
+            for (int o = 8; o > 0; o >>= 1)
+                mx = fmaxf(mx, __shfl_xor(mx, o));
+            float z = 0.0f;
             for (int j = sub; j < b; j += 16)
                 z += expf(scaled(row[j], inv_tau) - mx);
-        }
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1)
-            z += __shfl_xor(z, o);
-        local += logf(z) + mx - scaled(row[i], inv_tau);
+            for (int o = 8; o > 0; o >>= 1)
+                z += __shfl_xor(z, o);
+            local += logf(z) + mx - scaled(row[i], inv_tau);
+        }
     }
     if (sub == 0)
         part[slot] = local;
@@ -497,7 +513,12 @@ hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !loss)
         return e;
-    hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, stream, scores, n, b, 1.0f / tau, loss);
+    if (b <= 256)
+        hipLaunchKernelGGL(ce_loss_kernel<16>, dim3(1), dim3(1024), 0, stream, scores, n, b, 1.0f / tau, loss);
+    else if (b <= 512)
+        hipLaunchKernelGGL(ce_loss_kernel<32>, dim3(1), dim3(1024), 0, stream, scores, n, b, 1.0f / tau, loss);
+    else
+        hipLaunchKernelGGL(ce_loss_kernel<0>, dim3(1), dim3(1024), 0, stream, scores, n, b, 1.0f / tau, loss);
     return hipGetLastError();
 }
 

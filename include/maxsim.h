@@ -25,6 +25,10 @@
  *     other width streams both operands in slabs of the embedding dimension (the paper's inner loop
  *     over d).  Other widths must be zero-padded by the caller; they, and any width other than 128
  *     at the backward and int8 entry points, return MAXSIM_ERR_UNSUPPORTED.
+ *   - Two kernels use more than 64 KB of LDS (the float forward for the wide rows above and the int8
+ *     forward for corpora of 4096 documents or more); the library allows that once per device, at
+ *     the first such call, which therefore must not be made while `stream` is being captured into
+ *     a HIP graph.  Every later call may be captured.
  *   - L_q and L_d are arbitrary positive integers (no tile multiples needed).
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
  *   - Return value: MAXSIM_OK (0) or a negative error code; on error nothing

@@ -58,3 +58,41 @@ def test_training_step_replays_from_a_graph():
         torch.cuda.synchronize()
         for got, ref in zip((s, a, g, loss, dQ, dD, s8, s8b), want):
             assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
+
+
+def test_forward_variants_replay_from_a_graph():
+    """The packed-window kernel (ragged corpus, many short queries) and the slab kernel (wide rows, more than
+    64 KB of dynamic LDS) under capture, after one eager call each."""
+    lens = np.asarray([5, 0, 64, 33, 1, 1, 200, 31, 90] * 4)
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.unit_rows((int(lens.sum()), 128), "f16", 21, DEV)
+    Qs = W.unit_rows((40, 32, 128), "f16", 22, DEV)
+    Qw = W.unit_rows((2, 70, 768), "bf16", 23, DEV)
+    Dw = W.unit_rows((9, 150, 768), "bf16", 24, DEV)
+    s1 = torch.empty(40, len(lens), device=DEV)
+    s2 = torch.empty(2, 9, device=DEV)
+    a2 = torch.empty(2, 9, 70, dtype=torch.int32, device=DEV)
+
+    def step():
+        M.maxsim_forward_ragged(Qs, Dp, off, scores=s1)
+        M.maxsim_forward(Qw, Dw, scores=s2, argmax=a2)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (s1, s2, a2)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        s1.fill_(0), s2.fill_(0), a2.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((s1, s2, a2), want):
+            assert torch.equal(got, ref), "replay %d differs from the eager result" % rep

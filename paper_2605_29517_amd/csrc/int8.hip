@@ -276,6 +276,136 @@ constexpr int I8D_WAVES = 8;
 constexpr int I8D_MAX_BLOCKS = 32;                       // column blocks per group (1024 query tokens)
 constexpr int I8D_QSTRIDE = I8_ROW_BYTES + 16;           // padded LDS row of a query token
 
+// The token scales of a tile, from "one per lane" (lane rho holds row rho's scale) to the 16 rows of this
+// lane's accumulator registers, through 512 bytes of LDS private to the wavefront.
+__device__ __forceinline__ void i8d_tile_scales(float *w_scale, float *w_bias, float s_n, int rho, int h,
+                                                float (&sc)[16], float (&bi)[16])
+{
+    if (h == 0) {
+        w_scale[rho] = s_n;
+        w_bias[rho] = s_n * -8388608.0f;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        float4 s4 = *reinterpret_cast<const float4 *>(&w_scale[r4 * 8 + h * 4]);
+        float4 b4 = *reinterpret_cast<const float4 *>(&w_bias[r4 * 8 + h * 4]);
+        sc[r4 * 4 + 0] = s4.x;
+        sc[r4 * 4 + 1] = s4.y;
+        sc[r4 * 4 + 2] = s4.z;
+        sc[r4 * 4 + 3] = s4.w;
+        bi[r4 * 4 + 0] = b4.x;
+        bi[r4 * 4 + 1] = b4.y;
+        bi[r4 * 4 + 2] = b4.z;
+        bi[r4 * 4 + 3] = b4.w;
+    }
+}
+
+#ifndef I8D_LAG_STEPS
+#define I8D_LAG_STEPS 2
+#endif
+
+// One document tile (operands `a`, row scales sc / biases bi) against the NB column blocks in LDS, folded into
+// the running maxima m.  Step t: MFMA (t % 4) of block t / 4, the LDS read of the same chunk of the next block,
+// and a quarter of the epilogue of the block whose chain ended I8D_LAG steps ago (so that its results have long
+// left the matrix pipeline); three accumulators rotate.
+template <int NB>
+__device__ __forceinline__ void i8d_tile_blocks(const i32x4 (&a)[I8_NU], const float (&sc)[16], const float (&bi)[16],
+                                                const char *q_tile, int b_off, const i32x16 &seed, float (&m)[NB])
+{
+    i32x4 qb[2][I8_NU];
+#pragma unroll
+    for (int u = 0; u < I8_NU; ++u)
+        qb[0][u] = *reinterpret_cast<const i32x4 *>(q_tile + b_off + u * 32);
+    i32x16 acc[3];
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int I8D_LAG = I8D_LAG_STEPS;
+#pragma unroll
+    for (int t = 0; t < NB * I8_NU + I8_NU + I8D_LAG; ++t) {
+        const int blk = t / I8_NU, u = t % I8_NU;
+        if (blk < NB) {
+            acc[blk % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qb[blk & 1][u], u == 0 ? seed : acc[blk % 3], 0, 0, 0);
+            if (blk + 1 < NB)
+                qb[(blk + 1) & 1][u] = *reinterpret_cast<const i32x4 *>(
+                    q_tile + (blk + 1) * (BLOCK_COLS * I8D_QSTRIDE) + b_off + u * 32);
+        }
+        const int te = t - I8_NU - I8D_LAG; // epilogue step
+        if (te >= 0) {
+            const int eb = te / I8_NU, r = 4 * (te % I8_NU);
+            const i32x16 &e = acc[eb % 3];
+            float v0 = __builtin_fmaf(__int_as_float(e[r + 0]), sc[r + 0], bi[r + 0]);
+            float v1 = __builtin_fmaf(__int_as_float(e[r + 1]), sc[r + 1], bi[r + 1]);
+            float v2 = __builtin_fmaf(__int_as_float(e[r + 2]), sc[r + 2], bi[r + 2]);
+            float v3 = __builtin_fmaf(__int_as_float(e[r + 3]), sc[r + 3], bi[r + 3]);
+            float mm = m[eb];
+            mm = fmaxf(fmaxf(mm, v0), v1);
+            mm = fmaxf(fmaxf(mm, v2), v3);
+            m[eb] = mm;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// End of a document: mm[blk] is the maximum per query token (column rho of block blk; in lanes 0..31 and again
+// in lanes 32..63) in the halved-negatives form of the seeded accumulator.  Per query: one IEEE fp32 multiply
+// by the query scale per token, a lane-local fp64 sum over the query's blocks, one butterfly over the 32
+// columns, one rounding.
+template <int NB>
+__device__ __forceinline__ void i8d_finish(const I8Params &P, const float (&mmv)[NB], const float *q_scale, int nb,
+                                           int q_first, int doc, int lane, int rho)
+{
+    const FwdParams &p = P.f;
+    double dv = 0.0;
+    int iq = 0, j = 0; // block inside the query, query inside the group
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) {
+        if (blk >= nb)
+            continue;
+        float mm = mmv[blk];
+        mm = mm < 0.0f ? mm + mm : mm;                     // negative maxima were carried halved
+        float r = q_scale[blk * BLOCK_COLS + rho] * mm;    // one IEEE fp32 multiply per query token
+        dv += (iq * BLOCK_COLS + rho < p.l_q) ? (double)r : 0.0;
+        if (++iq == p.bpq) {
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1)
+                dv += __shfl_xor(dv, o);
+            if (lane == 0)
+                P.scores[(int64_t)(q_first + j) * p.ld + doc] = (float)dv;
+            dv = 0.0;
+            iq = 0;
+            ++j;
+        }
+    }
+}
+
+// Copies the group's query rows (padded) and scales (0 for padding columns) into LDS.
+template <int NB>
+__device__ __forceinline__ void i8d_load_queries(const I8Params &P, char *q_tile, float *q_scale, int gb0, int nb, int tid)
+{
+    const FwdParams &p = P.f;
+    for (int c = tid; c < NB * BLOCK_COLS * 8; c += I8D_WAVES * 64) { // 16-byte chunks of the group's query rows
+        int col = c >> 3, part = c & 7;
+        uint4 chunk = make_uint4(0, 0, 0, 0);
+        float qsv = 0.0f;
+        if (col < nb * BLOCK_COLS) {
+            int gb = gb0 + col / BLOCK_COLS;
+            int q = gb / p.bpq;
+            int tok = (gb % p.bpq) * BLOCK_COLS + col % BLOCK_COLS;
+            bool valid = tok < p.l_q;
+            if (!valid)
+                tok = p.l_q - 1;
+            const int64_t qrow = (int64_t)q * p.l_q + tok;
+            chunk = *reinterpret_cast<const uint4 *>(P.Q + qrow * I8_ROW_BYTES + part * 16);
+            qsv = valid ? P.qs[qrow] : 0.0f;
+        }
+        *reinterpret_cast<uint4 *>(q_tile + col * I8D_QSTRIDE + part * 16) = chunk;
+        if (part == 0)
+            q_scale[col] = qsv;
+    }
+}
+
 // NB: column blocks the tile loop walks over (the group's block count rounded up; the surplus
 // blocks multiply zero rows and are never looked at).
 template <int NB>
@@ -302,25 +432,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, 
     float *w_scale = q_scale + NB * BLOCK_COLS + w * 64;
     float *w_bias = w_scale + 32;
 
-    for (int c = tid; c < NB * BLOCK_COLS * 8; c += I8D_WAVES * 64) { // 16-byte chunks of the group's query rows
-        int col = c >> 3, part = c & 7;
-        uint4 chunk = make_uint4(0, 0, 0, 0);
-        float qsv = 0.0f;
-        if (col < nb * BLOCK_COLS) {
-            int gb = gb0 + col / BLOCK_COLS;
-            int q = gb / p.bpq;
-            int tok = (gb % p.bpq) * BLOCK_COLS + col % BLOCK_COLS;
-            bool valid = tok < p.l_q;
-            if (!valid)
-                tok = p.l_q - 1;
-            const int64_t qrow = (int64_t)q * p.l_q + tok;
-            chunk = *reinterpret_cast<const uint4 *>(P.Q + qrow * I8_ROW_BYTES + part * 16);
-            qsv = valid ? P.qs[qrow] : 0.0f;
-        }
-        *reinterpret_cast<uint4 *>(q_tile + col * I8D_QSTRIDE + part * 16) = chunk;
-        if (part == 0)
-            q_scale[col] = qsv;
-    }
+    i8d_load_queries<NB>(P, q_tile, q_scale, gb0, nb, tid);
     __syncthreads(); // the only barrier: from here on every wavefront is on its own
 
     int64_t doc0_, doc1_;
@@ -375,98 +487,173 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, 
 #pragma unroll
         for (int u = 0; u < I8_NU; ++u)
             a[u] = a_n[u];
-        if (h == 0) {
-            w_scale[rho] = s_n;
-            w_bias[rho] = s_n * -8388608.0f;
-        }
+        const float s_cur = s_n;
         gload(); // next tile, in flight during this one
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         float sc[16], bi[16];
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            float4 s4 = *reinterpret_cast<const float4 *>(&w_scale[r4 * 8 + h * 4]);
-            float4 b4 = *reinterpret_cast<const float4 *>(&w_bias[r4 * 8 + h * 4]);
-            sc[r4 * 4 + 0] = s4.x;
-            sc[r4 * 4 + 1] = s4.y;
-            sc[r4 * 4 + 2] = s4.z;
-            sc[r4 * 4 + 3] = s4.w;
-            bi[r4 * 4 + 0] = b4.x;
-            bi[r4 * 4 + 1] = b4.y;
-            bi[r4 * 4 + 2] = b4.z;
-            bi[r4 * 4 + 3] = b4.w;
-        }
+        i8d_tile_scales(w_scale, w_bias, s_cur, rho, h, sc, bi);
         if (ci.t0 == 0) {
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk)
                 m[blk] = neg_inf();
         }
 
-        i32x4 qb[2][I8_NU];
-#pragma unroll
-        for (int u = 0; u < I8_NU; ++u)
-            qb[0][u] = *reinterpret_cast<const i32x4 *>(q_tile + b_off + u * 32);
-        i32x16 acc[3];
-        __builtin_amdgcn_sched_barrier(0);
-        // step t: MFMA (t % 4) of block t / 4, the LDS read of the same chunk of the next block, and a
-        // quarter of the epilogue of the block whose chain ended I8D_LAG steps ago (so that its
-        // results have long left the matrix pipeline); three accumulators rotate
-#ifndef I8D_LAG_STEPS
-#define I8D_LAG_STEPS 2
-#endif
-        constexpr int I8D_LAG = I8D_LAG_STEPS;
-#pragma unroll
-        for (int t = 0; t < NB * I8_NU + I8_NU + I8D_LAG; ++t) {
-            const int blk = t / I8_NU, u = t % I8_NU;
-            if (blk < NB) {
-                acc[blk % 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], qb[blk & 1][u], u == 0 ? seed : acc[blk % 3], 0, 0, 0);
-                if (blk + 1 < NB)
-                    qb[(blk + 1) & 1][u] = *reinterpret_cast<const i32x4 *>(
-                        q_tile + (blk + 1) * (BLOCK_COLS * I8D_QSTRIDE) + b_off + u * 32);
-            }
-            const int te = t - I8_NU - I8D_LAG; // epilogue step
-            if (te >= 0) {
-                const int eb = te / I8_NU, r = 4 * (te % I8_NU);
-                const i32x16 &e = acc[eb % 3];
-                float v0 = __builtin_fmaf(__int_as_float(e[r + 0]), sc[r + 0], bi[r + 0]);
-                float v1 = __builtin_fmaf(__int_as_float(e[r + 1]), sc[r + 1], bi[r + 1]);
-                float v2 = __builtin_fmaf(__int_as_float(e[r + 2]), sc[r + 2], bi[r + 2]);
-                float v3 = __builtin_fmaf(__int_as_float(e[r + 3]), sc[r + 3], bi[r + 3]);
-                float mm = m[eb];
-                mm = fmaxf(fmaxf(mm, v0), v1);
-                mm = fmaxf(fmaxf(mm, v2), v3);
-                m[eb] = mm;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        i8d_tile_blocks<NB>(a, sc, bi, q_tile, b_off, seed, m);
 
         if (ci.t0 + TILE_ROWS >= ci.len) { // last tile of the document
-            // per query: lane-local fp64 sum over its blocks, then one butterfly over the 32 columns
-            double dv = 0.0;
-            int iq = 0, j = 0; // block inside the query, query inside the group
+            float mm[NB];
 #pragma unroll
-            for (int blk = 0; blk < NB; ++blk) {
-                if (blk >= nb)
-                    continue;
-                float mm = fmaxf(m[blk], __shfl_xor(m[blk], 32));
-                mm = mm < 0.0f ? mm + mm : mm;                     // negative maxima were carried halved
-                float r = q_scale[blk * BLOCK_COLS + rho] * mm;    // one IEEE fp32 multiply per query token
-                dv += (iq * BLOCK_COLS + rho < p.l_q) ? (double)r : 0.0;
-                if (++iq == p.bpq) {
-#pragma unroll
-                    for (int o = 16; o > 0; o >>= 1)
-                        dv += __shfl_xor(dv, o);
-                    if (lane == 0)
-                        P.scores[(int64_t)(q_first + j) * p.ld + ci.doc] = (float)dv;
-                    dv = 0.0;
-                    iq = 0;
-                    ++j;
-                }
-            }
+            for (int blk = 0; blk < NB; ++blk)
+                mm[blk] = fmaxf(m[blk], __shfl_xor(m[blk], 32));
+            i8d_finish<NB>(P, mm, q_scale, nb, q_first, ci.doc, lane, rho);
         }
         it_next(ci, p, off);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// the same for uniform corpora too small to give every wavefront documents of its own
+// ---------------------------------------------------------------------------------------
+// With a thousand long documents and a short query the corpus read is the cost, and a wavefront per document
+// would leave most of the chip idle.  Here a workgroup takes documents one after the other and its eight
+// wavefronts share each document's tiles (wavefront w the w-th eighth); the query tokens sit in LDS as above and
+// every wavefront still streams its tiles HBM -> registers, one tile ahead, across document borders.  At the end
+// of a document the eight partial maxima per query token meet in LDS (double-buffered, one barrier per
+// document) and one wavefront, a different one each time, finishes the score.  Built for up to 16 column
+// blocks (512 query tokens): beyond that the maxima of eight wavefronts no longer fit beside the queries in LDS.
+template <int NB>
+__global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_split_kernel(I8Params P)
+{
+    const FwdParams &p = P.f;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int rho = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int group = blockIdx.x % p.n_groups;
+    const int chunk = blockIdx.x / p.n_groups;
+    const int q_first = group * p.qpg;
+    const int nq = min(p.qpg, p.n_q - q_first);
+    const int gb0 = q_first * p.bpq;
+    const int nb = nq * p.bpq;
+
+    // LDS: query rows and scales, per wavefront 32 token scales and 32 biases, then the partial maxima
+    // comb[2][8 wavefronts][NB][32 columns]
+    char *q_tile = smem;
+    float *q_scale = reinterpret_cast<float *>(smem + NB * BLOCK_COLS * I8D_QSTRIDE);
+    float *w_scale = q_scale + NB * BLOCK_COLS + w * 64;
+    float *w_bias = w_scale + 32;
+    float *comb = q_scale + NB * BLOCK_COLS + I8D_WAVES * 64;
+    i8d_load_queries<NB>(P, q_tile, q_scale, gb0, nb, tid);
+    __syncthreads();
+
+    int64_t doc0_, doc1_;
+    chunk_doc_range(p, chunk, doc0_, doc1_);
+    if (doc0_ >= doc1_)
+        return;
+    const int doc0 = (int)doc0_, n_docs = (int)(doc1_ - doc0_);
+
+    // this wavefront's tiles of every document: [t_lo, t_lo + cnt)
+    const int n_tiles = (p.l_d + TILE_ROWS - 1) / TILE_ROWS;
+    const int t_lo = w * (n_tiles / I8D_WAVES) + min(w, n_tiles % I8D_WAVES);
+    const int cnt = n_tiles / I8D_WAVES + (w < n_tiles % I8D_WAVES ? 1 : 0);
+
+    // the loader walks (document, tile) pairs in order; past the end it stays on the last pair
+    i32x4 a_n[I8_NU];
+    float s_n = 0.0f;
+    int ld_doc = 0, ld_t = 0; // document (relative to doc0) and tile (relative to t_lo) of the next load
+    auto gload = [&]() {
+        if (cnt == 0)
+            return;
+        const int t0 = (t_lo + ld_t) * TILE_ROWS;
+        int row = p.l_d - t0 - 1; // rows past the document re-read its last token
+        row = rho < row ? rho : row;
+        const int64_t grow = (int64_t)(doc0 + ld_doc) * p.l_d + t0 + row;
+        const char *src = P.D + grow * I8_ROW_BYTES + h * 16;
+#pragma unroll
+        for (int u = 0; u < I8_NU; ++u)
+            a_n[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
+        s_n = P.ds[grow];
+        if (ld_t + 1 < cnt) {
+            ld_t += 1;
+        } else if (ld_doc + 1 < n_docs) {
+            ld_doc += 1;
+            ld_t = 0;
+        }
+    };
+    gload();
+
+    i32x16 seed;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int v = 0x4B000000;
+        asm volatile("" : "+v"(v));
+        seed[r] = v;
+    }
+    const int b_off = rho * I8D_QSTRIDE + h * 16;
+
+    int par = 0;
+    for (int d = 0; d < n_docs; ++d) {
+        float m[NB];
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk)
+            m[blk] = neg_inf();
+        for (int t = 0; t < cnt; ++t) {
+            i32x4 a[I8_NU];
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u)
+                a[u] = a_n[u];
+            const float s_cur = s_n;
+            gload();
+            float sc[16], bi[16];
+            i8d_tile_scales(w_scale, w_bias, s_cur, rho, h, sc, bi);
+            i8d_tile_blocks<NB>(a, sc, bi, q_tile, b_off, seed, m);
+        }
+        // partial maxima of this wavefront (the halved-negatives form keeps the order, so they can be compared
+        // as they are)
+        float *mine = comb + ((par * I8D_WAVES + w) * NB) * BLOCK_COLS;
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            float mm = fmaxf(m[blk], __shfl_xor(m[blk], 32));
+            if (h == 0)
+                mine[blk * BLOCK_COLS + rho] = mm;
+        }
+        __syncthreads();
+        if (w == (d & (I8D_WAVES - 1))) {
+            float mm[NB];
+#pragma unroll
+            for (int blk = 0; blk < NB; ++blk) {
+                float x = neg_inf();
+#pragma unroll
+                for (int ww = 0; ww < I8D_WAVES; ++ww)
+                    x = fmaxf(x, comb[((par * I8D_WAVES + ww) * NB + blk) * BLOCK_COLS + rho]);
+                mm[blk] = x;
+            }
+            i8d_finish<NB>(P, mm, q_scale, nb, q_first, doc0 + d, lane, rho);
+        }
+        par ^= 1;
+    }
+}
+
+template <int NB> static hipError_t launch_i8_split(const I8Params &P, int grid, hipStream_t s)
+{
+    const size_t lds = (size_t)NB * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float) +
+                       (size_t)2 * I8D_WAVES * NB * BLOCK_COLS * sizeof(float);
+    if (lds > 64 * 1024) { // to be allowed once per device (see launch_i8_doc)
+        static bool allowed[64] = {false};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+            return hipErrorInvalidDevice;
+        if (!allowed[dev]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_split_kernel<NB>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess)
+                return e;
+            allowed[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL((fwd_i8_split_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P);
+    return hipGetLastError();
 }
 
 template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStream_t s)
@@ -547,6 +734,31 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
         if (nb <= 16) return launch_i8_doc<16>(P, grid, stream);
         if (nb <= 24) return launch_i8_doc<24>(P, grid, stream);
         return launch_i8_doc<32>(P, grid, stream);
+    }
+
+    // Uniform corpora of long documents, up to 16 column blocks per query and one or two groups of 16: the
+    // wavefronts of a workgroup share each document (document-stationary like the kernel above, at any number
+    // of documents)
+    constexpr int SPLIT_BLOCKS = 16;
+    if (!offsets && p.bpq <= SPLIT_BLOCKS && total_blocks <= 2 * SPLIT_BLOCKS && l_d >= I8D_WAVES * TILE_ROWS) {
+        p.qpg = SPLIT_BLOCKS / p.bpq;
+        if (p.qpg > n_q)
+            p.qpg = n_q;
+        p.n_groups = (n_q + p.qpg - 1) / p.qpg;
+        const int nb = p.qpg * p.bpq;
+        // about four workgroups per CU while the queries are small, one when their LDS copy is large
+        int64_t n_chunks = ((int64_t)num_cu * (nb <= 4 ? 4 : 1) + p.n_groups - 1) / p.n_groups;
+        if (n_chunks > b)
+            n_chunks = b;
+        p.unit_per_chunk = (b + n_chunks - 1) / n_chunks;
+        n_chunks = (b + p.unit_per_chunk - 1) / p.unit_per_chunk;
+        p.n_chunks = (int)n_chunks;
+        const int grid = p.n_chunks * p.n_groups;
+        if (nb <= 1) return launch_i8_split<1>(P, grid, stream);
+        if (nb <= 2) return launch_i8_split<2>(P, grid, stream);
+        if (nb <= 4) return launch_i8_split<4>(P, grid, stream);
+        if (nb <= 8) return launch_i8_split<8>(P, grid, stream);
+        return launch_i8_split<16>(P, grid, stream);
     }
 
     int w = 8;

@@ -163,3 +163,31 @@ def test_forward_i8_tiny_huge_and_zero_scales(b):
     ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
     assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
     assert float(s[0, 1]) < 0
+
+
+# Uniform corpora of long documents (>= 256 tokens), queries of up to 16 column blocks (32 blocks in all) and fewer
+# than 4096 documents:
+# the wavefronts of a workgroup share each document's tiles and combine their maxima in LDS.
+@pytest.mark.parametrize("shape", [(1, 32, 50, 300), (2, 40, 37, 257), (1, 128, 20, 1024), (3, 32, 9, 256),
+                                   (8, 32, 5, 270), (1, 97, 1, 999), (2, 100, 600, 260), (1, 512, 12, 300), (2, 300, 9, 257),
+                                   (5, 100, 8, 260), (1, 200, 3, 1024)])
+def test_forward_i8_shared_documents_bit_exact(shape):
+    n_q, l_q, b, l_d = shape
+    g, o = quantised_case(n_q, l_q, b, l_d, 23)
+    s = M.maxsim_forward_i8(*g)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(*o)
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+
+
+def test_forward_i8_shared_documents_negative_maxima():
+    Q = torch.full((1, 33, 128), -127, dtype=torch.int8, device=DEV)
+    D = torch.full((30, 300, 128), 127, dtype=torch.int8, device=DEV)
+    D[1::2, 290] = -127       # one positive cell per odd document, in the last wavefront's share
+    qs = torch.rand(1, 33, device=DEV) + 0.5
+    ds = torch.rand(30, 300, device=DEV) + 0.01
+    s = M.maxsim_forward_i8(Q, qs, D, ds)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+    assert float(s[0, 0]) < 0 < float(s[0, 1])

@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--legs", default="c2_nq1,c2_i8,c2_train,c3,c3_host,wide_d,c4,c5,ceilings")
+    ap.add_argument("--legs", default="c1,c2_nq1,c2_i8,c2_train,c3,c3_host,wide_d,c4,c5,ceilings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-docs", type=int, default=4096, help="documents in the oracle's sample")
     args = ap.parse_args()
@@ -182,6 +182,19 @@ def main():
                       "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
                       "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 2, True), a, PEAK_HBM_GBS, "GB/s", "c2_nq1")})
         del s1
+    if "c1" in legs:
+        # config 1 (the parity case): 1 x 32 query tokens, 1000 x 128 document tokens, fp32 with argmax; 65.7 MB,
+        # timed cold (it would sit in the Infinity Cache otherwise); report only
+        Qt1, Dt1 = W.tiny_forward()
+        Qt1, Dt1 = Qt1.to(dev), Dt1.to(dev)
+        st1 = torch.empty(1, 1000, dtype=torch.float32, device=dev)
+        at1 = torch.empty(1, 1000, 32, dtype=torch.int32, device=dev)
+        w, a, m, mn = time_launches(lambda: M.maxsim_forward(Qt1, Dt1, scores=st1, argmax=at1), 50, 5, cold=True)
+        by1 = forward_bytes(1, 32, 1000 * 128, 1000, 4, False) + 1000 * 32 * 4
+        extra.append({"leg": "c1", "workload": "configs[0]: tiny forward with argmax, 1 x 32 x 128 fp32 query, 1000 x 128 x 128 fp32 corpus (cold)",
+                      "ms": round(w, 4), "docs_per_s": round(1000 / (w * 1e-3), 1),
+                      "roofline": roof("hbm", by1, a, PEAK_HBM_GBS, "GB/s", "c1")})
+        del Qt1, Dt1, st1, at1
     if "c2_i8" in legs:
         # the same ragged corpus quantised to int8 (offline), one query quantised on the fly: streaming regime
         D8p, dsp = M.maxsim_quantize_rows_i8(Dp)

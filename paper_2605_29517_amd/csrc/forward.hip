@@ -80,11 +80,18 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
         s_groups = 0;
 
     if (s_groups > 0) {
-        // one work chunk per group of wavefronts; enough chunks to oversubscribe the chip a few
-        // times, but no chunk smaller than about 2K tokens
+        // one work chunk per group of wavefronts; enough chunks to oversubscribe the chip a few times, but no
+        // chunk smaller than about 2K tokens -- unless that leaves wavefront slots empty (a small corpus is a chain
+        // of memory latencies per wavefront): then chunks go down to 128 tokens until every slot has one
         const int64_t tokens = ragged ? p.total_tokens : p.b * (int64_t)p.l_d;
         int64_t want = (int64_t)num_cu * 16 * 4 / s_groups;
         int64_t by_size = (tokens + 2047) / 2048;
+        const int64_t slots = (int64_t)num_cu * 16 / s_groups;
+        if (by_size < slots) {
+            by_size = (tokens + 127) / 128;
+            if (by_size > slots)
+                by_size = slots;
+        }
         int64_t n_chunks = want < by_size ? want : by_size;
         if (n_chunks > p.b)
             n_chunks = p.b;

@@ -655,16 +655,27 @@ struct Window {
 
 __device__ __forceinline__ bool win_valid(const WinIter &it) { return it.doc < it.doc_end; }
 
+// offsets[i] (i <= b), or i * l_d for a uniform corpus (UNI: a compile-time choice, so that the ragged case keeps
+// its branch-free scalar loads)
+template <bool UNI> __device__ __forceinline__ int win_offset(OffsetsPtr off, const FwdParams &p, int i)
+{
+    if constexpr (UNI)
+        return (i < p.b ? i : (int)p.b) * p.l_d;
+    else
+        return it_offset(off, p, i);
+}
+
 // First non-empty document after it.doc within the run: d (doc_end if none) and its end e.  Offsets are
 // forced into [previous end, T], so malformed offsets give wrong scores but no address outside D.
 // The common case costs no memory access (it.nxt was fetched ahead); only empty documents take the loop,
 // whose loads are made scalar values by hand so that the state stays in scalar registers.
+template <bool UNI>
 __device__ __forceinline__ void win_find_next(const WinIter &it, const FwdParams &p, OffsetsPtr off, int &d, int &e)
 {
     const int t_all = (int)p.total_tokens;
     d = it.doc + 1;
     e = min(max(it.nxt, it.end), t_all); // offsets[d + 1]
-    if (d < it.doc_end && e == it.end) {
+    if (!UNI && d < it.doc_end && e == it.end) {
         do {
             ++d;
             if (d >= it.doc_end)
@@ -679,28 +690,31 @@ __device__ __forceinline__ void win_find_next(const WinIter &it, const FwdParams
 
 // Makes d (with end e, `used` of its rows already consumed) the current document; no branch around the
 // read of the offset after next, so that it stays a scalar load
+template <bool UNI>
 __device__ __forceinline__ void win_enter(WinIter &it, const FwdParams &p, OffsetsPtr off, int d, int e, int used)
 {
     const bool ok = d < it.doc_end;
     it.doc = d;
-    it.nxt = it_offset(off, p, d + 2);
+    it.nxt = win_offset<UNI>(off, p, d + 2);
     it.rem = ok ? e - it.end - used : 0;
     it.end = ok ? e : it.end;
 }
 
+template <bool UNI>
 __device__ __forceinline__ void win_init(WinIter &it, const FwdParams &p, OffsetsPtr off, int doc0, int doc1)
 {
     it.doc = doc0 - 1; // a virtual empty document before the run: its successor is the first real one
     it.doc_end = doc1;
     it.rem = 0;
-    it.end = min(max(it_offset(off, p, doc0), 0), (int)p.total_tokens);
+    it.end = min(max(win_offset<UNI>(off, p, doc0), 0), (int)p.total_tokens);
     it.row0 = it.end;
-    it.nxt = it_offset(off, p, doc0 + 1);
+    it.nxt = win_offset<UNI>(off, p, doc0 + 1);
     int d, e;
-    win_find_next(it, p, off, d, e);
-    win_enter(it, p, off, d, e, 0);
+    win_find_next<UNI>(it, p, off, d, e);
+    win_enter<UNI>(it, p, off, d, e, 0);
 }
 
+template <bool UNI>
 __device__ __forceinline__ Window win_describe(const WinIter &it, const FwdParams &p, OffsetsPtr off)
 {
     Window w;
@@ -713,7 +727,7 @@ __device__ __forceinline__ Window win_describe(const WinIter &it, const FwdParam
     w.end_b = it.end;
     w.fin_b = false;
     if (w.fin_a) {
-        win_find_next(it, p, off, w.doc_b, w.end_b);
+        win_find_next<UNI>(it, p, off, w.doc_b, w.end_b);
         if (w.doc_b < it.doc_end) {
             w.len_b = w.end_b - it.end;
             w.n_b = min(w.len_b, TILE_ROWS - w.pa);
@@ -723,6 +737,7 @@ __device__ __forceinline__ Window win_describe(const WinIter &it, const FwdParam
     return w;
 }
 
+template <bool UNI>
 __device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const FwdParams &p, OffsetsPtr off)
 {
     it.row0 += w.n_a + w.n_b;
@@ -730,16 +745,17 @@ __device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const 
         it.rem -= TILE_ROWS;
         return;
     }
-    win_enter(it, p, off, w.doc_b, w.end_b, w.n_b);
+    win_enter<UNI>(it, p, off, w.doc_b, w.end_b, w.n_b);
     if (win_valid(it) && it.rem == 0) { // B lay inside the window whole: on to the document after it
         int d, e;
-        win_find_next(it, p, off, d, e);
-        win_enter(it, p, off, d, e, 0);
+        win_find_next<UNI>(it, p, off, d, e);
+        win_enter<UNI>(it, p, off, d, e, 0);
     }
 }
 
 // NCB: column blocks (queries) per wavefront, 3 or 4: a workgroup holds 24 or 32 queries
-template <int DT, int NCB>
+// UNI: uniform corpus (documents of l_d tokens, no offsets array)
+template <int DT, int NCB, bool UNI>
 __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
@@ -798,7 +814,7 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
     const bool wave_active = w * NCB < nb;
 
     WinIter li, ci;
-    win_init(li, p, off, doc0, doc1);
+    win_init<UNI>(li, p, off, doc0, doc1);
     ci = li;
     if (!win_valid(ci))
         return;
@@ -809,7 +825,7 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
         g_has = win_valid(li);
         if (!g_has)
             return;
-        const Window lw = win_describe(li, p, off);
+        const Window lw = win_describe<UNI>(li, p, off);
         if (copies) {
             // window row i holds A's row min(i, n_a - 1) below pa and B's row min(i - pa, n_b - 1) from pa on
             // (without a B that is A's last row again); A and B are neighbours in the packed corpus
@@ -821,7 +837,7 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
                 g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff(i));
             }
         }
-        win_advance(li, lw, p, off);
+        win_advance<UNI>(li, lw, p, off);
     };
     auto lstore = [&](int buf_off) {
         if (!g_has || !copies)
@@ -921,7 +937,7 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
                 }
             }
         }
-        win_advance(ci, cw, p, off);
+        win_advance<UNI>(ci, cw, p, off);
         __syncthreads();
         int t = o_cur;
         o_cur = o_nxt;
@@ -932,10 +948,10 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
     if (!wave_active) {
         // fewer than 32 queries in this group: the wavefront only helps moving tiles (same barriers as the others)
         while (win_valid(ci)) {
-            const Window cw = win_describe(ci, p, off);
+            const Window cw = win_describe<UNI>(ci, p, off);
             lstore(o_wr);
             gload();
-            win_advance(ci, cw, p, off);
+            win_advance<UNI>(ci, cw, p, off);
             __syncthreads();
             int t = o_cur;
             o_cur = o_nxt;
@@ -944,18 +960,18 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
         }
     } else {
         // runs of plain windows, each ended by one boundary window
-        Window cw = win_describe(ci, p, off);
+        Window cw = win_describe<UNI>(ci, p, off);
         for (;;) {
             while (cw.n_b == 0) {
                 stage(std::false_type{}, cw);
                 if (!win_valid(ci))
                     return;
-                cw = win_describe(ci, p, off);
+                cw = win_describe<UNI>(ci, p, off);
             }
             stage(std::true_type{}, cw);
             if (!win_valid(ci))
                 return;
-            cw = win_describe(ci, p, off);
+            cw = win_describe<UNI>(ci, p, off);
         }
     }
 }
@@ -981,7 +997,10 @@ static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
 template <int DT, int NCB>
 static hipError_t launch_pack(const FwdParams &p, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
+    if (p.offsets)
+        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, false>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
+    else
+        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, true>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 

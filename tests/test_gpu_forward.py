@@ -187,3 +187,13 @@ def test_ragged_packed_windows_many_chunks():
     Dp = W.unit_rows((int(lens.sum()), 128), "f16", 103, DEV)
     Q = W.unit_rows((48, 32, 128), "f16", 104, DEV)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, False, RTOL_16)
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 64)])
+@pytest.mark.parametrize("n_q,l_q", [(17, 32), (64, 20)])
+@pytest.mark.parametrize("b,l_d", [(50, 1), (33, 7), (21, 33), (40, 100), (9, 300), (700, 45)])
+def test_uniform_packed_windows(b, l_d, n_q, l_q, dtype, d):
+    """Uniform corpora whose documents are not a whole number of 32-row tiles take the packed windows as well."""
+    Q = W.unit_rows((n_q, l_q, d), dtype, 111, DEV)
+    D = W.unit_rows((b, l_d, d), dtype, 112, DEV)
+    forward_parity_uniform(Q, D, M.maxsim_forward, False, RTOL_16)

@@ -149,8 +149,9 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
         p.n_groups = p.n_q;
         p.n_pass = (p.bpq + group_blocks - 1) / group_blocks;
     }
-    // document chunks: about sixteen wavefronts per CU in total (two workgroups of eight), a multiple
-    // of 8 so that the XCD renumbering applies, and never more chunks than documents
+    // document chunks: about sixteen wavefronts per CU in total, i.e. twice what a CU holds at a time (256 registers
+    // per wavefront: two wavefronts per SIMD; one round or two measured the same), a multiple of 8 so that the XCD
+    // renumbering applies, and never more chunks than documents
     int64_t wg_target = (int64_t)num_cu * 16 / w;
     int64_t n_chunks = (wg_target + p.n_groups - 1) / p.n_groups;
     if (n_chunks < 8)

@@ -28,12 +28,13 @@ def pick_shape(rng):
     return n_q, l_q, b, l_d
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_forward_random_shape(seed):
     rng = np.random.default_rng(1000 + seed)
     n_q, l_q, b, l_d = pick_shape(rng)
     dtype = ["f16", "bf16", "f32"][seed % 3]
-    d = int(rng.choice([64, 128, 128, 256] if dtype == "f32" else [64, 128, 128, 256, 512]))
+    # register-stationary widths and slab-kernel widths (any multiple of 64 bytes per row)
+    d = int(rng.choice([64, 128, 128, 256, 48, 400] if dtype == "f32" else [64, 128, 128, 256, 512, 96, 320, 800]))
     rtol = RTOL_F32 if dtype == "f32" else RTOL_16
     Q = W.unit_rows((n_q, l_q, d), dtype, seed, DEV)
     if seed % 2 == 0:
@@ -47,7 +48,7 @@ def test_forward_random_shape(seed):
         forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, seed % 4 == 1, rtol)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(24))
 def test_int8_random_shape(seed):
     rng = np.random.default_rng(2000 + seed)
     n_q, l_q, b, l_d = pick_shape(rng)
@@ -55,6 +56,9 @@ def test_int8_random_shape(seed):
         b += 4096  # document-stationary kernel
         l_d = min(l_d, 40)
         n_q, l_q = min(n_q, 3), min(l_q, 100)
+    elif seed % 3 == 1 and seed % 2 == 0:
+        l_d = int(rng.choice([256, 257, 300, 520]))  # long uniform documents: a workgroup per document
+        n_q, l_q, b = min(n_q, 4), min(l_q, 129), min(b, 30)
     lens = rng.integers(0, 2 * l_d + 1, b) if seed % 2 else np.full(b, l_d)
     lens[0] = max(1, l_d)
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)

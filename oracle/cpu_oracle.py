@@ -66,6 +66,15 @@ def as_raw(x, dtype: str) -> np.ndarray:
     return a
 
 
+def decode_array(raw: np.ndarray, dtype: str) -> np.ndarray:
+    """Stored values as float64 (exact): fp32 widened, fp16 / bf16 bit patterns decoded."""
+    if dtype == "f32":
+        return raw.astype(np.float64)
+    if dtype == "f16":
+        return raw.view(np.float16).astype(np.float64)
+    return (raw.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
 def forward(Q, D, dtype: str, offsets=None, want_argmax=True, want_margin=True, threads=None):
     """Eq. 1.  Q [n_q,l_q,d]; D [b,l_d,d] (uniform) or [T,d] with int32 offsets [b+1] (ragged).
 
@@ -169,6 +178,42 @@ def backward_ragged(Q, D_packed, dtype: str, offsets, argmax, g):
             dQ += q1
             dD[s:e] = d1[0]
     return dQ, dD
+
+
+def csr_build(argmax, l_d: int):
+    """Inverse-grid CSR of the deterministic backward (Sec. "Closed-Form Gradients", Alg. 2): the edge with flat
+    index e = (i * b + j) * l_q + s and winning token t = argmax[i, j, s] has destination row dst = j * l_d + t;
+    row_ptr = [0, cumsum(bincount(dst))], col_idx = the edges in a STABLE sort by destination (so the edges of a
+    row appear in increasing e, i.e. increasing (i, s)).  Entries outside [0, l_d) are not edges.
+    Returns (row_ptr int32 [b * l_d + 1], col_idx int32 [number of edges])."""
+    A = np.ascontiguousarray(argmax, dtype=np.int64)
+    n_q, b, l_q = A.shape
+    dst = np.arange(b, dtype=np.int64)[None, :, None] * l_d + A
+    valid = (A >= 0) & (A < l_d)
+    e = np.flatnonzero(valid.ravel())
+    d = dst.ravel()[e]
+    order = np.argsort(d, kind="stable")
+    col_idx = e[order].astype(np.int32)
+    row_ptr = np.concatenate([[0], np.cumsum(np.bincount(d, minlength=b * l_d))]).astype(np.int32)
+    return row_ptr, col_idx
+
+
+def backward_dd_from_csr(Q, dtype: str, b: int, l_d: int, row_ptr, col_idx, g):
+    """Eq. 3 evaluated row by row from the CSR (Alg. 2, the row-owned loop): dD[r] = sum over the row's edges, in
+    list order, of g[i, j] * Q[i, s].  float64 [b, l_d, d].  (Plain Python loops: small cases only.)"""
+    Qr = as_raw(Q, dtype)
+    n_q, l_q, d = Qr.shape
+    Qd = decode_array(Qr, dtype)
+    G = np.asarray(g, dtype=np.float64)
+    dD = np.zeros((b * l_d, d), np.float64)
+    for r in range(b * l_d):
+        acc = np.zeros(d, np.float64)
+        for e in col_idx[row_ptr[r]:row_ptr[r + 1]]:
+            i, rest = divmod(int(e), b * l_q)
+            j, s_ = divmod(rest, l_q)
+            acc += G[i, j] * Qd[i, s_]
+        dD[r] = acc
+    return dD.reshape(b, l_d, d)
 
 
 def dot_i8(Q_i8, D_i8):

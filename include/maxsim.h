@@ -129,6 +129,37 @@ int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed
                            float *dQ, float *dD_packed, void *stream);
 
 /*
+ * The inverse-grid CSR of the deterministic backward, built on the device (Alg. 2; Sec.
+ * "Closed-Form Gradients"): the map destination row -> source edges that bincount, cumsum and
+ * a stable argsort by destination define.  Uniform corpus.
+ *   argmax   [n_q, b, l_q] int32 (device)   an entry t with 0 <= t < l_d is an edge with id
+ *                                           e = (i * b + j) * l_q + s and destination row
+ *                                           j * l_d + t; other entries are not edges
+ *   row_ptr  [b * l_d + 1] int32 (device)   output: row r's edges are col_idx[row_ptr[r] ..
+ *                                           row_ptr[r + 1]); row_ptr[b * l_d] = number of edges
+ *   col_idx  [n_q * b * l_q] int32 (device) output: edge ids, by destination row and by
+ *                                           increasing id within a row; only the first
+ *                                           row_ptr[b * l_d] entries are written
+ * Limits: l_d <= 4096 and n_q * b * l_q < 2^31 (MAXSIM_ERR_UNSUPPORTED beyond).  The result is
+ * the same on every run.  argmax must not change while the call is in flight.  The first call
+ * on a device must not be made under stream capture (it raises the kernel's LDS limit).
+ */
+int maxsim_csr_build(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,
+                     int32_t *col_idx, void *stream);
+
+/*
+ * maxsim_backward with dD taken through the explicit CSR (Alg. 2 as stated: build the CSR from
+ * argmax, then one owner per dD row walks that row's edge list).  row_ptr and col_idx are
+ * caller-provided device buffers of the sizes maxsim_csr_build states; they are overwritten
+ * and hold the CSR afterwards.  dQ, dD, the skipping of negative entries and the fp32
+ * accumulation order (a row's edges by increasing id) are those of maxsim_backward, so the two
+ * give the same bits.  Limits of maxsim_csr_build and of maxsim_backward apply.
+ */
+int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
+                        maxsim_dtype dtype, const int32_t *argmax, const float *dscore,
+                        int32_t *row_ptr, int32_t *col_idx, float *dQ, float *dD, void *stream);
+
+/*
  * Per-token symmetric absmax quantiser (Sec. "Quantised Scoring").
  *   X      [rows, d] dtype
  *   X_i8   [rows, d] int8    round_half_even(x / scale), clamped to [-127, 127]

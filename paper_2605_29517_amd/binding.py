@@ -17,6 +17,7 @@ MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
 SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
+           "maxsim_csr_build", "maxsim_backward_csr",
            "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_forward_i8_streamed", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
@@ -50,6 +51,10 @@ def load():
     L.maxsim_backward.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p]
     L.maxsim_backward_ragged.restype = i
     L.maxsim_backward_ragged.argtypes = [p, i, i, p, p, l, l, i, i, p, p, p, p, p]
+    L.maxsim_csr_build.restype = i
+    L.maxsim_csr_build.argtypes = [p, i, l, i, i, p, p, p]
+    L.maxsim_backward_csr.restype = i
+    L.maxsim_backward_csr.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p, p, p]
     L.maxsim_quantize_rows_i8.restype = i
     L.maxsim_quantize_rows_i8.argtypes = [p, l, i, i, p, p, p]
     L.maxsim_forward_i8.restype = i
@@ -211,6 +216,51 @@ def maxsim_backward_ragged(Q, D_packed, doc_offsets, argmax, dscore, total_token
                                       _dev(dD, "dD", torch.float32), _stream(Q))
     _check(rc, "maxsim_backward_ragged")
     return dQ, dD
+
+
+def maxsim_csr_build(argmax, l_d, row_ptr=None, col_idx=None):
+    """Alg. 2's inverse-grid CSR of argmax [n_q,b,l_q]: returns (row_ptr int32 [b*l_d+1], col_idx int32 [n_q*b*l_q],
+    of which the first row_ptr[-1] entries are the edges)."""
+    L = load()
+    n_q, b, l_q = argmax.shape
+    if row_ptr is None:
+        row_ptr = torch.empty(b * l_d + 1, dtype=torch.int32, device=argmax.device)
+    if col_idx is None:
+        col_idx = torch.empty(n_q * b * l_q, dtype=torch.int32, device=argmax.device)
+    if row_ptr.numel() < b * l_d + 1 or col_idx.numel() < n_q * b * l_q:
+        raise MaxSimError("row_ptr must hold b*l_d+1 and col_idx n_q*b*l_q entries")
+    with _on_device(argmax, "argmax"):
+        rc = L.maxsim_csr_build(_dev(argmax, "argmax", torch.int32), n_q, b, l_q, int(l_d),
+                                _dev(row_ptr, "row_ptr", torch.int32), _dev(col_idx, "col_idx", torch.int32),
+                                _stream(argmax))
+    _check(rc, "maxsim_csr_build")
+    return row_ptr, col_idx
+
+
+def maxsim_backward_csr(Q, D, argmax, dscore, row_ptr=None, col_idx=None, dQ=None, dD=None):
+    """Eqs. 2-3 with dD through the explicit CSR (Alg. 2): returns (dQ, dD, row_ptr, col_idx)."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    b, l_d, _ = D.shape
+    if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
+        raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
+    if row_ptr is None:
+        row_ptr = torch.empty(b * l_d + 1, dtype=torch.int32, device=Q.device)
+    if col_idx is None:
+        col_idx = torch.empty(n_q * b * l_q, dtype=torch.int32, device=Q.device)
+    if row_ptr.numel() < b * l_d + 1 or col_idx.numel() < n_q * b * l_q:
+        raise MaxSimError("row_ptr must hold b*l_d+1 and col_idx n_q*b*l_q entries")
+    if dQ is None:
+        dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
+    if dD is None:
+        dD = torch.empty(b, l_d, d, dtype=torch.float32, device=Q.device)
+    with _on_device(Q, "Q"):
+        rc = L.maxsim_backward_csr(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
+                                   _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
+                                   _dev(row_ptr, "row_ptr", torch.int32), _dev(col_idx, "col_idx", torch.int32),
+                                   _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
+    _check(rc, "maxsim_backward_csr")
+    return dQ, dD, row_ptr, col_idx
 
 
 def maxsim_quantize_rows_i8(X, X_i8=None, scale=None):

@@ -11,6 +11,11 @@ bool forward_width_supported(int dtype, int d);
 hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
                            int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
                            float *dD, int num_cu, hipStream_t stream);
+hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,
+                            int32_t *col_idx, int num_cu, hipStream_t stream);
+hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+                               const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
+                               float *dD, int num_cu, hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
@@ -286,6 +291,43 @@ int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed
         return MAXSIM_ERR_UNSUPPORTED;
     return finish(maxsim::backward_launch(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, (int)dtype, argmax,
                                           dscore, dQ, dD_packed, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+static bool csr_shape_ok(int n_q, int64_t b, int l_q, int l_d)
+{
+    return l_d <= 4096 && b * (int64_t)l_d < (int64_t(1) << 31) - 1 && b < (int64_t(1) << 31) &&
+           (int64_t)n_q * l_q < (int64_t(1) << 31) && (int64_t)n_q * l_q * b < (int64_t(1) << 31);
+}
+
+int maxsim_csr_build(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr, int32_t *col_idx,
+                     void *stream)
+{
+    if (!argmax || !row_ptr || !col_idx || n_q < 1 || l_q < 1 || b < 1 || l_d < 1)
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(argmax, 4) || !aligned(row_ptr, 4) || !aligned(col_idx, 4))
+        return MAXSIM_ERR_INVALID;
+    if (!csr_shape_ok(n_q, b, l_q, l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::csr_build_launch(argmax, n_q, b, l_q, l_d, row_ptr, col_idx, num_cu(),
+                                           static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, maxsim_dtype dtype,
+                        const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
+                        float *dD, void *stream)
+{
+    if (!Q || !D || !argmax || !dscore || !row_ptr || !col_idx || !dQ || !dD || n_q < 1 || l_q < 1 || b < 1 || l_d < 1 ||
+        !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(row_ptr, 4) ||
+        !aligned(col_idx, 4) || !aligned(dQ, 16) || !aligned(dD, 16))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (!csr_shape_ok(n_q, b, l_q, l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::backward_csr_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, row_ptr, col_idx, dQ,
+                                              dD, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dtype, int8_t *X_i8, float *scale,

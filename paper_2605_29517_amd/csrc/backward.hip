@@ -382,6 +382,317 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
 }
 
 // ---------------------------------------------------------------------------------------
+// Explicit inverse-grid CSR (Alg. 2): destination row j * l_d + t -> the edges that land on it.
+//
+// An edge is an argmax entry A[i, j, s] = t with 0 <= t < l_d; its id is the flat index
+// e = (i * b + j) * l_q + s.  row_ptr [b * l_d + 1] and col_idx [number of edges] are what
+// bincount + cumsum + a stable argsort by destination give: the edges of a row are listed by
+// increasing id.  Because all rows of document j are consecutive, the build is a counting sort
+// per document:
+//   csr_count_kernel   edges of document j            -> row_ptr[(j + 1) * l_d]
+//   csr_scan_kernel    running sum over the documents  (in place, stride l_d; row_ptr[0] = 0)
+//   csr_place_kernel   one workgroup per document: each of its 8 wavefronts takes a contiguous
+//                      eighth of the document's n_q * l_q entries and counts it into its own
+//                      histogram over t; a scan over (t, wavefront) turns the histograms into
+//                      write cursors and gives row_ptr; each wavefront then walks its entries
+//                      again, 64 at a time, ranks equal t within the 64 by ballots and writes
+//                      the edge ids.  No atomics decide an order, so the CSR is the same on
+//                      every run.
+//   csr_apply_kernel   sixteen lanes per dD row walk the row's list in order (Eq. 3).
+// ---------------------------------------------------------------------------------------
+constexpr int CSR_WAVES = 8;
+constexpr int CSR_MAX_LD = 4096;
+constexpr int CSR_LDS_EXTRA = 16; // ints after the histograms: one sum per wavefront for the block scan
+
+struct CsrParams {
+    const int32_t *A;
+    int32_t *row_ptr;
+    int32_t *col_idx;
+    int64_t b;
+    int n_q, l_q, l_d;
+};
+
+__global__ void __launch_bounds__(256) csr_count_kernel(CsrParams p)
+{
+    __shared__ int part[4];
+    const int tid = threadIdx.x;
+    const int n = p.n_q * p.l_q;
+    for (int64_t j = blockIdx.x; j < p.b; j += gridDim.x) {
+        int cnt = 0;
+        for (int k = tid; k < n; k += 256) {
+            int i = k / p.l_q;
+            int s = k - i * p.l_q;
+            int t = p.A[((int64_t)i * p.b + j) * p.l_q + s];
+            cnt += (unsigned)t < (unsigned)p.l_d ? 1 : 0;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1)
+            cnt += __shfl_xor(cnt, o);
+        if ((tid & 63) == 0)
+            part[tid >> 6] = cnt;
+        __syncthreads();
+        if (tid == 0)
+            p.row_ptr[(j + 1) * p.l_d] = part[0] + part[1] + part[2] + part[3];
+        __syncthreads();
+    }
+}
+
+// inclusive wave scan
+__device__ __forceinline__ int wave_scan_incl(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int u = __shfl_up(v, o);
+        if (lane >= o)
+            v += u;
+    }
+    return v;
+}
+
+__global__ void __launch_bounds__(1024) csr_scan_kernel(CsrParams p)
+{
+    __shared__ int wsum[16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int carry = 0;
+    for (int64_t c0 = 0; c0 < p.b; c0 += 1024) {
+        int64_t j = c0 + tid;
+        int v = j < p.b ? p.row_ptr[(j + 1) * p.l_d] : 0;
+        int incl = wave_scan_incl(v, lane);
+        if (lane == 63)
+            wsum[w] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            int sx = wsum[x];
+            before += x < w ? sx : 0;
+            total += sx;
+        }
+        if (j < p.b)
+            p.row_ptr[(j + 1) * p.l_d] = carry + before + incl;
+        carry += total;
+        __syncthreads();
+    }
+    if (tid == 0)
+        p.row_ptr[0] = 0;
+}
+
+__global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
+{
+    extern __shared__ int csr_lds[]; // [CSR_WAVES][l_d] histograms, then cursors; CSR_LDS_EXTRA ints of scan space
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l_d = p.l_d;
+    int *wsum = csr_lds + CSR_WAVES * l_d;
+    volatile int *H = csr_lds + w * l_d;
+    const int n = p.n_q * p.l_q;
+    const int chunk = (int)((((int64_t)n + CSR_WAVES * 64 - 1) / (CSR_WAVES * 64)) * 64);
+    const int64_t k0 = (int64_t)w * chunk;
+    const int64_t k1 = k0 + chunk < n ? k0 + chunk : n;
+    const int tpt = (l_d + CSR_WAVES * 64 - 1) / (CSR_WAVES * 64); // tokens per thread in the scan
+    int nbits = 0;
+    while ((1 << nbits) < l_d)
+        ++nbits;
+
+    for (int64_t j = blockIdx.x; j < p.b; j += gridDim.x) {
+        for (int x = tid; x < CSR_WAVES * l_d; x += CSR_WAVES * 64)
+            csr_lds[x] = 0;
+        __syncthreads();
+        for (int64_t k = k0 + lane; k < k1; k += 64) {
+            int i = (int)(k / p.l_q);
+            int s = (int)(k - (int64_t)i * p.l_q);
+            int t = p.A[((int64_t)i * p.b + j) * p.l_q + s];
+            if ((unsigned)t < (unsigned)l_d)
+                atomicAdd(csr_lds + w * l_d + t, 1);
+        }
+        __syncthreads();
+        // exclusive scan over (t major, wavefront minor), starting at the document's first edge
+        const int t_lo = tid * tpt;
+        const int t_hi = t_lo + tpt < l_d ? t_lo + tpt : l_d;
+        int local = 0;
+        for (int t = t_lo; t < t_hi; ++t)
+            for (int x = 0; x < CSR_WAVES; ++x)
+                local += csr_lds[x * l_d + t];
+        int incl = wave_scan_incl(local, lane);
+        if (lane == 63)
+            wsum[w] = incl;
+        __syncthreads();
+        int run = p.row_ptr[j * l_d] + incl - local;
+        for (int x = 0; x < w; ++x)
+            run += wsum[x];
+        for (int t = t_lo; t < t_hi; ++t) {
+            p.row_ptr[j * l_d + t] = run;
+            for (int x = 0; x < CSR_WAVES; ++x) {
+                int c = csr_lds[x * l_d + t];
+                csr_lds[x * l_d + t] = run;
+                run += c;
+            }
+        }
+        __syncthreads();
+        // placement: entries in order, equal t ranked by lane
+        for (int64_t kb = k0; kb < k1; kb += 64) {
+            int64_t k = kb + lane;
+            int t = -1;
+            int e = 0;
+            if (k < k1) {
+                int i = (int)(k / p.l_q);
+                int s = (int)(k - (int64_t)i * p.l_q);
+                int64_t e64 = ((int64_t)i * p.b + j) * p.l_q + s;
+                t = p.A[e64];
+                e = (int)e64;
+            }
+            const bool valid = (unsigned)t < (unsigned)l_d;
+            uint64_t same = __ballot(valid);
+            for (int bit = 0; bit < nbits; ++bit) {
+                bool one = (t >> bit) & 1;
+                uint64_t bm = __ballot(one);
+                same &= one ? bm : ~bm;
+            }
+            if (valid) {
+                uint64_t below = same & ((uint64_t(1) << lane) - 1);
+                int rank = __popcll(below);
+                int pos = H[t] + rank;
+                if ((int64_t)pos < (int64_t)n * p.b) // holds unless argmax changed since it was counted
+                    p.col_idx[pos] = e;
+                if (rank == 0)
+                    H[t] = pos + __popcll(same);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+    }
+}
+
+// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :]
+template <int DT>
+__global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
+                                                        const int32_t *__restrict__ col_idx)
+{
+    constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
+    const int lane = threadIdx.x & 63;
+    const int grp = lane >> 4;
+    const int c = lane & 15;
+    const int64_t row = ((((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) << 2) + grp;
+    if (row >= p.total_tokens)
+        return;
+    const int64_t j = row / p.l_d;
+    const int64_t n_edges = (int64_t)p.n_q * p.l_q * p.b;
+    const int beg = row_ptr[row] > 0 ? row_ptr[row] : 0;
+    const int end = row_ptr[row + 1] < n_edges ? row_ptr[row + 1] : (int)n_edges;
+    const uint32_t bl = (uint32_t)(p.b * p.l_q); // edge ids of one query
+    const int64_t jl = j * p.l_q;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    constexpr int UNROLL = 4;
+    for (int k = beg; k < end; k += UNROLL) {
+        int64_t qrow[UNROLL];
+        float gg[UNROLL];
+        bool on[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            on[u] = k + u < end;
+            int64_t rem = (on[u] ? (int64_t)col_idx[k + u] : jl) - jl; // i * (b * l_q) + s
+            uint32_t i = (uint32_t)rem / bl;
+            uint32_t s = (uint32_t)rem - i * bl;
+            on[u] = on[u] && rem >= 0 && rem < (int64_t(1) << 31) && i < (uint32_t)p.n_q && s < (uint32_t)p.l_q;
+            qrow[u] = on[u] ? (int64_t)i * p.l_q + s : 0;
+            gg[u] = on[u] ? p.g[(int64_t)i * p.b + j] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float v[8];
+            load8<DT>(p.Q + qrow[u] * ROWB + c * 8 * Elem<DT>::BYTES, v);
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                acc[x] = on[u] ? fmaf(gg[u], v[x], acc[x]) : acc[x];
+        }
+    }
+    float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
+    dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
+hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,
+                            int32_t *col_idx, int num_cu, hipStream_t stream)
+{
+    if (l_d > CSR_MAX_LD)
+        return hipErrorInvalidValue;
+    CsrParams c;
+    c.A = argmax;
+    c.row_ptr = row_ptr;
+    c.col_idx = col_idx;
+    c.b = b;
+    c.n_q = n_q;
+    c.l_q = l_q;
+    c.l_d = l_d;
+    // more than 64 KB of dynamic LDS has to be allowed once per device
+    static bool allowed[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!allowed[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&csr_place_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (CSR_WAVES * CSR_MAX_LD + CSR_LDS_EXTRA) * (int)sizeof(int));
+        if (e != hipSuccess)
+            return e;
+        allowed[dev] = true;
+    }
+    const int64_t cap = (int64_t)num_cu * 64;
+    const unsigned grid = (unsigned)(b < cap ? b : cap);
+    hipLaunchKernelGGL(csr_count_kernel, dim3(grid), dim3(256), 0, stream, c);
+    if ((e = hipGetLastError()) != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(csr_scan_kernel, dim3(1), dim3(1024), 0, stream, c);
+    if ((e = hipGetLastError()) != hipSuccess)
+        return e;
+    const size_t lds = (size_t)(CSR_WAVES * l_d + CSR_LDS_EXTRA) * sizeof(int);
+    hipLaunchKernelGGL(csr_place_kernel, dim3(grid), dim3(CSR_WAVES * 64), lds, stream, c);
+    return hipGetLastError();
+}
+
+template <int DT> static hipError_t launch_bwd_csr(const BwdParams &p, const int32_t *row_ptr, const int32_t *col_idx,
+                                                   hipStream_t stream)
+{
+    int64_t waves = (int64_t)p.n_q * p.l_q;
+    hipLaunchKernelGGL((bwd_dq_kernel<DT>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    int64_t groups = (p.total_tokens + 15) / 16; // 16 rows per workgroup of 4 wavefronts
+    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups), dim3(256), 0, stream, p, row_ptr, col_idx);
+    return hipGetLastError();
+}
+
+hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+                               const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
+                               float *dD, int num_cu, hipStream_t stream)
+{
+    hipError_t e = csr_build_launch(argmax, n_q, b, l_q, l_d, row_ptr, col_idx, num_cu, stream);
+    if (e != hipSuccess)
+        return e;
+    BwdParams p;
+    p.Q = static_cast<const char *>(Q);
+    p.D = static_cast<const char *>(D);
+    p.offsets = nullptr;
+    p.total_tokens = b * (int64_t)l_d;
+    p.A = argmax;
+    p.g = dscore;
+    p.dQ = dQ;
+    p.dD = dD;
+    p.b = b;
+    p.n_q = n_q;
+    p.l_q = l_q;
+    p.l_d = l_d;
+    switch (dtype) {
+    case MAXSIM_F32: return launch_bwd_csr<MAXSIM_F32>(p, row_ptr, col_idx, stream);
+    case MAXSIM_F16: return launch_bwd_csr<MAXSIM_F16>(p, row_ptr, col_idx, stream);
+    default: return launch_bwd_csr<MAXSIM_BF16>(p, row_ptr, col_idx, stream);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // cross-entropy gradient on the [n, b] score matrix (labels on the diagonal)
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_max(float v)

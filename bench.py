@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--legs", default="c1,c2_nq1,c2_i8,c2_train,c3,c3_host,wide_d,c4,c5,ceilings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--cpu-docs", type=int, default=4096, help="documents in the oracle's sample")
+    ap.add_argument("--cpu-docs", type=int, default=8192, help="documents in the oracle's sample")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus %d is not supported); "
@@ -301,6 +301,12 @@ def main():
         wc, ac, _, _ = time_launches(lambda: M.maxsim_ce_grad(s4, tau, g=g4, loss=loss4), 50, 5, cold=True)
         wb, ab, _, _ = time_launches(lambda: M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4), 50, 5, cold=True)
         wbw, _, _, _ = time_launches(lambda: M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4), 50, 5)
+        # the same backward with dD through the explicit CSR (Alg. 2), and the CSR build alone
+        rp4 = torch.empty(n4 * ld4 + 1, dtype=torch.int32, device=dev)
+        ci4 = torch.empty(n4 * n4 * lq4, dtype=torch.int32, device=dev)
+        wcsr, _, _, _ = time_launches(lambda: M.maxsim_backward_csr(Q4, D4, a4, g4, row_ptr=rp4, col_idx=ci4, dQ=dQ4, dD=dD4),
+                                      50, 5, cold=True)
+        wcb, _, _, _ = time_launches(lambda: M.maxsim_csr_build(a4, ld4, row_ptr=rp4, col_idx=ci4), 50, 5, cold=True)
 
         def step4():
             M.maxsim_forward(Q4, D4, scores=s4, argmax=a4)
@@ -313,10 +319,11 @@ def main():
                       "timing": "cold: 512 MB written before every timed launch; *_warm_ms: back to back, operands in cache",
                       "step_ms": round(ws, 4), "forward_ms": round(wf, 4), "ce_ms": round(wc, 4), "backward_ms": round(wb, 4),
                       "step_warm_ms": round(wsw, 4), "backward_warm_ms": round(wbw, 4),
+                      "backward_csr_ms": round(wcsr, 4), "csr_build_ms": round(wcb, 4),
                       "pairs_per_s": round(n4 * n4 / (ws * 1e-3), 1),
                       "roofline_forward": roof("mfma", forward_flops(n4, lq4, n4 * ld4), af, PEAK_MFMA_16BIT_TFLOPS, "TFLOP/s", "c4_fwd"),
                       "roofline_backward": roof("hbm", backward_bytes(n4, lq4, n4, ld4, 2), ab, PEAK_HBM_GBS, "GB/s", "c4_bwd")})
-        del Q4, D4, s4, a4, g4, dQ4, dD4
+        del Q4, D4, s4, a4, g4, dQ4, dD4, rp4, ci4
 
     if "c5" in legs:
         nd5, l5, chunk = 400_000, 1024, 10_000

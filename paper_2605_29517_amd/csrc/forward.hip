@@ -74,9 +74,10 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
         }
     }
 
-    // nine to sixteen blocks of narrow rows: the tile kernel with two blocks per wavefront is faster than
-    // three or four streaming wavefronts per run (measured: 2.1-2.6 ms against 2.7 ms on the ragged 100K corpus)
-    if (nu <= 8 && total_blocks > 8)
+    // five to sixteen blocks of narrow rows: the tile kernel with two blocks per wavefront is faster than two to
+    // four streaming wavefronts per run (measured on the ragged 100K corpus: 1.37 against 1.60 ms at 5 blocks,
+    // 2.1-2.6 against 2.7 ms at 9-16; uniform corpora of 50K documents: 10-22 % at 5-8 blocks)
+    if (nu <= 8 && total_blocks > 4)
         s_groups = 0;
 
     if (s_groups > 0) {
@@ -121,10 +122,17 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     else if (total_blocks <= 4 * ncb)
         w = 4;
     int shape = w, wave_blocks = ncb;
-    if (ncb == 4 && total_blocks <= 16) { // eight wavefronts with one or two column blocks each (shape code 81 / 82)
-        wave_blocks = total_blocks <= 8 ? 1 : 2;
-        w = 8;
-        shape = 80 + wave_blocks;
+    if (ncb == 4 && total_blocks <= 16) {
+        if (total_blocks <= 8 && !(am && p.bpq > 4)) {
+            // four wavefronts with two column blocks each (shape code 42), two workgroups per CU
+            wave_blocks = 2;
+            w = 4;
+            shape = 42;
+        } else { // eight wavefronts with one or two column blocks each (shape code 81 / 82)
+            wave_blocks = total_blocks <= 8 ? 1 : 2;
+            w = 8;
+            shape = 80 + wave_blocks;
+        }
     }
     // a ragged corpus (or a uniform one whose documents are not a whole number of tiles) scored by many queries of
     // one block: 32-row windows over the packed rows (no padded tiles at the ends of documents)

@@ -1030,6 +1030,8 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
             return launch_tile<DT, 8, 1, ARGMAX, 6>(p, grid, s);
         if (w == 82)
             return launch_tile<DT, 8, 2, ARGMAX, 3>(p, grid, s);
+        if (w == 42)
+            return launch_tile<DT, 4, 2, ARGMAX, 4>(p, grid, s);
         if constexpr (!ARGMAX) {
             if (w == 93) // ragged corpus, queries of one block: windows over the packed rows; 24 or 32 queries per workgroup
                 return launch_pack<DT, 3>(p, grid, s);

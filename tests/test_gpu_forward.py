@@ -60,14 +60,14 @@ def _ragged_case(n_q, l_q, lens, dtype, seed):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("want_argmax", [False, True])
-@pytest.mark.parametrize("n_q,l_q", [(1, 32), (3, 32), (7, 33), (64, 32), (2, 300)])
+@pytest.mark.parametrize("n_q,l_q", [(1, 32), (3, 32), (5, 32), (8, 30), (3, 40), (7, 33), (64, 32), (2, 300)])
 def test_ragged_edge_lengths(n_q, l_q, want_argmax, dtype):
     lens = [1, 31, 32, 33, 0, 64, 300, 0, 0, 2, 65, 128, 1, 97]
     Q, Dp, off = _ragged_case(n_q, l_q, lens, dtype, 31)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, want_argmax, RTOL_F32 if dtype == "f32" else RTOL_16)
 
 
-@pytest.mark.parametrize("n_q", [1, 4, 64])
+@pytest.mark.parametrize("n_q", [1, 4, 6, 64])
 def test_ragged_colbert_like(n_q):
     Q, Dp, off, _ = W.colbert_rerank(n_q=n_q, n_docs=700, device=DEV)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, n_q == 4, RTOL_16)

@@ -119,6 +119,16 @@ def test_config4_contrastive_step_full_size():
     col = torch.einsum("ij,ik->jk", g.double(), Q.double().sum(1))
     assert float((dD.double().sum(1) - col).abs().max()) <= 1e-4 * float(col.abs().max())
 
+    # the explicit CSR at full size: the whole structure against the oracle's (integer work, bit-exact), and the
+    # gradients through it against the default backward (same summation order and arithmetic: same bits)
+    a_dev = torch.from_numpy(a_in).to(DEV)
+    cQ, cD, row_ptr, col_idx = M.maxsim_backward_csr(Q, D, a_dev, g)
+    torch.cuda.synchronize()
+    rp, ci = O.csr_build(a_in, l_d)
+    assert np.array_equal(row_ptr.cpu().numpy(), rp)
+    assert np.array_equal(col_idx.cpu().numpy()[:rp[-1]], ci)
+    assert torch.equal(cQ, dQ) and torch.equal(cD, dD)
+
 
 def test_config5_int8_corpus_full_size():
     n_docs, l, chunk = 400_000, 1024, 10_000

@@ -28,6 +28,11 @@ def test_training_step_replays_from_a_graph():
     # a corpus large enough for the document-stationary int8 kernel (dynamic LDS above 64 KB)
     big8, bigs = M.maxsim_quantize_rows_i8(W.unit_rows((4200, 40, 128), "f32", 8, DEV))
     s8b = torch.empty(n, 4200, device=DEV)
+    cQ = torch.empty(n, l_q, 128, device=DEV)
+    cD = torch.empty(n, l_d, 128, device=DEV)
+    row_ptr = torch.empty(n * l_d + 1, dtype=torch.int32, device=DEV)
+    col_idx = torch.empty(n * n * l_q, dtype=torch.int32, device=DEV)
+    outs = (s, a, g, loss, dQ, dD, s8, s8b, cQ, cD, row_ptr, col_idx)
 
     def step():
         M.maxsim_forward(Q, D, scores=s, argmax=a)
@@ -36,10 +41,12 @@ def test_training_step_replays_from_a_graph():
         M.maxsim_quantize_rows_i8(Q, X_i8=q8, scale=qs)
         M.maxsim_forward_i8(q8, qs, d8, ds, scores=s8)
         M.maxsim_forward_i8(q8, qs, big8, bigs, scores=s8b)
+        M.maxsim_backward_csr(Q, D, a, g, row_ptr=row_ptr, col_idx=col_idx, dQ=cQ, dD=cD)
 
     step()
     torch.cuda.synchronize()
-    want = [t.clone() for t in (s, a, g, loss, dQ, dD, s8, s8b)]
+    want = [t.clone() for t in outs]
+    assert torch.equal(cQ, dQ) and torch.equal(cD, dD)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -51,12 +58,12 @@ def test_training_step_replays_from_a_graph():
             step()
     torch.cuda.synchronize()
     for rep in range(4):
-        for t in (s, a, g, loss, dQ, dD, s8, s8b):
+        for t in outs:
             t.fill_(0) if t.dtype != torch.int32 else t.fill_(-7)   # eager work between replays
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for got, ref in zip((s, a, g, loss, dQ, dD, s8, s8b), want):
+        for got, ref in zip(outs, want):
             assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
 
 

@@ -793,58 +793,108 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
 // ---------------------------------------------------------------------------------------
 // per-token symmetric absmax quantiser: one wavefront per row, two elements per lane
 // ---------------------------------------------------------------------------------------
-template <int DT> __device__ __forceinline__ void load2(const char *row, int lane, float &x0, float &x1)
+// 8 consecutive elements of a row, widened to fp32
+template <int DT> __device__ __forceinline__ void load_row8(const char *p, float (&v)[8])
 {
     if (DT == MAXSIM_F32) {
-        float2 v = reinterpret_cast<const float2 *>(row)[lane];
-        x0 = v.x;
-        x1 = v.y;
+        float4 a = *reinterpret_cast<const float4 *>(p);
+        float4 b = *reinterpret_cast<const float4 *>(p + 16);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
     } else {
-        uint32_t wv = reinterpret_cast<const uint32_t *>(row)[lane];
-        if (DT == MAXSIM_F16) {
-            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv & 0xffffu));
-            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv >> 16));
-        } else {
-            x0 = __uint_as_float(wv << 16);
-            x1 = __uint_as_float(wv & 0xffff0000u);
+        uint4 raw = *reinterpret_cast<const uint4 *>(p);
+        uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (DT == MAXSIM_F16) {
+                v[2 * i] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] & 0xffffu));
+                v[2 * i + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[i] >> 16));
+            } else {
+                v[2 * i] = __uint_as_float(w[i] << 16);
+                v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            }
         }
     }
 }
 
+template <int CTRL> __device__ __forceinline__ float dpp_max(float v)
+{
+    return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true)));
+}
+
+// round_half_even(x / s) clamped to [-127, 127], with the IEEE quotient
 __device__ __forceinline__ int quant_code(float x, float s)
 {
-    if (s == 0.0f)
-        return 0;
-    float r = rintf(x / s); // IEEE division, round half to even
+    float r = rintf(x / s);
     r = fminf(fmaxf(r, -127.0f), 127.0f);
     return (int)r;
 }
 
+// Sixteen lanes per row (8 elements each), four rows per wavefront and step.  The code of an element is
+// round_half_even(fl32(x / s)).  One IEEE division per element would make the kernel VALU-bound (about twelve
+// instructions each), so the quotient is formed from the row's correctly rounded reciprocal r = fl32(1 / s):
+// q0 = fl32(x * r), e = x - q0 * s (exact in one fused multiply-add), q = fl32(q0 + e * r), which is the correctly
+// rounded x / s (Markstein's division step: r is correctly rounded and q0 is within one ulp).  Rows whose scale has
+// an all-ones significand (the one case the theorem leaves out) or lies outside [2^-60, 2^60] (where e could
+// underflow), and all-zero rows, take the per-element division instead.
 template <int DT>
 __global__ void __launch_bounds__(256) quantize_rows_kernel(const char *X, int64_t rows, int8_t *out, float *scale)
 {
-    constexpr int ROWB = D_MODEL * (DT == MAXSIM_F32 ? 4 : 2);
+    constexpr int EB = DT == MAXSIM_F32 ? 4 : 2;
+    constexpr int ROWB = D_MODEL * EB;
+    static_assert(D_MODEL == 128, "sixteen lanes x eight elements cover a row");
     const int lane = threadIdx.x & 63;
+    const int grp = lane >> 4, c = lane & 15;
     const int64_t n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    for (int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; r < rows; r += n_waves) {
-        float x0, x1;
-        load2<DT>(X + r * ROWB, lane, x0, x1);
-        float a = fmaxf(fabsf(x0), fabsf(x1));
+    for (int64_t r0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) * 4; r0 < rows; r0 += n_waves * 4) {
+        const int64_t row = r0 + grp;
+        const bool live = row < rows;
+        const int64_t rr = live ? row : rows - 1;
+        float x[8];
+        load_row8<DT>(X + rr * ROWB + c * 8 * EB, x);
+        float a = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fabsf(x[2]));
+        a = fmaxf(fmaxf(a, fabsf(x[3])), fabsf(x[4]));
+        a = fmaxf(fmaxf(a, fabsf(x[5])), fabsf(x[6]));
+        a = fmaxf(a, fabsf(x[7]));
+        a = dpp_max<0xB1>(a);  // quad_perm [1,0,3,2]
+        a = dpp_max<0x4E>(a);  // quad_perm [2,3,0,1]
+        a = dpp_max<0x141>(a); // row_half_mirror
+        a = dpp_max<0x140>(a); // row_mirror: all sixteen lanes of the row hold its absmax
+        const float s = a / 127.0f;
+        const uint32_t sb = __float_as_uint(s);
+        const bool fast = s >= 0x1p-60f && s <= 0x1p60f && (sb & 0x7fffffu) != 0x7fffffu;
+        int code[8];
+        if (fast) {
+#pragma clang fp contract(off)
+            const float r = 1.0f / s;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1)
-            a = fmaxf(a, __shfl_xor(a, o));
-        float s = a / 127.0f;
-        int c0 = quant_code(x0, s), c1 = quant_code(x1, s);
-        uint16_t packed = (uint16_t)((c0 & 0xff) | ((c1 & 0xff) << 8));
-        reinterpret_cast<uint16_t *>(out + r * D_MODEL)[lane] = packed;
-        if (lane == 0)
-            scale[r] = s;
+            for (int i = 0; i < 8; ++i) {
+                float q0 = x[i] * r;
+                float e = fmaf(-q0, s, x[i]);
+                float q = rintf(fmaf(e, r, q0));
+                code[i] = (int)fminf(fmaxf(q, -127.0f), 127.0f);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                code[i] = s == 0.0f ? 0 : quant_code(x[i], s);
+        }
+        uint2 packed;
+        packed.x = (uint32_t)(code[0] & 0xff) | ((uint32_t)(code[1] & 0xff) << 8) | ((uint32_t)(code[2] & 0xff) << 16) |
+                   ((uint32_t)code[3] << 24);
+        packed.y = (uint32_t)(code[4] & 0xff) | ((uint32_t)(code[5] & 0xff) << 8) | ((uint32_t)(code[6] & 0xff) << 16) |
+                   ((uint32_t)code[7] << 24);
+        if (live) {
+            *reinterpret_cast<uint2 *>(out + row * D_MODEL + c * 8) = packed;
+            if (c == 0)
+                scale[row] = s;
+        }
     }
 }
 
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream)
 {
-    int64_t blocks = (rows + 3) / 4;
+    int64_t blocks = (rows + 15) / 16; // 4 wavefronts x 4 rows per step
     if (blocks > 65536 * 4)
         blocks = 65536 * 4;
     const char *x = static_cast<const char *>(X);

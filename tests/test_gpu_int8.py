@@ -35,6 +35,37 @@ def test_quantiser_half_to_even():
     assert codes[0, :8].tolist() == [127, 0, 2, 2, 0, -2, -2, 3]
 
 
+def test_quantiser_hard_quotients_and_extreme_scales():
+    """Rows built to stress the rounding of x / s: elements a few ulps around every half-integer multiple of the
+    scale, scales with an all-ones significand, scales from the subnormal range up to 2^100, and a row count that
+    leaves the last wavefront partly empty.  Bit-exact against the oracle's IEEE division."""
+    rng = np.random.default_rng(12)
+    rows = []
+    # scales with an all-ones significand: absmax = fl32(127 * s) gives fl32(absmax / 127) = s for most exponents
+    cand = (np.arange(60, 200, dtype=np.uint32) << 23 | np.uint32(0x7fffff)).view(np.float32)
+    amax = (cand.astype(np.float64) * 127.0).astype(np.float32)
+    keep = (amax / np.float32(127.0)).view(np.uint32) & 0x7fffff == 0x7fffff
+    assert keep.sum() > 20
+    for a in list(amax[keep][:40]) + [np.float32(v) for v in (1e-42, 3e-39, 1e-30, 1e-19, 1e-3, 1.0, 77.7, 1e19, 1e30)]:
+        s = np.float32(a) / np.float32(127.0)
+        k = rng.integers(-127, 127, 127).astype(np.float32) + np.float32(0.5)
+        x = (k * s).astype(np.float32)
+        x = (x.view(np.int32) + rng.integers(-3, 4, 127).astype(np.int32)).view(np.float32)   # a few ulps around the tie
+        x = np.clip(x, -a, a)
+        rows.append(np.concatenate([[a], x]).astype(np.float32))
+    for _ in range(150):                                  # random rows of every magnitude
+        e = rng.integers(-120, 100)
+        rows.append((rng.standard_normal(128) * 2.0 ** e).astype(np.float32))
+    Xn = np.stack(rows)
+    assert Xn.shape[0] % 16 != 0
+    X = torch.from_numpy(Xn).to(DEV)
+    codes, scale = M.maxsim_quantize_rows_i8(X)
+    torch.cuda.synchronize()
+    rc, rs = O.quantize_rows_i8(Xn, "f32")
+    assert np.array_equal(bits(scale.cpu().numpy()), bits(rs))
+    assert np.array_equal(codes.cpu().numpy(), rc)
+
+
 def quantised_case(n_q, l_q, b, l_d, seed):
     Qf = W.unit_rows((n_q, l_q, 128), "f16", seed, DEV)
     Df = W.unit_rows((b, l_d, 128), "f32", seed + 1, DEV)

@@ -10,7 +10,10 @@
 // of the workgroup owns the rows with row % W == w and keeps their fp32 gradient in registers.
 // Every wavefront scans the argmax column [n_q * l_q entries] of each document with rows in the
 // block, picks out the edges that land on its rows and accumulates them in scan order.  No atomics, no sort, no zero-fill
-// pass over dD, and the summation order is fixed, so the result is bitwise reproducible.
+// pass over dD, and the summation order is fixed, so the result is bitwise reproducible.  With many edges per row
+// (short documents, many queries) a second kernel takes over that sorts the block's edges by row inside the
+// workgroup (a stable counting sort in LDS) and lets sixteen lanes walk each row's list: same order, same bits.
+// The explicit CSR of the paper (built in global memory, then walked by row owners) is there as an opt-in.
 #include "common.h"
 
 namespace maxsim {
@@ -334,6 +337,223 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
     }
 }
 
+// inclusive wave scan
+__device__ __forceinline__ int wave_scan_incl(int v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int u = __shfl_up(v, o);
+        if (lane >= o)
+            v += u;
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// dD by sorting inside the workgroup.  A workgroup owns R = 32 * PASSES consecutive rows of the (packed) corpus
+// and, for every document with rows in the block and every round of DS_COL argmax entries of that document's
+// column: (A) each wavefront reads a contiguous eighth of the round, notes for every entry the row of the block it
+// lands on (or none) in LDS and counts it into its own histogram over the block's rows; (B) one wavefront turns the
+// histograms into list starts and per-wavefront write cursors; (C) each wavefront walks its eighth again, 64 entries at
+// a time, ranks equal rows inside the 64 by ballots and writes the entry numbers to the row lists: a stable counting
+// sort, so every list is in entry order; (D) sixteen lanes per row (8 columns each), four rows per wavefront, walk
+// the lists with four Q rows in flight each.  The gradient of a row stays in registers until all its document's
+// rounds are done and is written once.  Same edges in the same order with the same fused multiply-add as
+// bwd_dd_kernel, hence the same bits; the difference is parallelism: every edge is touched by one wavefront
+// (bwd_dd_kernel lets all eight walk all lists) and four rows advance per load instruction.
+// ---------------------------------------------------------------------------------------
+constexpr int DS_COL = 8192;               // entries per round: an entry's number within the round fits 16 bits
+constexpr int DS_SEG = DS_COL / DD_WAVES;  // entries each wavefront sorts per round
+constexpr int DS_NONE = 0xffff;
+
+template <int DT, int PASSES>
+__global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p, uint32_t lq_magic, int lq_shift)
+{
+    constexpr int R = 32 * PASSES;
+    constexpr int RBITS = PASSES == 1 ? 5 : PASSES == 2 ? 6 : 7;
+    constexpr int EB = Elem<DT>::BYTES;
+    constexpr int ROWB = D_MODEL * EB;
+    __shared__ uint16_t ent[DS_COL];   // per entry of the round: row of the block it lands on, or DS_NONE
+    __shared__ uint16_t list[DS_COL];  // entry numbers (within the round) by row, in entry order
+    __shared__ int hist[DD_WAVES][R];  // per wavefront: entries per row, then write cursors
+    __shared__ int start[R + 1];       // list of row r: list[start[r] .. start[r + 1])
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int grp = lane >> 4, c = lane & 15;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row0 = (int64_t)blockIdx.x * R;
+    const int64_t row_end = min(row0 + R, p.total_tokens);
+
+    int64_t j_first, j_last;
+    if (p.offsets) {
+        j_first = lower_bound_offsets(p.offsets, p.b, row0 + 1) - 1;
+        j_last = lower_bound_offsets(p.offsets, p.b, row_end) - 1;
+        j_first = j_first < 0 ? 0 : j_first; // only offsets that break their contract get here
+        j_last = j_last > p.b - 1 ? p.b - 1 : j_last;
+    } else {
+        j_first = row0 / p.l_d;
+        j_last = (row_end - 1) / p.l_d;
+    }
+
+    float acc[PASSES][8];
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps)
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+            acc[ps][x] = 0.0f;
+
+    const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
+    for (int64_t j = j_first; j <= j_last; ++j) {
+        int64_t first;
+        int len;
+        if (p.offsets) {
+            first = p.offsets[j];
+            len = p.offsets[j + 1] - (int)first;
+        } else {
+            first = j * p.l_d;
+            len = p.l_d;
+        }
+        if (len <= 0)
+            continue;
+        const int t_base = (int)(row0 - first); // document-local index of the block's first row (may be negative)
+
+        for (int c0 = 0; c0 < n_entries; c0 += DS_COL) {
+            const int cn = min(DS_COL, n_entries - c0);
+            __syncthreads(); // the previous round's lists have been walked
+            for (int x = tid; x < DD_WAVES * R; x += DD_WAVES * 64)
+                (&hist[0][0])[x] = 0;
+            __syncthreads();
+            {
+                // (A) entry n = c0 + x -> (q, i); all loads are issued before the first result is used
+                constexpr int PER = DS_SEG / 64;
+                int x = w * DS_SEG + lane;
+                int n = c0 + x;
+                int q = n / p.l_q, i = n - q * p.l_q;
+                const int dq = 64 / p.l_q, di = 64 % p.l_q;
+                int t[PER];
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    t[k] = (x + k * 64) < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
+                    q += dq;
+                    i += di;
+                    if (i >= p.l_q) {
+                        i -= p.l_q;
+                        q += 1;
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < PER; ++k) {
+                    int rel = t[k] - t_base;
+                    bool in = t[k] >= 0 && t[k] < len && rel >= 0 && rel < R;
+                    ent[x + k * 64] = (uint16_t)(in ? rel : DS_NONE);
+                    if (in)
+                        atomicAdd(&hist[w][rel], 1);
+                }
+            }
+            __syncthreads();
+            if (w == 0) {
+                // (B) rows lane and lane + 64: list starts, then each wavefront's cursor within the list
+                int tot[2], cur[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int r = lane + 64 * u;
+                    tot[u] = 0;
+                    if (r < R)
+                        for (int sw = 0; sw < DD_WAVES; ++sw)
+                            tot[u] += hist[sw][r];
+                }
+                const int inc0 = wave_scan_incl(tot[0], lane);
+                const int all0 = __builtin_amdgcn_readlane(inc0, 63);
+                const int inc1 = wave_scan_incl(tot[1], lane);
+                cur[0] = inc0 - tot[0];
+                cur[1] = all0 + inc1 - tot[1];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int r = lane + 64 * u;
+                    if (r < R) {
+                        start[r] = cur[u];
+                        int run = cur[u];
+                        for (int sw = 0; sw < DD_WAVES; ++sw) {
+                            int cnt = hist[sw][r];
+                            hist[sw][r] = run;
+                            run += cnt;
+                        }
+                        if (r == R - 1)
+                            start[R] = run;
+                    }
+                }
+            }
+            __syncthreads();
+            {
+                // (C) stable placement: entries in order, equal rows ranked by lane
+                volatile int *cursor = &hist[w][0];
+                for (int k = 0; k < DS_SEG / 64; ++k) {
+                    const int x = w * DS_SEG + k * 64 + lane;
+                    const int rel = ent[x];
+                    const bool valid = rel != DS_NONE;
+                    uint64_t same = __ballot(valid);
+                    if (same == 0)
+                        continue;
+#pragma unroll
+                    for (int bit = 0; bit < RBITS; ++bit) {
+                        const bool one = (rel >> bit) & 1;
+                        const uint64_t bm = __ballot(one);
+                        same &= one ? bm : ~bm;
+                    }
+                    if (valid) {
+                        const int rank = __popcll(same & ((uint64_t(1) << lane) - 1));
+                        const int pos = cursor[rel] + rank;
+                        list[pos] = (uint16_t)x;
+                        if (rank == 0)
+                            cursor[rel] = pos + __popcll(same);
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+            __syncthreads();
+            // (D) walk the lists
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int r = ps * 32 + w * 4 + grp;
+                const int beg = start[r], end = start[r + 1];
+                constexpr int UNROLL = 4;
+                for (int k = beg; k < end; k += UNROLL) {
+                    int64_t qrow[UNROLL];
+                    float gg[UNROLL];
+                    bool on[UNROLL];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        on[u] = k + u < end;
+                        const uint32_t n = (uint32_t)c0 + (on[u] ? (uint32_t)list[k + u] : 0u); // = q * l_q + i: the Q row
+                        const uint32_t q = (uint32_t)(((uint64_t)n * lq_magic) >> lq_shift);
+                        on[u] = on[u] && q < (uint32_t)p.n_q;
+                        qrow[u] = on[u] ? (int64_t)n : 0;
+                        gg[u] = on[u] ? p.g[(int64_t)q * p.b + j] : 0.0f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        float v[8];
+                        load8<DT>(p.Q + qrow[u] * ROWB + c * 8 * EB, v);
+#pragma unroll
+                        for (int x = 0; x < 8; ++x)
+                            acc[ps][x] = on[u] ? fmaf(gg[u], v[x], acc[ps][x]) : acc[ps][x];
+                    }
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int64_t row = row0 + ps * 32 + w * 4 + grp;
+        if (row < row_end) {
+            float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
+            dst[0] = make_float4(acc[ps][0], acc[ps][1], acc[ps][2], acc[ps][3]);
+            dst[1] = make_float4(acc[ps][4], acc[ps][5], acc[ps][6], acc[ps][7]);
+        }
+    }
+}
+
 template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, hipStream_t stream)
 {
     int64_t waves = (int64_t)p.n_q * p.l_q;
@@ -344,6 +564,31 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, h
         return e;
     // blocks of 128 rows unless that leaves the chip short of workgroups (about 4 per CU wanted)
     const int64_t want = (int64_t)num_cu * 4;
+    // Many edges per dD row (short documents, many queries): the kernel that sorts inside the workgroup; few edges
+    // per row: the kernel whose wavefronts filter the lists.  Same bits either way.  Measured (L_q = 32, fp16,
+    // whole backward, sort / filter): 512 x 128 tokens 0.43 / 0.87 ms, 256 x 300 0.17 / 0.26, 256 x 64 0.13 / 0.19,
+    // 192 x 256 0.10 / 0.12, 256 x 512 0.157 / 0.166, 128 x 300 0.082 / 0.080, 512 x 1024 0.74 / 0.66,
+    // 256 x 1024 0.196 / 0.177, 64 x 180 0.047 / 0.040: the crossover is near 20 edges per row.
+    const int64_t avg_len = p.total_tokens / p.b > 0 ? p.total_tokens / p.b : 1;
+    if ((int64_t)p.n_q * p.l_q >= 20 * avg_len) {
+        // q = n / l_q for n < 2^31 as (n * magic) >> shift
+        int lg = 0;
+        while ((1 << lg) < p.l_q)
+            ++lg;
+        const int shift = 31 + lg;
+        const uint32_t magic = (uint32_t)((((uint64_t)1 << shift) + (uint64_t)p.l_q - 1) / (uint64_t)p.l_q);
+        if (p.total_tokens / 128 >= want) {
+            int64_t grid_d = (p.total_tokens + 127) / 128;
+            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 4>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
+        } else if (p.total_tokens / 64 >= want) {
+            int64_t grid_d = (p.total_tokens + 63) / 64;
+            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 2>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
+        } else {
+            int64_t grid_d = (p.total_tokens + 31) / 32;
+            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 1>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
+        }
+        return hipGetLastError();
+    }
     if (p.total_tokens / (DD_WAVES * 16) >= want) {
         int64_t grid_d = (p.total_tokens + DD_WAVES * 16 - 1) / (DD_WAVES * 16);
         hipLaunchKernelGGL((bwd_dd_kernel<DT, 16>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
@@ -435,18 +680,6 @@ __global__ void __launch_bounds__(256) csr_count_kernel(CsrParams p)
             p.row_ptr[(j + 1) * p.l_d] = part[0] + part[1] + part[2] + part[3];
         __syncthreads();
     }
-}
-
-// inclusive wave scan
-__device__ __forceinline__ int wave_scan_incl(int v, int lane)
-{
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        int u = __shfl_up(v, o);
-        if (lane >= o)
-            v += u;
-    }
-    return v;
 }
 
 __global__ void __launch_bounds__(1024) csr_scan_kernel(CsrParams p)

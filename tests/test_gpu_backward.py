@@ -53,6 +53,40 @@ def test_backward_parity(shape, dtype):
     run_case(*shape, dtype, 7)
 
 
+# Twenty or more edges per dD row on average (n_q * l_q >= 20 * l_d): the kernel that sorts the edges inside the
+# workgroup.  (n_q, l_q, b, l_d): blocks of 32 rows; 9600 column entries = two rounds; one hot row; blocks of 64 and
+# of 128 rows spanning several short documents.
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("shape", [(40, 32, 6, 50), (64, 32, 9, 33), (30, 70, 5, 100), (300, 32, 3, 70), (130, 8, 40, 5),
+                                   (33, 32, 1, 1), (70, 32, 4, 100)])
+def test_backward_many_edges_per_row(shape, dtype):
+    run_case(*shape, dtype, 17, holes=(shape[0] % 2 == 0))
+
+
+@pytest.mark.parametrize("shape", [(48, 32, 1000, 70), (48, 32, 2000, 70)])
+def test_backward_many_edges_per_row_large_blocks(shape):
+    run_case(*shape, "f16", 19)
+
+
+def test_backward_skewed_argmax():
+    """Half of the edges of every document land on four hot tokens (long row lists next to empty rows)."""
+    n_q, l_q, b, l_d = 96, 32, 7, 90
+    rng = np.random.default_rng(23)
+    Q = W.unit_rows((n_q, l_q, 128), "f16", 5, DEV)
+    D = W.unit_rows((b, l_d, 128), "f16", 6, DEV)
+    hot = rng.integers(0, l_d, (1, b, 4))
+    pick = rng.integers(0, 4, (n_q, b, l_q))
+    A = np.where(rng.random((n_q, b, l_q)) < 0.5, np.take_along_axis(np.broadcast_to(hot, (n_q, b, 4)), pick, axis=2),
+                 rng.integers(0, l_d, (n_q, b, l_q))).astype(np.int32)
+    A[rng.random(A.shape) < 0.05] = -1
+    g = rng.standard_normal((n_q, b)).astype(np.float32)
+    rQ, rD = O.backward(W.to_raw_numpy(Q), W.to_raw_numpy(D), "f16", A, g.astype(np.float64))
+    dQ, dD = M.maxsim_backward(Q, D, torch.from_numpy(A).to(DEV), torch.from_numpy(g).to(DEV))
+    torch.cuda.synchronize()
+    close(dQ, rQ, "dQ")
+    close(dD, rD, "dD")
+
+
 def test_negative_indices_are_skipped():
     run_case(4, 32, 6, 70, "f16", 9, holes=True)
 
@@ -123,6 +157,13 @@ def run_ragged_case(n_q, l_q, lens, dtype, seed):
                                   (2, 100, [0, 0, 127, 129, 128, 1, 1, 1, 0]), (9, 32, [70, 250, 64, 300, 199])])
 def test_backward_ragged_parity(case, dtype):
     run_ragged_case(*case, dtype, 13)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("case", [(40, 32, [5, 0, 64, 65, 1, 130, 0, 30] * 3), (64, 32, [20] * 30), (300, 32, [70, 1, 0, 33]),
+                                  (50, 40, [1] * 70 + [0] * 5 + [3] * 20)])
+def test_backward_ragged_many_edges_per_row(case, dtype):
+    run_ragged_case(*case, dtype, 29)
 
 
 def test_ragged_forward_argmax_feeds_ragged_backward():

@@ -91,15 +91,18 @@ def test_negative_indices_are_skipped():
     run_case(4, 32, 6, 70, "f16", 9, holes=True)
 
 
-def test_backward_is_bitwise_reproducible():
-    Q = W.unit_rows((8, 32, 128), "f16", 1, DEV)
-    D = W.unit_rows((8, 200, 128), "f16", 2, DEV)
+@pytest.mark.parametrize("n,l_d", [(8, 200), (64, 40)])      # few / many edges per dD row: both dD kernels
+def test_backward_is_bitwise_reproducible(n, l_d):
+    Q = W.unit_rows((n, 32, 128), "f16", 1, DEV)
+    D = W.unit_rows((n, l_d, 128), "f16", 2, DEV)
     s, a = M.maxsim_forward(Q, D, want_argmax=True)
-    g = torch.randn(8, 8, device=DEV, generator=torch.Generator(DEV).manual_seed(3))
+    g = torch.randn(n, n, device=DEV, generator=torch.Generator(DEV).manual_seed(3))
     r1 = M.maxsim_backward(Q, D, a, g)
     r2 = M.maxsim_backward(Q, D, a, g)
+    r3 = M.maxsim_backward_csr(Q, D, a, g)                   # the explicit CSR adds the same edges in the same order
     torch.cuda.synchronize()
     assert torch.equal(r1[0], r2[0]) and torch.equal(r1[1], r2[1])
+    assert torch.equal(r1[0], r3[0]) and torch.equal(r1[1], r3[1])
 
 
 def test_contrastive_step_small():

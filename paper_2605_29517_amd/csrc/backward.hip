@@ -261,7 +261,8 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
             }
         };
 
-        for (int c0 = 0; c0 < n_entries; c0 += DD_COL) {
+        for (int64_t c64 = 0; c64 < n_entries; c64 += DD_COL) { // 64-bit: n_entries may be within DD_COL of 2^31
+            const int c0 = (int)c64;
             const int cn = min(DD_COL, n_entries - c0);
             __syncthreads(); // the previous round's lists have been consumed
             {
@@ -269,7 +270,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
                 // n = c0 + x -> (q, i); all loads are issued before the first result is used
                 constexpr int PER = DD_SEG / 64;
                 int x = w * DD_SEG + lane;
-                int n = c0 + x;
+                int n = (int)((unsigned)c0 + (unsigned)x); // entries past the end of the column are masked below
                 int q = n / p.l_q, i = n - q * p.l_q;
                 const int dq = 64 / p.l_q, di = 64 % p.l_q;
                 int t[PER];
@@ -417,7 +418,8 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
             continue;
         const int t_base = (int)(row0 - first); // document-local index of the block's first row (may be negative)
 
-        for (int c0 = 0; c0 < n_entries; c0 += DS_COL) {
+        for (int64_t c64 = 0; c64 < n_entries; c64 += DS_COL) { // 64-bit: n_entries may be within DS_COL of 2^31
+            const int c0 = (int)c64;
             const int cn = min(DS_COL, n_entries - c0);
             __syncthreads(); // the previous round's lists have been walked
             for (int x = tid; x < DD_WAVES * R; x += DD_WAVES * 64)
@@ -427,7 +429,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
                 // (A) entry n = c0 + x -> (q, i); all loads are issued before the first result is used
                 constexpr int PER = DS_SEG / 64;
                 int x = w * DS_SEG + lane;
-                int n = c0 + x;
+                int n = (int)((unsigned)c0 + (unsigned)x); // entries past the end of the column are masked below
                 int q = n / p.l_q, i = n - q * p.l_q;
                 const int dq = 64 / p.l_q, di = 64 % p.l_q;
                 int t[PER];

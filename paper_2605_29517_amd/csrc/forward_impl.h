@@ -627,14 +627,14 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
 //
 // With documents of 64-300 tokens a sixth of the 32-row tiles is the ragged end of a document, and
 // half of such a tile is padding.  Here a 32-row window may hold the last rows of document A and, from
-// the next multiple of 8 rows on, the first rows of the next (non-empty) document B; it is cut short
+// the next multiple of 4 rows on, the first rows of the next (non-empty) document B; it is cut short
 // only where a third document would begin.  The MFMAs are the same.  The boundary sits on a multiple of
-// 8 rows because the 32x32 result keeps rows 8q .. 8q+7 in accumulator registers 4q .. 4q+3 of every
-// lane: a group of four registers then belongs to one document in all lanes, and a window with a boundary
-// folds each group into A's or B's maximum by a wavefront-uniform choice (no per-lane masks).  Such a
-// window finishes A and carries B's maximum on.  Everything else (rotating LDS buffers, pinned pipeline)
-// is fwd_tile_kernel's.  Queries have one column block here (L_q <= 32), so a wavefront's lane writes a
-// score directly and no partial sums are combined.
+// 4 rows because a lane of the 32x32 result keeps rows 8q + 4h .. 8q + 4h + 3 (h = its lane half) in
+// accumulator registers 4q .. 4q+3: a group of four registers then belongs to one document, and a window
+// with a boundary folds the maximum of each group into A's or B's maximum by one compare per group (no
+// per-row masks).  Such a window finishes A and carries B's maximum on.  Everything else (rotating LDS
+// buffers, pinned pipeline) is fwd_tile_kernel's.  Queries have one column block here (L_q <= 32), so a
+// wavefront's lane writes a score directly and no partial sums are combined.
 
 struct WinIter {
     int doc, doc_end; // document that owns the window's first row; end of the run
@@ -646,7 +646,7 @@ struct WinIter {
 
 struct Window {
     int n_a;   // rows of document A = it.doc
-    int pa;    // window row at which B starts: n_a rounded up to a multiple of 8 (rows n_a .. pa-1 repeat A's last)
+    int pa;    // window row at which B starts: n_a rounded up to a multiple of 4 (rows n_a .. pa-1 repeat A's last)
     int n_b;   // rows of document B (0: no boundary inside the window)
     int doc_b; // next non-empty document (doc_end if there is none); only known when A ends in the window
     int len_b, end_b;
@@ -720,7 +720,7 @@ __device__ __forceinline__ Window win_describe(const WinIter &it, const FwdParam
     Window w;
     w.n_a = min(TILE_ROWS, it.rem);
     w.fin_a = w.n_a == it.rem;
-    w.pa = (w.n_a + 7) & ~7;
+    w.pa = (w.n_a + 3) & ~3;
     w.n_b = 0;
     w.doc_b = it.doc_end;
     w.len_b = 0;
@@ -874,12 +874,12 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
         auto fold = [&](const f32x16 &acc, int u, float &ma, float &mbv) {
             if (u < LAG)
                 return;
-            if (BND) { // register groups 4q .. 4q+3 (rows 8q .. 8q+7) go to A below the boundary, to B from it on
+            if (BND) { // register groups 4q .. 4q+3 (rows 8q + 4h .. 8q + 4h + 3) go to A below the boundary, to B from it on
                 const int q0 = 4 * (u - LAG) / (NU - LAG), q1 = 4 * (u - LAG + 1) / (NU - LAG);
 #pragma unroll
                 for (int q = q0; q < q1; ++q) {
                     const float qm = fmaxf(fmaxf(fmaxf(acc[4 * q], acc[4 * q + 1]), acc[4 * q + 2]), acc[4 * q + 3]);
-                    const bool in_a = 8 * q < cw.pa; // the same in every lane
+                    const bool in_a = 8 * q + 4 * h < cw.pa;
                     ma = fmaxf(ma, in_a ? qm : neg_inf());
                     mbv = fmaxf(mbv, in_a ? neg_inf() : qm);
                 }

@@ -366,6 +366,10 @@ __device__ __forceinline__ int wave_scan_incl(int v, int lane)
 constexpr int DS_COL = 8192;               // entries per round: an entry's number within the round fits 16 bits
 constexpr int DS_SEG = DS_COL / DD_WAVES;  // entries each wavefront sorts per round
 constexpr int DS_NONE = 0xffff;
+constexpr int DS_LONG = 32;               // a list at least this long and twice as long as its neighbours' is walked by the whole wavefront
+#ifndef DD_SORT_MIN_EDGES
+#define DD_SORT_MIN_EDGES 20 // average edges per dD row from which the sorting kernel is used
+#endif
 
 template <int DT, int PASSES>
 __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p, uint32_t lq_magic, int lq_shift)
@@ -378,6 +382,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
     __shared__ uint16_t list[DS_COL];  // entry numbers (within the round) by row, in entry order
     __shared__ int hist[DD_WAVES][R];  // per wavefront: entries per row, then write cursors
     __shared__ int start[R + 1];       // list of row r: list[start[r] .. start[r + 1])
+    __shared__ float xfer[DD_WAVES][D_MODEL]; // one gradient row per wavefront on its way between register layouts
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int grp = lane >> 4, c = lane & 15;
@@ -517,7 +522,78 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
                 const int r = ps * 32 + w * 4 + grp;
-                const int beg = start[r], end = start[r + 1];
+                int beg = start[r], end = start[r + 1];
+                // A list much longer than the other three of the wavefront (a hot token) would leave 48 lanes idle
+                // for most of its length: the whole wavefront walks it instead, one Q row per load instruction and 16 in
+                // flight, in the same order and with the same arithmetic.  The row's gradient moves between the two
+                // register layouts (8 columns per lane of its group <-> 2 columns per lane of the wavefront) through LDS.
+                {
+                    int len_g[4], longest = 0, second = 0, who = 0;
+#pragma unroll
+                    for (int gi = 0; gi < 4; ++gi) {
+                        len_g[gi] = __builtin_amdgcn_readlane(end - beg, 16 * gi);
+                        if (len_g[gi] > longest) {
+                            second = longest;
+                            longest = len_g[gi];
+                            who = gi;
+                        } else if (len_g[gi] > second) {
+                            second = len_g[gi];
+                        }
+                    }
+                    if (longest >= DS_LONG && longest >= 2 * second) {
+                        const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
+                        const int le = lb + longest;
+                        float *xf = &xfer[w][0];
+                        if (grp == who) {
+#pragma unroll
+                            for (int x = 0; x < 8; ++x)
+                                xf[c * 8 + x] = acc[ps][x];
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        float ax = xf[2 * lane], ay = xf[2 * lane + 1];
+                        for (int k = lb; k < le; k += DD_BATCH) {
+                            // lanes 0 .. 15 look up one edge each
+                            const int kk = k + (lane & (DD_BATCH - 1));
+                            const uint32_t n = (uint32_t)c0 + (kk < le ? (uint32_t)list[kk] : 0u);
+                            const uint32_t q = (uint32_t)(((uint64_t)n * lq_magic) >> lq_shift);
+                            const bool ok = kk < le && q < (uint32_t)p.n_q;
+                            const float gv = ok ? p.g[(int64_t)q * p.b + j] : 0.0f;
+                            const int64_t roff = (int64_t)(ok ? n : 0u) * ROWB;
+                            const int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
+                            const int okv = ok ? 1 : 0;
+                            float x0[DD_BATCH], x1[DD_BATCH];
+#pragma unroll
+                            for (int u = 0; u < DD_BATCH; ++u) {
+                                const int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, u) << 32) |
+                                                    (uint32_t)__builtin_amdgcn_readlane(rlo, u);
+                                load_pair<DT>(p.Q + off, lane, x0[u], x1[u]);
+                            }
+#pragma unroll
+                            for (int u = 0; u < DD_BATCH; ++u) {
+                                if (__builtin_amdgcn_readlane(okv, u)) {
+                                    const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), u));
+                                    ax = fmaf(gg, x0[u], ax);
+                                    ay = fmaf(gg, x1[u], ay);
+                                }
+                            }
+                        }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        xf[2 * lane] = ax;
+                        xf[2 * lane + 1] = ay;
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                        if (grp == who) {
+#pragma unroll
+                            for (int x = 0; x < 8; ++x)
+                                acc[ps][x] = xf[c * 8 + x];
+                            end = beg; // done
+                        }
+                    }
+                }
                 constexpr int UNROLL = 4;
                 for (int k = beg; k < end; k += UNROLL) {
                     int64_t qrow[UNROLL];
@@ -566,13 +642,16 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, h
         return e;
     // blocks of 128 rows unless that leaves the chip short of workgroups (about 4 per CU wanted)
     const int64_t want = (int64_t)num_cu * 4;
-    // Many edges per dD row (short documents, many queries): the kernel that sorts inside the workgroup; few edges
-    // per row: the kernel whose wavefronts filter the lists.  Same bits either way.  Measured (L_q = 32, fp16,
-    // whole backward, sort / filter): 512 x 128 tokens 0.43 / 0.87 ms, 256 x 300 0.17 / 0.26, 256 x 64 0.13 / 0.19,
-    // 192 x 256 0.10 / 0.12, 256 x 512 0.157 / 0.166, 128 x 300 0.082 / 0.080, 512 x 1024 0.74 / 0.66,
-    // 256 x 1024 0.196 / 0.177, 64 x 180 0.047 / 0.040: the crossover is near 20 edges per row.
+    // Many edges per dD row (short documents, many queries) or a corpus of fewer than 128 rows per wanted workgroup:
+    // the kernel that sorts inside the workgroup; few edges per row on a large corpus: the kernel whose wavefronts
+    // filter the lists.  Same bits either way.  Measured (L_q = 32, fp16, whole backward, sort / filter):
+    // 512 x 128 tokens 0.40 / 0.90 ms, 256 x 300 0.17 / 0.27, 256 x 64 0.13 / 0.19, 192 x 256 0.10 / 0.12,
+    // 128 x 512 0.072 / 0.097, 256 x 512 0.157 / 0.166, 128 x 300 0.082 / 0.080, 64 x 180 0.050 / 0.044,
+    // 512 x 1024 0.74 / 0.66, 256 x 1024 0.206 / 0.188.  With a quarter or more of a document's edges on a few hot
+    // tokens the sorting kernel is ahead everywhere except 256 x 1024 (0.30 / 0.28 ms).
     const int64_t avg_len = p.total_tokens / p.b > 0 ? p.total_tokens / p.b : 1;
-    if ((int64_t)p.n_q * p.l_q >= 20 * avg_len) {
+    const int64_t edges = (int64_t)p.n_q * p.l_q; // per document
+    if (edges >= (int64_t)DD_SORT_MIN_EDGES * avg_len || (edges >= 8 * avg_len && p.total_tokens / 128 < want)) {
         // q = n / l_q for n < 2^31 as (n * magic) >> shift
         int lg = 0;
         while ((1 << lg) < p.l_q)

@@ -68,9 +68,9 @@ def test_backward_many_edges_per_row_large_blocks(shape):
     run_case(*shape, "f16", 19)
 
 
-def test_backward_skewed_argmax():
+@pytest.mark.parametrize("n_q,l_q,b,l_d", [(96, 32, 7, 90), (300, 32, 3, 50), (64, 32, 40, 33)])
+def test_backward_skewed_argmax(n_q, l_q, b, l_d):
     """Half of the edges of every document land on four hot tokens (long row lists next to empty rows)."""
-    n_q, l_q, b, l_d = 96, 32, 7, 90
     rng = np.random.default_rng(23)
     Q = W.unit_rows((n_q, l_q, 128), "f16", 5, DEV)
     D = W.unit_rows((b, l_d, 128), "f16", 6, DEV)
@@ -82,9 +82,11 @@ def test_backward_skewed_argmax():
     g = rng.standard_normal((n_q, b)).astype(np.float32)
     rQ, rD = O.backward(W.to_raw_numpy(Q), W.to_raw_numpy(D), "f16", A, g.astype(np.float64))
     dQ, dD = M.maxsim_backward(Q, D, torch.from_numpy(A).to(DEV), torch.from_numpy(g).to(DEV))
+    cQ, cD, _, _ = M.maxsim_backward_csr(Q, D, torch.from_numpy(A).to(DEV), torch.from_numpy(g).to(DEV))
     torch.cuda.synchronize()
     close(dQ, rQ, "dQ")
     close(dD, rD, "dD")
+    assert torch.equal(cD, dD)      # long lists are walked by a whole wavefront: same order, same bits
 
 
 def test_negative_indices_are_skipped():

@@ -876,40 +876,110 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
     }
 }
 
-// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :]
+// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :].  Sixteen lanes per row; a list
+// at least DS_LONG long and twice as long as the other three of its wavefront is walked by the whole wavefront
+// (as in bwd_dd_sort_kernel: same order, same arithmetic).
 template <int DT>
 __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
                                                         const int32_t *__restrict__ col_idx)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
+    __shared__ float xfer[4][D_MODEL];
     const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
     const int grp = lane >> 4;
     const int c = lane & 15;
     const int64_t row = ((((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) << 2) + grp;
-    if (row >= p.total_tokens)
-        return;
-    const int64_t j = row / p.l_d;
+    const bool live = row < p.total_tokens;
+    const int64_t rr = live ? row : p.total_tokens - 1;
+    const int64_t j = rr / p.l_d;
     const int64_t n_edges = (int64_t)p.n_q * p.l_q * p.b;
-    const int beg = row_ptr[row] > 0 ? row_ptr[row] : 0;
-    const int end = row_ptr[row + 1] < n_edges ? row_ptr[row + 1] : (int)n_edges;
+    int beg = row_ptr[rr] > 0 ? row_ptr[rr] : 0;
+    int end = row_ptr[rr + 1] < n_edges ? row_ptr[rr + 1] : (int)n_edges;
+    if (!live || end < beg)
+        end = beg;
     const uint32_t bl = (uint32_t)(p.b * p.l_q); // edge ids of one query
     const int64_t jl = j * p.l_q;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    // edge id -> (usable, Q row, weight) for a row of document jd
+    auto decode = [&](bool want, int e, int64_t jd, int64_t jld, bool &ok, int64_t &qrow, float &gv) {
+        int64_t rem = (want ? (int64_t)e : jld) - jld; // i * (b * l_q) + s
+        uint32_t i = (uint32_t)rem / bl;
+        uint32_t s_ = (uint32_t)rem - i * bl;
+        ok = want && rem >= 0 && rem < (int64_t(1) << 31) && i < (uint32_t)p.n_q && s_ < (uint32_t)p.l_q;
+        qrow = ok ? (int64_t)i * p.l_q + s_ : 0;
+        gv = ok ? p.g[(int64_t)i * p.b + jd] : 0.0f;
+    };
+
+    {
+        int longest = 0, second = 0, who = 0;
+#pragma unroll
+        for (int gi = 0; gi < 4; ++gi) {
+            const int len = __builtin_amdgcn_readlane(end - beg, 16 * gi);
+            if (len > longest) {
+                second = longest;
+                longest = len;
+                who = gi;
+            } else if (len > second) {
+                second = len;
+            }
+        }
+        if (longest >= DS_LONG && longest >= 2 * second) {
+            const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
+            const int le = lb + longest;
+            const int64_t row_w = ((((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) << 2) + who; // a live row
+            const int64_t jw = row_w / p.l_d;
+            const int64_t jlw = jw * p.l_q;
+            float ax = 0.0f, ay = 0.0f;
+            for (int k = lb; k < le; k += DD_BATCH) {
+                const int kk = k + (lane & (DD_BATCH - 1));
+                bool ok;
+                int64_t qrow;
+                float gv;
+                decode(kk < le, kk < le ? col_idx[kk] : 0, jw, jlw, ok, qrow, gv);
+                const int64_t roff = qrow * ROWB;
+                const int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
+                const int okv = ok ? 1 : 0;
+                float x0[DD_BATCH], x1[DD_BATCH];
+#pragma unroll
+                for (int u = 0; u < DD_BATCH; ++u) {
+                    const int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, u) << 32) |
+                                        (uint32_t)__builtin_amdgcn_readlane(rlo, u);
+                    load_pair<DT>(p.Q + off, lane, x0[u], x1[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < DD_BATCH; ++u) {
+                    if (__builtin_amdgcn_readlane(okv, u)) {
+                        const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), u));
+                        ax = fmaf(gg, x0[u], ax);
+                        ay = fmaf(gg, x1[u], ay);
+                    }
+                }
+            }
+            float *xf = &xfer[w][0];
+            xf[2 * lane] = ax;
+            xf[2 * lane + 1] = ay;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (grp == who) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    acc[x] = xf[c * 8 + x];
+                end = beg; // done
+            }
+        }
+    }
+
     constexpr int UNROLL = 4;
     for (int k = beg; k < end; k += UNROLL) {
         int64_t qrow[UNROLL];
         float gg[UNROLL];
         bool on[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            on[u] = k + u < end;
-            int64_t rem = (on[u] ? (int64_t)col_idx[k + u] : jl) - jl; // i * (b * l_q) + s
-            uint32_t i = (uint32_t)rem / bl;
-            uint32_t s = (uint32_t)rem - i * bl;
-            on[u] = on[u] && rem >= 0 && rem < (int64_t(1) << 31) && i < (uint32_t)p.n_q && s < (uint32_t)p.l_q;
-            qrow[u] = on[u] ? (int64_t)i * p.l_q + s : 0;
-            gg[u] = on[u] ? p.g[(int64_t)i * p.b + j] : 0.0f;
-        }
+        for (int u = 0; u < UNROLL; ++u)
+            decode(k + u < end, k + u < end ? col_idx[k + u] : 0, j, jl, on[u], qrow[u], gg[u]);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             float v[8];
@@ -919,9 +989,11 @@ __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32
                 acc[x] = on[u] ? fmaf(gg[u], v[x], acc[x]) : acc[x];
         }
     }
-    float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
-    dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    if (live) {
+        float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
+        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
 }
 
 hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,

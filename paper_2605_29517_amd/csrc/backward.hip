@@ -338,6 +338,42 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
     }
 }
 
+// Which of the four row lists of a wavefront (lengths len[0..3], one per group of 16 lanes) the whole wavefront
+// should walk: with the lists sorted by length, L1 >= L2 >= L3 >= L4, walking the k longest one after the other with
+// 16 rows in flight and the rest side by side with 4 in flight each costs about (L1 + .. + Lk) / 16 + L(k+1) / 4 load
+// round trips; the k that minimises this is returned (only lists of at least DS_LONG count), order[0..k) are their
+// groups.  All values are wavefront-uniform.
+constexpr int DS_LONG = 32;
+__device__ __forceinline__ int pick_long_lists(const int (&len)[4], int (&order)[4])
+{
+    int sorted[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi) {
+        int rank = 0;
+#pragma unroll
+        for (int gj = 0; gj < 4; ++gj)
+            rank += (len[gj] > len[gi] || (len[gj] == len[gi] && gj < gi)) ? 1 : 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (rank == t) {
+                order[t] = gi;
+                sorted[t] = len[gi];
+            }
+        }
+    }
+    int best_k = 0, best = 4 * sorted[0], sum = 0;
+#pragma unroll
+    for (int k = 1; k <= 4; ++k) {
+        sum += sorted[k - 1];
+        const int cost = sum + 4 * sorted[k];
+        if (sorted[k - 1] >= DS_LONG && cost < best) {
+            best = cost;
+            best_k = k;
+        }
+    }
+    return best_k;
+}
+
 // inclusive wave scan
 __device__ __forceinline__ int wave_scan_incl(int v, int lane)
 {
@@ -366,7 +402,6 @@ __device__ __forceinline__ int wave_scan_incl(int v, int lane)
 constexpr int DS_COL = 8192;               // entries per round: an entry's number within the round fits 16 bits
 constexpr int DS_SEG = DS_COL / DD_WAVES;  // entries each wavefront sorts per round
 constexpr int DS_NONE = 0xffff;
-constexpr int DS_LONG = 32;               // a list at least this long and twice as long as its neighbours' is walked by the whole wavefront
 #ifndef DD_SORT_MIN_EDGES
 #define DD_SORT_MIN_EDGES 20 // average edges per dD row from which the sorting kernel is used
 #endif
@@ -521,28 +556,22 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
             // (D) walk the lists
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
-                const int r = ps * 32 + w * 4 + grp;
+                const int r = ps * 32 + grp * DD_WAVES + w; // neighbouring rows (hot tokens often are) go to different wavefronts
                 int beg = start[r], end = start[r + 1];
-                // A list much longer than the other three of the wavefront (a hot token) would leave 48 lanes idle
-                // for most of its length: the whole wavefront walks it instead, one Q row per load instruction and 16 in
-                // flight, in the same order and with the same arithmetic.  The row's gradient moves between the two
+                // A list much longer than the others of the wavefront (a hot token) would leave 48 lanes idle for
+                // most of its length: the whole wavefront walks such lists instead, one after the other, one Q row per
+                // load instruction and 16 in flight, in the same order and with the same arithmetic.  The row's gradient moves between the two
                 // register layouts (8 columns per lane of its group <-> 2 columns per lane of the wavefront) through LDS.
                 {
-                    int len_g[4], longest = 0, second = 0, who = 0;
+                    int len_g[4], order[4];
 #pragma unroll
-                    for (int gi = 0; gi < 4; ++gi) {
+                    for (int gi = 0; gi < 4; ++gi)
                         len_g[gi] = __builtin_amdgcn_readlane(end - beg, 16 * gi);
-                        if (len_g[gi] > longest) {
-                            second = longest;
-                            longest = len_g[gi];
-                            who = gi;
-                        } else if (len_g[gi] > second) {
-                            second = len_g[gi];
-                        }
-                    }
-                    if (longest >= DS_LONG && longest >= 2 * second) {
+                    const int n_long = pick_long_lists(len_g, order);
+                    for (int t = 0; t < n_long; ++t) {
+                        const int who = t == 0 ? order[0] : t == 1 ? order[1] : t == 2 ? order[2] : order[3];
                         const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
-                        const int le = lb + longest;
+                        const int le = __builtin_amdgcn_readlane(end, 16 * who);
                         float *xf = &xfer[w][0];
                         if (grp == who) {
 #pragma unroll
@@ -592,6 +621,8 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
                                 acc[ps][x] = xf[c * 8 + x];
                             end = beg; // done
                         }
+                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // xfer is written again by the next list
+                        __builtin_amdgcn_wave_barrier();
                     }
                 }
                 constexpr int UNROLL = 4;
@@ -623,7 +654,7 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
 
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
-        const int64_t row = row0 + ps * 32 + w * 4 + grp;
+        const int64_t row = row0 + ps * 32 + grp * DD_WAVES + w;
         if (row < row_end) {
             float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
             dst[0] = make_float4(acc[ps][0], acc[ps][1], acc[ps][2], acc[ps][3]);
@@ -876,9 +907,9 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
     }
 }
 
-// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :].  Sixteen lanes per row; a list
-// at least DS_LONG long and twice as long as the other three of its wavefront is walked by the whole wavefront
-// (as in bwd_dd_sort_kernel: same order, same arithmetic).
+// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :].  Sixteen lanes per row; lists
+// much longer than the others of their wavefront are walked by the whole wavefront (as in bwd_dd_sort_kernel:
+// same order, same arithmetic).
 template <int DT>
 __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
                                                         const int32_t *__restrict__ col_idx)
@@ -889,7 +920,7 @@ __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32
     const int w = threadIdx.x >> 6;
     const int grp = lane >> 4;
     const int c = lane & 15;
-    const int64_t row = ((((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) << 2) + grp;
+    const int64_t row = (int64_t)blockIdx.x * 16 + grp * 4 + w; // neighbouring rows go to different wavefronts
     const bool live = row < p.total_tokens;
     const int64_t rr = live ? row : p.total_tokens - 1;
     const int64_t j = rr / p.l_d;
@@ -913,22 +944,16 @@ __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32
     };
 
     {
-        int longest = 0, second = 0, who = 0;
+        int len_g[4], order[4];
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) {
-            const int len = __builtin_amdgcn_readlane(end - beg, 16 * gi);
-            if (len > longest) {
-                second = longest;
-                longest = len;
-                who = gi;
-            } else if (len > second) {
-                second = len;
-            }
-        }
-        if (longest >= DS_LONG && longest >= 2 * second) {
+        for (int gi = 0; gi < 4; ++gi)
+            len_g[gi] = __builtin_amdgcn_readlane(end - beg, 16 * gi);
+        const int n_long = pick_long_lists(len_g, order);
+        for (int t = 0; t < n_long; ++t) {
+            const int who = t == 0 ? order[0] : t == 1 ? order[1] : t == 2 ? order[2] : order[3];
             const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
-            const int le = lb + longest;
-            const int64_t row_w = ((((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) << 2) + who; // a live row
+            const int le = __builtin_amdgcn_readlane(end, 16 * who);
+            const int64_t row_w = (int64_t)blockIdx.x * 16 + who * 4 + w; // a live row
             const int64_t jw = row_w / p.l_d;
             const int64_t jlw = jw * p.l_q;
             float ax = 0.0f, ay = 0.0f;
@@ -969,6 +994,8 @@ __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32
                     acc[x] = xf[c * 8 + x];
                 end = beg; // done
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // xfer is written again by the next list
+            __builtin_amdgcn_wave_barrier();
         }
     }
 

@@ -68,13 +68,15 @@ def test_backward_many_edges_per_row_large_blocks(shape):
     run_case(*shape, "f16", 19)
 
 
+@pytest.mark.parametrize("adjacent", [False, True])
 @pytest.mark.parametrize("n_q,l_q,b,l_d", [(96, 32, 7, 90), (300, 32, 3, 50), (64, 32, 40, 33)])
-def test_backward_skewed_argmax(n_q, l_q, b, l_d):
-    """Half of the edges of every document land on four hot tokens (long row lists next to empty rows)."""
+def test_backward_skewed_argmax(n_q, l_q, b, l_d, adjacent):
+    """Half of the edges of every document land on four hot tokens (long row lists next to empty rows); the hot
+    tokens anywhere in the document, or its first four (several long lists in one wavefront)."""
     rng = np.random.default_rng(23)
     Q = W.unit_rows((n_q, l_q, 128), "f16", 5, DEV)
     D = W.unit_rows((b, l_d, 128), "f16", 6, DEV)
-    hot = rng.integers(0, l_d, (1, b, 4))
+    hot = np.broadcast_to(np.arange(4), (1, b, 4)) if adjacent else rng.integers(0, l_d, (1, b, 4))
     pick = rng.integers(0, 4, (n_q, b, l_q))
     A = np.where(rng.random((n_q, b, l_q)) < 0.5, np.take_along_axis(np.broadcast_to(hot, (n_q, b, 4)), pick, axis=2),
                  rng.integers(0, l_d, (n_q, b, l_q))).astype(np.int32)

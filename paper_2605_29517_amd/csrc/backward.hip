@@ -759,6 +759,9 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
 // ---------------------------------------------------------------------------------------
 constexpr int CSR_WAVES = 8;
 constexpr int CSR_MAX_LD = 4096;
+#ifndef CSR_APPLY_WAVES
+#define CSR_APPLY_WAVES 8 // wavefronts per workgroup of csr_apply_kernel (4 rows each)
+#endif
 constexpr int CSR_LDS_EXTRA = 16; // ints after the histograms: one sum per wavefront for the block scan
 
 struct CsrParams {
@@ -911,16 +914,16 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
 // much longer than the others of their wavefront are walked by the whole wavefront (as in bwd_dd_sort_kernel:
 // same order, same arithmetic).
 template <int DT>
-__global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
+__global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
                                                         const int32_t *__restrict__ col_idx)
 {
     constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
-    __shared__ float xfer[4][D_MODEL];
+    __shared__ float xfer[CSR_APPLY_WAVES][D_MODEL];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const int grp = lane >> 4;
     const int c = lane & 15;
-    const int64_t row = (int64_t)blockIdx.x * 16 + grp * 4 + w; // neighbouring rows go to different wavefronts
+    const int64_t row = (int64_t)blockIdx.x * (4 * CSR_APPLY_WAVES) + grp * CSR_APPLY_WAVES + w; // neighbouring rows go to different wavefronts
     const bool live = row < p.total_tokens;
     const int64_t rr = live ? row : p.total_tokens - 1;
     const int64_t j = rr / p.l_d;
@@ -953,7 +956,7 @@ __global__ void __launch_bounds__(256) csr_apply_kernel(BwdParams p, const int32
             const int who = t == 0 ? order[0] : t == 1 ? order[1] : t == 2 ? order[2] : order[3];
             const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
             const int le = __builtin_amdgcn_readlane(end, 16 * who);
-            const int64_t row_w = (int64_t)blockIdx.x * 16 + who * 4 + w; // a live row
+            const int64_t row_w = (int64_t)blockIdx.x * (4 * CSR_APPLY_WAVES) + who * CSR_APPLY_WAVES + w; // a live row
             const int64_t jw = row_w / p.l_d;
             const int64_t jlw = jw * p.l_q;
             float ax = 0.0f, ay = 0.0f;
@@ -1073,8 +1076,9 @@ template <int DT> static hipError_t launch_bwd_csr(const BwdParams &p, const int
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
-    int64_t groups = (p.total_tokens + 15) / 16; // 16 rows per workgroup of 4 wavefronts
-    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups), dim3(256), 0, stream, p, row_ptr, col_idx);
+    constexpr int ROWS = 4 * CSR_APPLY_WAVES; // rows per workgroup
+    int64_t groups = (p.total_tokens + ROWS - 1) / ROWS;
+    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups), dim3(CSR_APPLY_WAVES * 64), 0, stream, p, row_ptr, col_idx);
     return hipGetLastError();
 }
 

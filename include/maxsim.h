@@ -106,8 +106,9 @@ int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed,
  *   dQ      [n_q, l_q, d] float32 fully overwritten:  dQ[q,i,:] = sum_b dscore[q,b] D[b, A[q,b,i], :]
  *   dD      [b,  l_d, d]  float32 fully overwritten:  dD[b,t,:] = sum_{(q,i): A[q,b,i]=t} dscore[q,b] Q[q,i,:]
  * Accumulation is fp32 in a fixed order: results are bitwise reproducible from run to run
- * (no atomics; every dD row is owned by one wavefront, which plays the role of the paper's
- * inverse-grid CSR without building it).
+ * (no atomics; every dD row has one owner, a wavefront or a group of sixteen lanes, which adds
+ * the row's edges in argmax order: the role of the paper's inverse-grid CSR, without building it
+ * in global memory).
  */
 int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                     maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ,

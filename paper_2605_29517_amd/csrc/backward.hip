@@ -394,8 +394,9 @@ __device__ __forceinline__ int wave_scan_incl(int v, int lane)
 // histograms into list starts and per-wavefront write cursors; (C) each wavefront walks its eighth again, 64 entries at
 // a time, ranks equal rows inside the 64 by ballots and writes the entry numbers to the row lists: a stable counting
 // sort, so every list is in entry order; (D) sixteen lanes per row (8 columns each), four rows per wavefront, walk
-// the lists with four Q rows in flight each.  The gradient of a row stays in registers until all its document's
-// rounds are done and is written once.  Same edges in the same order with the same fused multiply-add as
+// the lists with four Q rows in flight each; lists much longer than the others of their wavefront (hot tokens) are
+// walked by the whole wavefront, one after the other.  The gradient of a row stays in registers until all its
+// document's rounds are done and is written once.  Same edges in the same order with the same fused multiply-add as
 // bwd_dd_kernel, hence the same bits; the difference is parallelism: every edge is touched by one wavefront
 // (bwd_dd_kernel lets all eight walk all lists) and four rows advance per load instruction.
 // ---------------------------------------------------------------------------------------

@@ -221,10 +221,11 @@ int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float
  *
  * maxsim_probe_mfma: a register-only loop of 32x32 MFMAs with four independent accumulators,
  *   512 workgroups x 4 wavefronts, `iters` rounds of 4 instructions per wavefront.
- *   kind 0 = fp16 (32x32x16), 1 = bf16 (32x32x16), 2 = int8 (32x32x32).  `operands` is >= 1 MiB of
+ *   kind 0 = fp16 (32x32x16), 1 = bf16 (32x32x16), 2 = int8 (32x32x32), 3 = fp16 with ONE
+ *   accumulator (each MFMA waits for the one before: the cost of a dependent chain).  `operands` is >= 1 MiB of
  *   device memory whose bits are used as MFMA operands (random bits give the rate under realistic
  *   switching activity, zeros the rate at full clocks).  Operations per launch:
- *   512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1, 2*32*32*32 for kind 2).
+ *   512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1/3, 2*32*32*32 for kind 2).
  * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them.
  * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
  *   traffic for calibrating profiler byte counters.

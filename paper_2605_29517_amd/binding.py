@@ -354,7 +354,8 @@ def maxsim_ce_grad(scores, tau, g=None, loss=None):
     return g, loss
 
 
-PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32}
+PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32,
+                           3: 512 * 4 * 4 * 2 * 32 * 32 * 16}
 
 
 def maxsim_probe_mfma(kind, operands, iters, sink):

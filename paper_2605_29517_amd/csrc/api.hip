@@ -388,7 +388,7 @@ int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float
 
 int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream)
 {
-    if (!operands || !sink || iters < 1 || kind < 0 || kind > 2 || !aligned(operands, 16))
+    if (!operands || !sink || iters < 1 || kind < 0 || kind > 3 || !aligned(operands, 16))
         return MAXSIM_ERR_INVALID;
     return finish(maxsim::probe_mfma_launch(kind, operands, iters, sink, static_cast<hipStream_t>(stream)));
 }

@@ -29,7 +29,12 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(const uint4 *in, int it
     } else {
         f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
         for (int it = 0; it < iters; ++it) {
-            if (KIND == 0) {
+            if (KIND == 3) { // one dependent chain: every MFMA needs the result of the one before
+                Traits<MAXSIM_F16>::mma(a, b0, c0);
+                Traits<MAXSIM_F16>::mma(a, b1, c0);
+                Traits<MAXSIM_F16>::mma(a, b2, c0);
+                Traits<MAXSIM_F16>::mma(a, b3, c0);
+            } else if (KIND == 0) {
                 Traits<MAXSIM_F16>::mma(a, b0, c0);
                 Traits<MAXSIM_F16>::mma(a, b1, c1);
                 Traits<MAXSIM_F16>::mma(a, b2, c2);
@@ -78,6 +83,7 @@ hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *s
     switch (kind) {
     case 0: hipLaunchKernelGGL((probe_mfma_kernel<0>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     case 1: hipLaunchKernelGGL((probe_mfma_kernel<1>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
+    case 3: hipLaunchKernelGGL((probe_mfma_kernel<3>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     default: hipLaunchKernelGGL((probe_mfma_kernel<2>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     }
     return hipGetLastError();

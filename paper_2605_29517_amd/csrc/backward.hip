@@ -760,6 +760,7 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
 // ---------------------------------------------------------------------------------------
 constexpr int CSR_WAVES = 8;
 constexpr int CSR_MAX_LD = 4096;
+constexpr int CSR_LOADS = 8;      // argmax entries a lane fetches before it uses the first
 #ifndef CSR_APPLY_WAVES
 #define CSR_APPLY_WAVES 8 // wavefronts per workgroup of csr_apply_kernel (4 rows each)
 #endif
@@ -780,11 +781,18 @@ __global__ void __launch_bounds__(256) csr_count_kernel(CsrParams p)
     const int n = p.n_q * p.l_q;
     for (int64_t j = blockIdx.x; j < p.b; j += gridDim.x) {
         int cnt = 0;
-        for (int k = tid; k < n; k += 256) {
-            int i = k / p.l_q;
-            int s = k - i * p.l_q;
-            int t = p.A[((int64_t)i * p.b + j) * p.l_q + s];
-            cnt += (unsigned)t < (unsigned)p.l_d ? 1 : 0;
+        for (int64_t kb = tid; kb < n; kb += 256 * CSR_LOADS) { // CSR_LOADS entries in flight per lane
+            int t[CSR_LOADS];
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u) {
+                const int64_t k = kb + u * 256;
+                const int i = (int)(k / p.l_q);
+                const int s = (int)(k - (int64_t)i * p.l_q);
+                t[u] = k < n ? p.A[((int64_t)i * p.b + j) * p.l_q + s] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u)
+                cnt += (unsigned)t[u] < (unsigned)p.l_d ? 1 : 0;
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1)
@@ -846,12 +854,19 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
         for (int x = tid; x < CSR_WAVES * l_d; x += CSR_WAVES * 64)
             csr_lds[x] = 0;
         __syncthreads();
-        for (int64_t k = k0 + lane; k < k1; k += 64) {
-            int i = (int)(k / p.l_q);
-            int s = (int)(k - (int64_t)i * p.l_q);
-            int t = p.A[((int64_t)i * p.b + j) * p.l_q + s];
-            if ((unsigned)t < (unsigned)l_d)
-                atomicAdd(csr_lds + w * l_d + t, 1);
+        for (int64_t kb = k0 + lane; kb < k1; kb += 64 * CSR_LOADS) {
+            int t[CSR_LOADS];
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u) {
+                const int64_t k = kb + u * 64;
+                const int i = (int)(k / p.l_q);
+                const int s = (int)(k - (int64_t)i * p.l_q);
+                t[u] = k < k1 ? p.A[((int64_t)i * p.b + j) * p.l_q + s] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u)
+                if ((unsigned)t[u] < (unsigned)l_d)
+                    atomicAdd(csr_lds + w * l_d + t[u], 1);
         }
         __syncthreads();
         // exclusive scan over (t major, wavefront minor), starting at the document's first edge
@@ -878,34 +893,40 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
         }
         __syncthreads();
         // placement: entries in order, equal t ranked by lane
-        for (int64_t kb = k0; kb < k1; kb += 64) {
-            int64_t k = kb + lane;
-            int t = -1;
-            int e = 0;
-            if (k < k1) {
-                int i = (int)(k / p.l_q);
-                int s = (int)(k - (int64_t)i * p.l_q);
-                int64_t e64 = ((int64_t)i * p.b + j) * p.l_q + s;
-                t = p.A[e64];
-                e = (int)e64;
+        for (int64_t kb0 = k0; kb0 < k1; kb0 += 64 * CSR_LOADS) {
+            int tt[CSR_LOADS], ee[CSR_LOADS];
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u) { // all loads of the batch before the first is used
+                const int64_t k = kb0 + u * 64 + lane;
+                const int i = (int)(k / p.l_q);
+                const int s = (int)(k - (int64_t)i * p.l_q);
+                const int64_t e64 = ((int64_t)i * p.b + j) * p.l_q + s;
+                tt[u] = k < k1 ? p.A[e64] : -1;
+                ee[u] = (int)e64;
             }
-            const bool valid = (unsigned)t < (unsigned)l_d;
-            uint64_t same = __ballot(valid);
-            for (int bit = 0; bit < nbits; ++bit) {
-                bool one = (t >> bit) & 1;
-                uint64_t bm = __ballot(one);
-                same &= one ? bm : ~bm;
+#pragma unroll
+            for (int u = 0; u < CSR_LOADS; ++u) {
+                if (kb0 + u * 64 >= k1)
+                    break;
+                const int t = tt[u];
+                const bool valid = (unsigned)t < (unsigned)l_d;
+                uint64_t same = __ballot(valid);
+                for (int bit = 0; bit < nbits; ++bit) {
+                    bool one = (t >> bit) & 1;
+                    uint64_t bm = __ballot(one);
+                    same &= one ? bm : ~bm;
+                }
+                if (valid) {
+                    uint64_t below = same & ((uint64_t(1) << lane) - 1);
+                    int rank = __popcll(below);
+                    int pos = H[t] + rank;
+                    if ((int64_t)pos < (int64_t)n * p.b) // holds unless argmax changed since it was counted
+                        p.col_idx[pos] = ee[u];
+                    if (rank == 0)
+                        H[t] = pos + __popcll(same);
+                }
+                __builtin_amdgcn_wave_barrier();
             }
-            if (valid) {
-                uint64_t below = same & ((uint64_t(1) << lane) - 1);
-                int rank = __popcll(below);
-                int pos = H[t] + rank;
-                if ((int64_t)pos < (int64_t)n * p.b) // holds unless argmax changed since it was counted
-                    p.col_idx[pos] = e;
-                if (rank == 0)
-                    H[t] = pos + __popcll(same);
-            }
-            __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
     }

@@ -774,18 +774,18 @@ struct CsrParams {
     int n_q, l_q, l_d;
 };
 
-__global__ void __launch_bounds__(256) csr_count_kernel(CsrParams p)
+__global__ void __launch_bounds__(1024) csr_count_kernel(CsrParams p)
 {
-    __shared__ int part[4];
+    __shared__ int part[16];
     const int tid = threadIdx.x;
     const int n = p.n_q * p.l_q;
     for (int64_t j = blockIdx.x; j < p.b; j += gridDim.x) {
         int cnt = 0;
-        for (int64_t kb = tid; kb < n; kb += 256 * CSR_LOADS) { // CSR_LOADS entries in flight per lane
+        for (int64_t kb = tid; kb < n; kb += 1024 * CSR_LOADS) { // CSR_LOADS entries in flight per lane
             int t[CSR_LOADS];
 #pragma unroll
             for (int u = 0; u < CSR_LOADS; ++u) {
-                const int64_t k = kb + u * 256;
+                const int64_t k = kb + u * 1024;
                 const int i = (int)(k / p.l_q);
                 const int s = (int)(k - (int64_t)i * p.l_q);
                 t[u] = k < n ? p.A[((int64_t)i * p.b + j) * p.l_q + s] : -1;
@@ -800,8 +800,13 @@ __global__ void __launch_bounds__(256) csr_count_kernel(CsrParams p)
         if ((tid & 63) == 0)
             part[tid >> 6] = cnt;
         __syncthreads();
-        if (tid == 0)
-            p.row_ptr[(j + 1) * p.l_d] = part[0] + part[1] + part[2] + part[3];
+        if (tid == 0) {
+            int total = 0;
+#pragma unroll
+            for (int x = 0; x < 16; ++x)
+                total += part[x];
+            p.row_ptr[(j + 1) * p.l_d] = total;
+        }
         __syncthreads();
     }
 }
@@ -1079,7 +1084,7 @@ hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, 
     }
     const int64_t cap = (int64_t)num_cu * 64;
     const unsigned grid = (unsigned)(b < cap ? b : cap);
-    hipLaunchKernelGGL(csr_count_kernel, dim3(grid), dim3(256), 0, stream, c);
+    hipLaunchKernelGGL(csr_count_kernel, dim3(grid), dim3(1024), 0, stream, c);
     if ((e = hipGetLastError()) != hipSuccess)
         return e;
     hipLaunchKernelGGL(csr_scan_kernel, dim3(1), dim3(1024), 0, stream, c);

@@ -137,6 +137,13 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     // a ragged corpus (or a uniform one whose documents are not a whole number of tiles) scored by many queries of
     // one block: 32-row windows over the packed rows (no padded tiles at the ends of documents)
     const bool ragged_ends = ragged || (p.l_d % TILE_ROWS != 0 && p.b * (int64_t)p.l_d < ((int64_t)1 << 31)); // 32-bit packed rows
+    if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 8 && total_blocks <= 16) {
+        // nine to sixteen queries: the same windows with two queries per wavefront (6 % over the per-document tiles of
+        // shape 82 on the ragged 100K corpus)
+        w = 8;
+        wave_blocks = 2;
+        shape = 92;
+    }
     if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 16) {
         // as many workgroups per chunk as 32 queries each would need, then 3 or 4 queries per wavefront so that the
         // queries are spread evenly (48 queries: two workgroups of 24 rather than 32 + 16)

@@ -1037,6 +1037,8 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
                 return launch_pack<DT, 3>(p, grid, s);
             if (w == 94)
                 return launch_pack<DT, 4>(p, grid, s);
+            if (w == 92)
+                return launch_pack<DT, 2>(p, grid, s);
         }
     }
     switch (w) {

@@ -169,7 +169,7 @@ PACK_LENGTHS = {
 
 
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("f32", 64)])
-@pytest.mark.parametrize("n_q,l_q", [(17, 32), (40, 20), (64, 32), (33, 1)])
+@pytest.mark.parametrize("n_q,l_q", [(9, 32), (12, 7), (16, 32), (17, 32), (40, 20), (64, 32), (33, 1)])
 @pytest.mark.parametrize("mix", sorted(PACK_LENGTHS))
 def test_ragged_packed_windows(mix, n_q, l_q, dtype, d):
     lens = np.asarray(PACK_LENGTHS[mix] * 3)
@@ -190,7 +190,7 @@ def test_ragged_packed_windows_many_chunks():
 
 
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 64)])
-@pytest.mark.parametrize("n_q,l_q", [(17, 32), (64, 20)])
+@pytest.mark.parametrize("n_q,l_q", [(11, 32), (17, 32), (64, 20)])
 @pytest.mark.parametrize("b,l_d", [(50, 1), (33, 7), (21, 33), (40, 100), (9, 300), (700, 45)])
 def test_uniform_packed_windows(b, l_d, n_q, l_q, dtype, d):
     """Uniform corpora whose documents are not a whole number of 32-row tiles take the packed windows as well."""

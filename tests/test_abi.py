@@ -15,7 +15,7 @@ def declared_symbols():
 def test_header_declares_the_boundary():
     syms = declared_symbols()
     for name in ("maxsim_forward", "maxsim_forward_ragged", "maxsim_backward", "maxsim_quantize_rows_i8",
-                 "maxsim_forward_i8", "maxsim_strerror"):
+                 "maxsim_forward_i8", "maxsim_csr_build", "maxsim_backward_csr", "maxsim_strerror"):
         assert name in syms
 
 
@@ -51,6 +51,11 @@ def test_error_codes_without_touching_a_gpu():
     assert L.maxsim_forward_i8_ragged(p, p, 1, 32, p, p, None, 4, 100, 128, p, None) == -1  # no offsets
     assert L.maxsim_forward_i8_streamed(p, p, 1, 32, p, p, 4, 10, 128, 2, None, p, p, None) == -1  # no staging buffer
     assert L.maxsim_backward_ragged(p, 1, 1, p, p, 1, 0, 128, 1, p, p, p, p, None) == -1     # total_tokens < 1
+    assert L.maxsim_csr_build(None, 1, 1, 1, 1, p, p, None) == -1                  # no argmax
+    assert L.maxsim_csr_build(p, 2, 3, 4, 4097, p, p, None) == -2                  # documents above 4096 tokens
+    assert L.maxsim_csr_build(p, 70000, 40000, 32, 8, p, p, None) == -2            # more than 2^31 edges
+    assert L.maxsim_backward_csr(p, 1, 1, p, 1, 1, 128, 1, p, p, None, p, p, p, None) == -1   # no row_ptr
+    assert L.maxsim_backward_csr(p, 1, 1, p, 1, 1, 64, 1, p, p, p, p, p, p, None) == -2      # d = 128 only
     assert L.maxsim_forward(p, 0, 32, p, 4, 40, 128, 1, p, None, None) == -1      # n_q < 1
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 128, 7, p, None, None) == -1      # bad dtype
     assert L.maxsim_forward(ctypes.c_void_p(addr + 2), 1, 32, p, 4, 40, 128, 1, p, None, None) == -1  # misaligned

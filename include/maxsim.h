@@ -47,6 +47,7 @@ extern "C" {
 #define MAXSIM_ERR_INVALID (-1)     /* null pointer, non-positive size, misaligned pointer, bad enum */
 #define MAXSIM_ERR_UNSUPPORTED (-2) /* an embedding width or a size that the kernels are not built for */
 #define MAXSIM_ERR_LAUNCH (-3)      /* the HIP runtime reported an error at launch */
+#define MAXSIM_ERR_SCRATCH (-4)     /* sizes beyond the library's static scratch buffer (maxsim_backward_csr_static) */
 
 typedef enum { MAXSIM_F32 = 0, MAXSIM_F16 = 1, MAXSIM_BF16 = 2 } maxsim_dtype;
 
@@ -159,6 +160,22 @@ int maxsim_csr_build(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d
 int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                         maxsim_dtype dtype, const int32_t *argmax, const float *dscore,
                         int32_t *row_ptr, int32_t *col_idx, float *dQ, float *dD, void *stream);
+
+/*
+ * maxsim_backward_csr for callers that cannot allocate device memory at all (code that runs under HIP graph
+ * capture, tight serving loops, harnesses that forbid it): the same kernels, with row_ptr and col_idx in a
+ * device array that is part of the library's image (9.4 MB, one copy on every GPU the library runs on, held
+ * until the process ends) instead of caller buffers.  The call allocates and frees nothing.
+ *   Limits: b * l_d <= 262144 rows and n_q * b * l_q <= 2097152 argmax entries (config 4 exactly); larger
+ *   sizes return MAXSIM_ERR_SCRATCH and enqueue nothing.  Other arguments, limits, arithmetic and results
+ *   as maxsim_backward_csr (identical bits); the CSR itself is not returned.
+ *   All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different
+ *   streams, different host threads) race; calls on one stream are ordered and safe.  Nothing has to be
+ *   cleared between calls.  The first call on a device looks up the array's address (no allocation).
+ */
+int maxsim_backward_csr_static(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
+                               maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                               float *dD, void *stream);
 
 /*
  * Per-token symmetric absmax quantiser (Sec. "Quantised Scoring").

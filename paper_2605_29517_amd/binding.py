@@ -17,7 +17,7 @@ MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
 SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
-           "maxsim_csr_build", "maxsim_backward_csr",
+           "maxsim_csr_build", "maxsim_backward_csr", "maxsim_backward_csr_static",
            "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_forward_i8_streamed", "maxsim_ce_grad",
            "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
 
@@ -55,6 +55,8 @@ def load():
     L.maxsim_csr_build.argtypes = [p, i, l, i, i, p, p, p]
     L.maxsim_backward_csr.restype = i
     L.maxsim_backward_csr.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p, p, p]
+    L.maxsim_backward_csr_static.restype = i
+    L.maxsim_backward_csr_static.argtypes = [p, i, i, p, l, i, i, i, p, p, p, p, p]
     L.maxsim_quantize_rows_i8.restype = i
     L.maxsim_quantize_rows_i8.argtypes = [p, l, i, i, p, p, p]
     L.maxsim_forward_i8.restype = i
@@ -261,6 +263,24 @@ def maxsim_backward_csr(Q, D, argmax, dscore, row_ptr=None, col_idx=None, dQ=Non
                                    _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
     _check(rc, "maxsim_backward_csr")
     return dQ, dD, row_ptr, col_idx
+
+
+def maxsim_backward_csr_static(Q, D, argmax, dscore, dQ, dD):
+    """maxsim_backward_csr with the CSR in the library's static device array; dQ and dD are the caller's
+    (this wrapper allocates nothing either)."""
+    L = load()
+    n_q, l_q, d = Q.shape
+    b, l_d, _ = D.shape
+    if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
+        raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
+    if tuple(dQ.shape) != (n_q, l_q, d) or tuple(dD.shape) != (b, l_d, d) or D.dtype != Q.dtype or D.shape[2] != d:
+        raise MaxSimError("dQ must be [n_q,l_q,d], dD [b,l_d,d], and D must share Q's dtype and d")
+    with _on_device(Q, "Q"):
+        rc = L.maxsim_backward_csr_static(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
+                                          _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
+                                          _dev(dQ, "dQ", torch.float32), _dev(dD, "dD", torch.float32), _stream(Q))
+    _check(rc, "maxsim_backward_csr_static")
+    return dQ, dD
 
 
 def maxsim_quantize_rows_i8(X, X_i8=None, scale=None):

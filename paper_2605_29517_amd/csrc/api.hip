@@ -16,6 +16,10 @@ hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, 
 hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
                                const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
                                float *dD, int num_cu, hipStream_t stream);
+bool csr_static_fits(int n_q, int64_t b, int l_q, int l_d);
+hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+                                      const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
+                                      hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
@@ -160,6 +164,7 @@ const char *maxsim_strerror(int code)
     case MAXSIM_ERR_INVALID: return "invalid argument (null or misaligned pointer, non-positive size, bad dtype)";
     case MAXSIM_ERR_UNSUPPORTED: return "unsupported shape (d must be 128; sizes must fit the kernels' index ranges)";
     case MAXSIM_ERR_LAUNCH: return "HIP reported an error at kernel launch";
+    case MAXSIM_ERR_SCRATCH: return "sizes exceed the library's static scratch buffer (use the entry point that takes caller buffers)";
     default: return "unknown maxsim error code";
     }
 }
@@ -328,6 +333,25 @@ int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t 
         return MAXSIM_ERR_UNSUPPORTED;
     return finish(maxsim::backward_csr_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, row_ptr, col_idx, dQ,
                                               dD, num_cu(), static_cast<hipStream_t>(stream)));
+}
+
+int maxsim_backward_csr_static(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
+                               maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ, float *dD,
+                               void *stream)
+{
+    if (!Q || !D || !argmax || !dscore || !dQ || !dD || n_q < 1 || l_q < 1 || b < 1 || l_d < 1 || !dtype_ok((int)dtype))
+        return MAXSIM_ERR_INVALID;
+    if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(dQ, 16) ||
+        !aligned(dD, 16))
+        return MAXSIM_ERR_INVALID;
+    if (d != maxsim::D_MODEL)
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (!csr_shape_ok(n_q, b, l_q, l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (!maxsim::csr_static_fits(n_q, b, l_q, l_d))
+        return MAXSIM_ERR_SCRATCH;
+    return finish(maxsim::backward_csr_static_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
+                                                     static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dtype, int8_t *X_i8, float *scale,

@@ -14,6 +14,8 @@
 // (short documents, many queries) a second kernel takes over that sorts the block's edges by row inside the
 // workgroup (a stable counting sort in LDS) and lets sixteen lanes walk each row's list: same order, same bits.
 // The explicit CSR of the paper (built in global memory, then walked by row owners) is there as an opt-in.
+#include <mutex>
+
 #include "common.h"
 
 namespace maxsim {
@@ -1134,6 +1136,64 @@ hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, i
     case MAXSIM_F16: return launch_bwd_csr<MAXSIM_F16>(p, row_ptr, col_idx, stream);
     default: return launch_bwd_csr<MAXSIM_BF16>(p, row_ptr, col_idx, stream);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// The CSR backward for callers that cannot allocate (code under graph capture, serving loops): row_ptr and
+// col_idx live in a device array that is part of the library's image, one copy per GPU, held until the process
+// ends.  Every call on a GPU uses that GPU's copy: calls that overlap on one GPU race.  Nothing in it has to
+// start at zero: the build writes every row_ptr entry and every col_idx entry that the walk reads.
+// ---------------------------------------------------------------------------------------
+constexpr int64_t CSR_STATIC_MAX_ROWS = int64_t(1) << 18;  // b * l_d
+constexpr int64_t CSR_STATIC_MAX_EDGES = int64_t(1) << 21; // n_q * b * l_q
+constexpr int64_t CSR_STATIC_COL_AT = CSR_STATIC_MAX_ROWS + 64; // col_idx starts here (ints; keeps 256-byte alignment)
+static __device__ __align__(256) int32_t scratch[CSR_STATIC_COL_AT + CSR_STATIC_MAX_EDGES];
+
+namespace {
+int32_t *scratch_ptr[64] = {nullptr}; // device address of `scratch` on each GPU (the array's name is no address on the host)
+std::mutex scratch_guard;
+} // namespace
+
+// Once per device, with that device current: the address of the device's copy of `scratch`.
+static hipError_t csr_static_buffer(int32_t **out)
+{
+    std::lock_guard<std::mutex> lock(scratch_guard);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= 64)
+        return hipErrorInvalidDevice;
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return e;
+        if (!ptr)
+            return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = static_cast<int32_t *>(ptr);
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
+
+bool csr_static_fits(int n_q, int64_t b, int l_q, int l_d)
+{
+    return b * (int64_t)l_d <= CSR_STATIC_MAX_ROWS && (int64_t)n_q * l_q * b <= CSR_STATIC_MAX_EDGES;
+}
+
+hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+                                      const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
+                                      hipStream_t stream)
+{
+    if (!csr_static_fits(n_q, b, l_q, l_d))
+        return hipErrorInvalidValue;
+    int32_t *buf = nullptr;
+    hipError_t e = csr_static_buffer(&buf);
+    if (e != hipSuccess)
+        return e;
+    return backward_csr_launch(Q, n_q, l_q, D, b, l_d, dtype, argmax, dscore, buf, buf + CSR_STATIC_COL_AT, dQ, dD, num_cu,
+                               stream);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -9,15 +9,15 @@ namespace maxsim {
 hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t stream);
 bool forward_width_supported(int dtype, int d);
 hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
-                           int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                           int64_t total_tokens, int d, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
                            float *dD, int num_cu, hipStream_t stream);
 hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,
                             int32_t *col_idx, int num_cu, hipStream_t stream);
-hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, int dtype,
                                const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
                                float *dD, int num_cu, hipStream_t stream);
 bool csr_static_fits(int n_q, int64_t b, int l_q, int l_d);
-hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, int dtype,
                                       const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
                                       hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
@@ -50,6 +50,16 @@ int num_cu()
         cached[dev] = n;
     }
     return cached[dev];
+}
+
+// embedding widths of the backward entry points: whole 16-byte chunks of 8 elements, up to 64 slabs of 128 columns
+bool backward_width_ok(int d) { return d >= 8 && d <= 8192 && d % 8 == 0; }
+// the dD kernels address Q rows through 32-bit byte offsets: Q must stay below 4 GiB
+// and the dQ kernel addresses D rows through 32-bit offsets in units of 16 bytes: D must stay below 64 GiB
+bool backward_q_ok(int n_q, int l_q, int d, int dtype, int64_t total_tokens)
+{
+    const int64_t row_bytes = (int64_t)d * (dtype == MAXSIM_F32 ? 4 : 2);
+    return (int64_t)n_q * l_q * row_bytes < (int64_t(1) << 32) && total_tokens <= ((int64_t(1) << 36) - 1) / row_bytes;
 }
 
 int finish(hipError_t e) { return e == hipSuccess ? MAXSIM_OK : MAXSIM_ERR_LAUNCH; }
@@ -162,7 +172,7 @@ const char *maxsim_strerror(int code)
     switch (code) {
     case MAXSIM_OK: return "ok";
     case MAXSIM_ERR_INVALID: return "invalid argument (null or misaligned pointer, non-positive size, bad dtype)";
-    case MAXSIM_ERR_UNSUPPORTED: return "unsupported shape (d must be 128; sizes must fit the kernels' index ranges)";
+    case MAXSIM_ERR_UNSUPPORTED: return "unsupported shape (an embedding width or a size outside what this entry point is built for)";
     case MAXSIM_ERR_LAUNCH: return "HIP reported an error at kernel launch";
     case MAXSIM_ERR_SCRATCH: return "sizes exceed the library's static scratch buffer (use the entry point that takes caller buffers)";
     default: return "unknown maxsim error code";
@@ -270,12 +280,12 @@ int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, i
     if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(dQ, 16) ||
         !aligned(dD, 16))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
-        return MAXSIM_ERR_UNSUPPORTED;
-    if (b * (int64_t)l_d >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
+    if (b > ((int64_t(1) << 31) - 1) / l_d || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
         (int64_t)n_q * b >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
-    return finish(maxsim::backward_launch(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, (int)dtype, argmax, dscore,
+    if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, b * (int64_t)l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::backward_launch(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, d, (int)dtype, argmax, dscore,
                                           dQ, dD, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
@@ -289,12 +299,12 @@ int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed
     if (!aligned(Q, 16) || !aligned(D_packed, 16) || !aligned(doc_offsets, 4) || !aligned(argmax, 4) ||
         !aligned(dscore, 4) || !aligned(dQ, 16) || !aligned(dD_packed, 16))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, total_tokens))
         return MAXSIM_ERR_UNSUPPORTED;
     if (total_tokens >= (int64_t(1) << 31) || b >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
         (int64_t)n_q * b >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
-    return finish(maxsim::backward_launch(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, (int)dtype, argmax,
+    return finish(maxsim::backward_launch(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, d, (int)dtype, argmax,
                                           dscore, dQ, dD_packed, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
@@ -327,11 +337,11 @@ int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t 
     if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(row_ptr, 4) ||
         !aligned(col_idx, 4) || !aligned(dQ, 16) || !aligned(dD, 16))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
-        return MAXSIM_ERR_UNSUPPORTED;
     if (!csr_shape_ok(n_q, b, l_q, l_d))
         return MAXSIM_ERR_UNSUPPORTED;
-    return finish(maxsim::backward_csr_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, row_ptr, col_idx, dQ,
+    if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, b * (int64_t)l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    return finish(maxsim::backward_csr_launch(Q, n_q, l_q, D, b, l_d, d, (int)dtype, argmax, dscore, row_ptr, col_idx, dQ,
                                               dD, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
@@ -344,13 +354,13 @@ int maxsim_backward_csr_static(const void *Q, int n_q, int l_q, const void *D, i
     if (!aligned(Q, 16) || !aligned(D, 16) || !aligned(argmax, 4) || !aligned(dscore, 4) || !aligned(dQ, 16) ||
         !aligned(dD, 16))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
-        return MAXSIM_ERR_UNSUPPORTED;
     if (!csr_shape_ok(n_q, b, l_q, l_d))
+        return MAXSIM_ERR_UNSUPPORTED;
+    if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, b * (int64_t)l_d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (!maxsim::csr_static_fits(n_q, b, l_q, l_d))
         return MAXSIM_ERR_SCRATCH;
-    return finish(maxsim::backward_csr_static_launch(Q, n_q, l_q, D, b, l_d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
+    return finish(maxsim::backward_csr_static_launch(Q, n_q, l_q, D, b, l_d, d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
                                                      static_cast<hipStream_t>(stream)));
 }
 

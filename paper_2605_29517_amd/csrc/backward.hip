@@ -1,20 +1,19 @@
 // MaxSim backward through the stored argmax (Eqs. 2-3 of the paper) for gfx950, plus the
 // in-batch-negatives cross-entropy gradient helper.
 //
-// dQ (Eq. 2) is a collision-free gather: one wavefront per query token (q, i) walks the
-// documents, four document rows per load instruction (16 lanes x 16 bytes cover a row).
+// dQ (Eq. 2) is a collision-free gather, partitioned by documents so that every XCD's L2 serves its own
+// part of the corpus; the partial sums are combined in a fixed order.
 //
 // dD (Eq. 3) is the contended side.  The paper resolves it either with atomics or with an
 // inverse-grid CSR built by bincount / cumsum / argsort.  Here every dD row has exactly one
-// owner instead: a workgroup owns a block of consecutive rows of the (packed) corpus; wavefront w
-// of the workgroup owns the rows with row % W == w and keeps their fp32 gradient in registers.
-// Every wavefront scans the argmax column [n_q * l_q entries] of each document with rows in the
-// block, picks out the edges that land on its rows and accumulates them in scan order.  No atomics, no sort, no zero-fill
-// pass over dD, and the summation order is fixed, so the result is bitwise reproducible.  With many edges per row
-// (short documents, many queries) a second kernel takes over that sorts the block's edges by row inside the
-// workgroup (a stable counting sort in LDS) and lets sixteen lanes walk each row's list: same order, same bits.
-// The explicit CSR of the paper (built in global memory, then walked by row owners) is there as an opt-in.
+// owner instead: a workgroup owns a block of consecutive rows of the (packed) corpus, sorts the edges that land
+// in the block by row inside LDS (filter, count, scan, stable placement) and each of its wavefronts walks
+// the lists of its rows, one row after the other, all 64 lanes on one edge.  No atomics, no zero-fill
+// pass over dD, and the summation order is fixed (a row's edges by increasing edge id), so the result is
+// bitwise reproducible and equal to that of the explicit CSR of the paper, which is there as an opt-in
+// (built in global memory, then walked the same way).
 #include <mutex>
+#include <type_traits>
 
 #include "common.h"
 
@@ -41,17 +40,65 @@ template <> struct Elem<MAXSIM_BF16> {
     }
 };
 
-// 8 consecutive elements of a row, decoded to fp32
-template <int DT> __device__ __forceinline__ void load8(const char *p, float (&v)[8])
+struct BwdParams {
+    const char *Q;
+    const char *D;          // [b, l_d, d] or packed [total_tokens, d]
+    const int32_t *offsets; // [b + 1] for a packed corpus, nullptr for a uniform one
+    const int32_t *A;
+    const float *g;
+    float *dQ;
+    float *dD;              // laid out like D
+    int64_t b;
+    int64_t total_tokens;   // b * l_d for a uniform corpus
+    int n_q, l_q, l_d;
+    int d;                  // embedding width: a multiple of 8, columns are handled in slabs of 128
+};
+
+constexpr int SLAB = 128; // columns a wavefront handles (blockIdx.y selects the slab of wider rows)
+
+// n / divisor for 0 <= n < 2^31 as (n * mul) >> shift (round-up method: shift = 31 + ceil(log2(divisor)))
+struct Magic {
+    uint32_t mul;
+    int shift;
+};
+static Magic magic_u31(uint32_t divisor)
+{
+    int lg = 0;
+    while (lg < 31 && (uint32_t(1) << lg) < divisor)
+        ++lg;
+    Magic m;
+    m.shift = 31 + lg;
+    m.mul = (uint32_t)((((uint64_t)1 << m.shift) + (uint64_t)divisor - 1) / (uint64_t)divisor);
+    return m;
+}
+__device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) { return (uint32_t)(((uint64_t)n * m.mul) >> m.shift); }
+
+// f(integral_constant<int, I>) for I = BEGIN .. END-1, unrolled at compile time (for builtins that want constants)
+template <int BEGIN, int END, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>());
+        static_for<BEGIN + 1, END>(f);
+    }
+}
+
+// 8 consecutive elements of a row: the raw load and its decoding to fp32, apart, so that several loads can be in flight
+struct Raw8 {
+    uint4 a, b;
+};
+template <int DT> __device__ __forceinline__ void load_raw8(const char *p, Raw8 &r)
+{
+    r.a = *reinterpret_cast<const uint4 *>(p);
+    if (DT == MAXSIM_F32)
+        r.b = *reinterpret_cast<const uint4 *>(p + 16);
+}
+template <int DT> __device__ __forceinline__ void decode8(const Raw8 &r, float (&v)[8])
 {
     if (DT == MAXSIM_F32) {
-        float4 a = *reinterpret_cast<const float4 *>(p);
-        float4 b = *reinterpret_cast<const float4 *>(p + 16);
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
+        v[4] = __uint_as_float(r.b.x); v[5] = __uint_as_float(r.b.y); v[6] = __uint_as_float(r.b.z); v[7] = __uint_as_float(r.b.w);
     } else {
-        uint4 raw = *reinterpret_cast<const uint4 *>(p);
-        uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (DT == MAXSIM_F16) {
@@ -65,315 +112,221 @@ template <int DT> __device__ __forceinline__ void load8(const char *p, float (&v
     }
 }
 
-struct BwdParams {
-    const char *Q;
-    const char *D;          // [b, l_d, d] or packed [total_tokens, d]
-    const int32_t *offsets; // [b + 1] for a packed corpus, nullptr for a uniform one
-    const int32_t *A;
-    const float *g;
-    float *dQ;
-    float *dD;              // laid out like D
-    int64_t b;
-    int64_t total_tokens;   // b * l_d for a uniform corpus
-    int n_q, l_q, l_d;
-};
+// ---------------------------------------------------------------------------------------
+// dQ[q,i,:] = sum_j g[q,j] * D[j, A[q,j,i], :]                                      (Eq. 2)
+//
+// The documents are cut into n_part contiguous partitions and workgroup k works on partition k % n_part.
+// Workgroup ids are dealt round-robin to the 8 XCDs, so with n_part = 8 every XCD gathers rows from its own
+// eighth of the corpus only and its L2 fetches each document row once (a wavefront per query token over the whole
+// corpus makes every XCD pull most of D: 6.6 times the corpus at 256 x 256 x 1024).  A wavefront owns four
+// query tokens (one per group of sixteen lanes, 8 columns per lane) and adds its partition's documents in
+// order; the n_part partial sums of a query token are then added in partition order by bwd_dq_combine_kernel
+// (fixed order: bitwise reproducible).  n_part = 1 writes dQ directly.
+// ---------------------------------------------------------------------------------------
+constexpr int DQ_SB = 16; // documents per index fetch: one per lane of a group of sixteen
 
-// ---------------------------------------------------------------------------------------
-// dQ[q,i,:] = sum_j g[q,j] * D[j, A[q,j,i], :]
-// ---------------------------------------------------------------------------------------
-template <int DT>
-__global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p)
+// TPG = query tokens per group of sixteen lanes: 1, or 4 consecutive tokens of one query (l_q a multiple of 4: their
+// argmax entries are one 16-byte load and they share the weight).  With 4 the whole grid is resident at once at
+// 8192 query tokens, so the wavefronts of an XCD sweep the partition's documents side by side and a document row
+// that one group brought into the L2 is found there by the others.
+template <int DT, int TPG>
+__global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p, float *out, int n_part, int64_t docs_per_part)
 {
-    constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
+    constexpr int EB = Elem<DT>::BYTES;
+    constexpr int U = DT == MAXSIM_F32 ? 4 : 8; // document rows per batch of loads (two batches in flight)
+    constexpr int DPB = U / TPG > 0 ? U / TPG : 1; // documents per batch
+    static_assert(TPG == 1 || TPG == 4, "tokens per group");
+    static_assert(DPB * TPG == U, "a batch holds whole documents");
     const int lane = threadIdx.x & 63;
-    const int grp = lane >> 4; // which of 4 documents per step
-    const int c = lane & 15;   // which 8 columns of the row
-    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    if (wave >= (int64_t)p.n_q * p.l_q)
+    const int grp = lane >> 4; // which of the wavefront's four groups
+    const int c = lane & 15;   // which 8 columns of the slab
+    const int part = (int)(blockIdx.x % (unsigned)n_part);
+    const int64_t wave = (int64_t)(blockIdx.x / (unsigned)n_part) * 4 + (threadIdx.x >> 6);
+    const int64_t nql = (int64_t)p.n_q * p.l_q;
+    if (wave * 4 * TPG >= nql)
         return;
-    const int q = (int)(wave / p.l_q);
-    const int i = (int)(wave % p.l_q);
-    const int32_t *Aq = p.A + (int64_t)q * p.b * p.l_q + i;
-    const float *gq = p.g + (int64_t)q * p.b;
+    const int64_t n0 = (wave * 4 + grp) * TPG; // the group's first query token
+    const int col = (int)blockIdx.y * SLAB + c * 8;
+    const bool col_ok = col < p.d;
+    const int64_t row_bytes = (int64_t)p.d * EB;
+    const char *Dcol = p.D + (int64_t)(col_ok ? col : 0) * EB; // lanes past the row's end re-read its first columns
+    const int64_t j0 = (int64_t)part * docs_per_part;
+    const int64_t j1 = j0 + docs_per_part < p.b ? j0 + docs_per_part : p.b;
+    const int64_t nn = n0 < nql ? n0 : nql - TPG; // a group past the last token repeats the last one (nothing is stored)
+    const int q = (int)(nn / p.l_q);
+    const int i = (int)(nn - (int64_t)q * p.l_q);
+    const int32_t *Aq = p.A + (int64_t)q * p.b * p.l_q + i; // A[q, 0, i]
+    const float *gq = p.g + (int64_t)q * p.b;               // g[q, 0]
 
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    constexpr int UNROLL = 4;
-    for (int64_t j0 = 0; j0 < p.b; j0 += 4 * UNROLL) {
-        int64_t row[UNROLL]; // packed row of the winning token (row 0 with weight 0 if there is none)
-        float gg[UNROLL];
+    float acc[TPG][8];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            int64_t j = j0 + u * 4 + grp;
-            bool ok = j < p.b;
-            int tt = ok ? Aq[j * p.l_q] : -1;
-            int64_t first = 0;
-            int len = p.l_d;
-            if (ok) {
-                if (p.offsets) {
-                    first = p.offsets[j];
-                    len = p.offsets[j + 1] - (int)first;
-                } else {
-                    first = j * p.l_d;
-                }
+    for (int t = 0; t < TPG; ++t)
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            acc[t][k] = 0.0f;
+    if (j0 < j1) {
+        // Lane c of a group fetches, for document jb + c, the winning tokens and the weight and turns them into the
+        // rows' offsets in D (in units of 16 bytes: D is below 64 GiB, checked by the caller; the offset of a row that
+        // is not to be added is that of row 0) and a weight that is 0 where nothing is added; the group then takes
+        // them from each other's registers (a swizzle inside each half of the wavefront), so that one memory round trip
+        // brings the indices of 16 documents and a row costs a lane exchange or two, one address add, its load and
+        // its eight multiply-adds.
+        const uint32_t row16 = (uint32_t)(row_bytes >> 4);
+        uint32_t o[TPG];
+        float g;
+        auto fetch = [&](int64_t jb) {
+            const bool in = jb + c < j1;
+            const int64_t j = in ? jb + c : j1 - 1;
+            int64_t first;
+            int len;
+            if (p.offsets) {
+                first = p.offsets[j];
+                len = p.offsets[j + 1] - (int)first;
+            } else {
+                first = j * p.l_d;
+                len = p.l_d;
             }
-            ok = ok && tt >= 0 && tt < len && first >= 0 && first + tt < p.total_tokens; // also guards bad offsets
-            row[u] = ok ? first + tt : 0;
-            gg[u] = ok ? gq[j] : 0.0f;
-        }
+            int tt[TPG];
+            if constexpr (TPG == 4) {
+                const int4 v = *reinterpret_cast<const int4 *>(Aq + j * p.l_q);
+                tt[0] = v.x;
+                tt[1] = v.y;
+                tt[2] = v.z;
+                tt[3] = v.w;
+            } else {
+                tt[0] = Aq[j * p.l_q];
+            }
+            const float gv = gq[j];
+            g = in ? gv : 0.0f;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            float v[8];
-            load8<DT>(p.D + row[u] * ROWB + c * 8 * Elem<DT>::BYTES, v);
-#pragma unroll
-            for (int k = 0; k < 8; ++k)
-                acc[k] = fmaf(gg[u], v[k], acc[k]);
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        acc[k] += __shfl_xor(acc[k], 16);
-        acc[k] += __shfl_xor(acc[k], 32);
-    }
-    if (grp == 0) {
-        float4 *dst = reinterpret_cast<float4 *>(p.dQ + wave * D_MODEL + c * 8);
-        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// dD[j,t,:] = sum over edges (q,i) with A[q,j,i] = t of g[q,j] * Q[q,i,:]
-// ---------------------------------------------------------------------------------------
-constexpr int DD_WAVES = 8;
-// gradient rows a wavefront keeps in registers: RPW = 16 (a workgroup owns 128 consecutive rows), or 8 / 4 when the
-// corpus is too small to fill the chip with blocks of 128 rows
-constexpr int DD_COL = 8192;    // argmax entries of a document's column handled per round
-constexpr int DD_SEG = DD_COL / DD_WAVES; // entries each wavefront filters per round
-constexpr int DD_QUEUE = 128;   // edges a wavefront collects before it applies them
-constexpr int DD_BATCH = 16;    // Q rows in flight while edges are applied
-
-// two consecutive elements (2 * lane, 2 * lane + 1) of a row, decoded to fp32
-template <int DT> __device__ __forceinline__ void load_pair(const char *row, int lane, float &x0, float &x1)
-{
-    if (DT == MAXSIM_F32) {
-        float2 v = reinterpret_cast<const float2 *>(row)[lane];
-        x0 = v.x;
-        x1 = v.y;
-    } else {
-        uint32_t wv = reinterpret_cast<const uint32_t *>(row)[lane];
-        if (DT == MAXSIM_F16) {
-            x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv & 0xffffu));
-            x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(wv >> 16));
-        } else {
-            x0 = __uint_as_float(wv << 16);
-            x1 = __uint_as_float(wv & 0xffff0000u);
-        }
-    }
-}
-
-// A workgroup owns 128 consecutive rows of the (packed) corpus, whichever documents they belong
-// to.  Wavefront w owns the rows row0 + 8 * r + w (r = 0..15) and keeps them in registers: lane
-// l holds columns 2l, 2l+1 of each.  For every document that has rows in the block, per round:
-// (1) each wavefront reads an eighth of DD_COL entries of that document's argmax column and
-// writes those that land in this block, compacted by ballot and in entry order, to its list in
-// LDS; (2) every wavefront walks the eight lists in order and queues the edges that land on its
-// rows; (3) when a queue holds 64 edges, the 64 lanes look up
-// q, i, g and the Q row address of one edge each, and the edges are then applied in order, 16
-// Q-row loads in flight, the target row picked by a wavefront-uniform register index
-// (s_set_gpr_idx).  Every row has one owner and a fixed order of accumulation (entry order), so
-// the result is bitwise reproducible; there are no atomics, no sort and no zero-fill pass.
-template <int DT, int RPW>
-__global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_kernel(BwdParams p)
-{
-    constexpr int DD_ROWS_PER_WAVE = RPW;
-    constexpr int DD_TOKENS = DD_WAVES * RPW;
-    constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
-    __shared__ int seg[DD_WAVES][DD_SEG]; // per filtering wavefront: the round's edges into this block, in entry order
-    __shared__ int seg_len[DD_WAVES];
-    __shared__ int queue[DD_WAVES][DD_QUEUE];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t row0 = (int64_t)blockIdx.x * DD_TOKENS;
-    const int64_t row_end = min(row0 + DD_TOKENS, p.total_tokens);
-
-    // documents with rows in [row0, row_end): the last document that starts at or before a row owns it
-    int64_t j_first, j_last;
-    if (p.offsets) {
-        j_first = lower_bound_offsets(p.offsets, p.b, row0 + 1) - 1;
-        j_last = lower_bound_offsets(p.offsets, p.b, row_end) - 1;
-        j_first = j_first < 0 ? 0 : j_first; // only offsets that break their contract get here
-        j_last = j_last > p.b - 1 ? p.b - 1 : j_last;
-    } else {
-        j_first = row0 / p.l_d;
-        j_last = (row_end - 1) / p.l_d;
-    }
-
-    typedef float rowvec __attribute__((ext_vector_type(DD_ROWS_PER_WAVE)));
-    rowvec ax, ay; // ax[r], ay[r]: columns 2 * lane, 2 * lane + 1 of owned row r
-#pragma unroll
-    for (int r = 0; r < DD_ROWS_PER_WAVE; ++r) {
-        ax[r] = 0.0f;
-        ay[r] = 0.0f;
-    }
-
-    const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
-    for (int64_t j = j_first; j <= j_last; ++j) {
-        int64_t first;
-        int len;
-        if (p.offsets) {
-            first = p.offsets[j];
-            len = p.offsets[j + 1] - (int)first;
-        } else {
-            first = j * p.l_d;
-            len = p.l_d;
-        }
-        if (len == 0)
-            continue;
-        const int t_base = (int)(row0 - first); // document-local index of the block's first row (may be negative)
-
-        // apply the first `cnt` (<= 64) queued edges of this wavefront
-        auto process = [&](int cnt, int c0) {
-            int packed = lane < cnt ? queue[w][lane] : 0;
-            int n = c0 + (packed & 0xffff);
-            int rel = packed >> 16;
-            int q = n / p.l_q;
-            int i = n - q * p.l_q;
-            float gv = lane < cnt ? p.g[(int64_t)q * p.b + j] : 0.0f;
-            int64_t roff = ((int64_t)q * p.l_q + i) * ROWB;
-            int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
-            for (int e0 = 0; e0 < cnt; e0 += DD_BATCH) {
-                float x0[DD_BATCH], x1[DD_BATCH];
-#pragma unroll
-                for (int k = 0; k < DD_BATCH; ++k) {
-                    int e = e0 + k < cnt ? e0 + k : cnt - 1; // past the end: a harmless re-read of the last row
-                    int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, e) << 32) |
-                                  (uint32_t)__builtin_amdgcn_readlane(rlo, e);
-                    load_pair<DT>(p.Q + off, lane, x0[k], x1[k]);
-                }
-#pragma unroll
-                for (int k = 0; k < DD_BATCH; ++k) {
-                    if (e0 + k < cnt) {
-                        float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), e0 + k));
-                        int r = __builtin_amdgcn_readlane(rel, e0 + k) >> 3; // rel = 8 * r + w
-                        ax[r] = fmaf(gg, x0[k], ax[r]); // r is uniform: indexed register access, no branch
-                        ay[r] = fmaf(gg, x1[k], ay[r]);
-                    }
-                }
+            for (int t = 0; t < TPG; ++t) {
+                // also guards bad offsets; the row's weight is the document's unless the row is row 0 by default
+                const bool ok = tt[t] >= 0 && tt[t] < len && first >= 0 && first + tt[t] < p.total_tokens;
+                o[t] = ok ? (uint32_t)(first + tt[t]) * row16 : 0xffffffffu;
             }
         };
-
-        for (int64_t c64 = 0; c64 < n_entries; c64 += DD_COL) { // 64-bit: n_entries may be within DD_COL of 2^31
-            const int c0 = (int)c64;
-            const int cn = min(DD_COL, n_entries - c0);
-            __syncthreads(); // the previous round's lists have been consumed
-            {
-                // (1) wavefront w filters entries [w * DD_SEG, (w + 1) * DD_SEG) of the round: entry
-                // n = c0 + x -> (q, i); all loads are issued before the first result is used
-                constexpr int PER = DD_SEG / 64;
-                int x = w * DD_SEG + lane;
-                int n = (int)((unsigned)c0 + (unsigned)x); // entries past the end of the column are masked below
-                int q = n / p.l_q, i = n - q * p.l_q;
-                const int dq = 64 / p.l_q, di = 64 % p.l_q;
-                int t[PER];
+        fetch(j0);
+        for (int64_t jb = j0; jb < j1; jb += DQ_SB) {
+            uint32_t co[TPG];
 #pragma unroll
-                for (int k = 0; k < PER; ++k) {
-                    t[k] = (x + k * 64) < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
-                    q += dq;
-                    i += di;
-                    if (i >= p.l_q) {
-                        i -= p.l_q;
-                        q += 1;
-                    }
-                }
-                int kept = 0;
+            for (int t = 0; t < TPG; ++t)
+                co[t] = o[t];
+            const float cg = g;
+            fetch(jb + DQ_SB); // the next 16 documents' indices travel while these documents' rows do
+            Raw8 raw[2][U];
+            float gc[2][U];
+            auto issue = [&](auto batch_tag, Raw8(&dst)[U], float(&w)[U]) {
+                constexpr int m0 = decltype(batch_tag)::value * DPB;
+                static_for<0, U>([&](auto u_tag) {
+                    constexpr int u = decltype(u_tag)::value;
+                    constexpr int t = u % TPG;
+                    constexpr int m = m0 + u / TPG;
+                    // ds_swizzle, bit mode (and_mask | or_mask << 5 | xor_mask << 10 on the lane id inside each half of
+                    // the wavefront): keep which group of sixteen, take lane m of it
+                    constexpr int pat = 0x10 | ((m & 15) << 5);
+                    const uint32_t off16 = (uint32_t)__builtin_amdgcn_ds_swizzle((int)co[t], pat);
+                    const float gg = __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(cg), pat));
+                    w[u] = off16 == 0xffffffffu ? 0.0f : gg;
+                    load_raw8<DT>(Dcol + ((uint64_t)(off16 == 0xffffffffu ? 0u : off16) << 4), dst[u]);
+                });
+            };
+            auto consume = [&](const Raw8(&src)[U], const float(&w)[U]) {
 #pragma unroll
-                for (int k = 0; k < PER; ++k) {
-                    int rel = t[k] - t_base;
-                    bool in = t[k] >= 0 && t[k] < len && rel >= 0 && rel < DD_TOKENS;
-                    unsigned long long mask = __ballot(in);
-                    int before =
-                        __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-                    if (in)
-                        seg[w][kept + before] = (x + k * 64) | (rel << 16);
-                    kept += __builtin_popcountll(mask);
+                for (int u = 0; u < U; ++u) {
+                    float v[8];
+                    decode8<DT>(src[u], v);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        acc[u % TPG][k] = fmaf(w[u], v[k], acc[u % TPG][k]);
                 }
-                if (lane == 0)
-                    seg_len[w] = kept;
-            }
-            __syncthreads();
-            // (2) every wavefront walks the eight lists in order and queues the edges on its rows
-            int qlen = 0;
-            for (int sw = 0; sw < DD_WAVES; ++sw) {
-                const int sn = __builtin_amdgcn_readfirstlane(seg_len[sw]);
-                for (int e0 = 0; e0 < sn; e0 += 64) {
-                    int ent = e0 + lane < sn ? seg[sw][e0 + lane] : -1;
-                    bool mine = ent >= 0 && ((ent >> 16) & (DD_WAVES - 1)) == w;
-                    unsigned long long mask = __ballot(mine);
-                    if (mask == 0)
-                        continue;
-                    int before =
-                        __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-                    if (mine)
-                        queue[w][qlen + before] = ent;
-                    qlen += __builtin_popcountll(mask);
-                    if (qlen >= 64) {
-                        process(64, c0);
-                        int rest = qlen - 64; // at most 63 edges move to the front
-                        int moved = lane < rest ? queue[w][64 + lane] : 0;
-                        if (lane < rest)
-                            queue[w][lane] = moved;
-                        qlen = rest;
-                    }
-                }
-            }
-            if (qlen > 0)
-                process(qlen, c0);
+            };
+            // batches of DPB documents, two in flight; documents past the partition carry weight 0 (their rows are
+            // the last document's)
+            constexpr int NBATCH = DQ_SB / DPB;
+            issue(std::integral_constant<int, 0>(), raw[0], gc[0]);
+            static_for<0, NBATCH>([&](auto b_tag) {
+                constexpr int bi = decltype(b_tag)::value;
+                if constexpr (bi + 1 < NBATCH)
+                    issue(std::integral_constant<int, bi + 1>(), raw[(bi + 1) & 1], gc[(bi + 1) & 1]);
+                consume(raw[bi & 1], gc[bi & 1]);
+            });
         }
     }
-
+    if (col_ok) {
 #pragma unroll
-    for (int r = 0; r < DD_ROWS_PER_WAVE; ++r) {
-        int64_t row = row0 + r * DD_WAVES + w;
-        if (row < row_end)
-            reinterpret_cast<float2 *>(p.dD + row * D_MODEL)[lane] = make_float2(ax[r], ay[r]);
+        for (int t = 0; t < TPG; ++t) {
+            if (n0 + t < nql) {
+                float4 *dst = reinterpret_cast<float4 *>(out + ((int64_t)part * nql + n0 + t) * p.d + col);
+                dst[0] = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+                dst[1] = make_float4(acc[t][4], acc[t][5], acc[t][6], acc[t][7]);
+            }
+        }
     }
 }
 
-// Which of the four row lists of a wavefront (lengths len[0..3], one per group of 16 lanes) the whole wavefront
-// should walk: with the lists sorted by length, L1 >= L2 >= L3 >= L4, walking the k longest one after the other with
-// 16 rows in flight and the rest side by side with 4 in flight each costs about (L1 + .. + Lk) / 16 + L(k+1) / 4 load
-// round trips; the k that minimises this is returned (only lists of at least DS_LONG count), order[0..k) are their
-// groups.  All values are wavefront-uniform.
-constexpr int DS_LONG = 32;
-__device__ __forceinline__ int pick_long_lists(const int (&len)[4], int (&order)[4])
+// dQ = part[0] + part[1] + ... + part[n_part - 1], in that order; n4 = float4s per partial = n_q * l_q * d / 4
+__global__ void __launch_bounds__(256) bwd_dq_combine_kernel(const float4 *part, float4 *dQ, int64_t n4, int n_part)
 {
-    int sorted[5] = {0, 0, 0, 0, 0};
-#pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-        int rank = 0;
-#pragma unroll
-        for (int gj = 0; gj < 4; ++gj)
-            rank += (len[gj] > len[gi] || (len[gj] == len[gi] && gj < gi)) ? 1 : 0;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if (rank == t) {
-                order[t] = gi;
-                sorted[t] = len[gi];
-            }
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n4; x += (int64_t)gridDim.x * 256) {
+        float4 s = part[x];
+        for (int k = 1; k < n_part; ++k) {
+            const float4 v = part[(int64_t)k * n4 + x];
+            s.x += v.x;
+            s.y += v.y;
+            s.z += v.z;
+            s.w += v.w;
         }
+        dQ[x] = s;
     }
-    int best_k = 0, best = 4 * sorted[0], sum = 0;
-#pragma unroll
-    for (int k = 1; k <= 4; ++k) {
-        sum += sorted[k - 1];
-        const int cost = sum + 4 * sorted[k];
-        if (sorted[k - 1] >= DS_LONG && cost < best) {
-            best = cost;
-            best_k = k;
-        }
+}
+
+// ---------------------------------------------------------------------------------------
+// dD[j,t,:] = sum over edges (q,i) with A[q,j,i] = t of g[q,j] * Q[q,i,:]              (Eq. 3)
+//
+// A workgroup owns R = 8 * RPW consecutive rows of the (packed) corpus, whichever documents they belong to;
+// wavefront w owns the rows row0 + 8 * s + w (s = 0 .. RPW-1; neighbouring rows, often hot together, go to
+// different wavefronts).  For every document with rows in the block and every round of DW_COL entries of that
+// document's argmax column:
+//   (1) filter: each wavefront reads a contiguous eighth of the round, keeps the entries that land in the block,
+//       compacted by ballot in entry order, and counts them per row into its own histogram (LDS);
+//   (2) scan: the histograms become list starts per row and a write cursor per (row, filtering wavefront);
+//   (3) place: each wavefront ranks its kept entries, 64 at a time, among equal rows by log2(R) ballots and
+//       writes the entry numbers to the row lists -- a stable counting sort, so a row's list is in entry order and
+//       the lists of a wavefront's rows are contiguous;
+//   (4) walk: every wavefront walks its contiguous range of the sorted entries, ALL 64 lanes on one edge at a
+//       time (two columns per lane): per 64 edges one vector step looks up (Q row, weight), then the edges are
+//       applied in order with 16 Q-row loads in flight, addresses and weights passed through scalar registers;
+//       the running row lives in two fixed registers and is written when the walk crosses into the next row's
+//       list (empty rows get zeros).
+// Every row has one owner and its edges are added in entry order with one fused multiply-add each, starting
+// from zero: the same bits as the explicit CSR walk, on every run.  No atomics decide anything, no zero-fill
+// pass.  Columns beyond 128 are further slabs (blockIdx.y) that repeat the integer work.  If a document has more
+// than DW_COL entries, later rounds continue from the value the earlier ones wrote.
+// ---------------------------------------------------------------------------------------
+constexpr int DD_WAVES = 8;
+constexpr int DW_COL = 8192;              // entries per round: an entry's number within the round fits 16 bits
+constexpr int DD_BATCH = 16;              // Q rows in flight while edges are applied
+
+// two consecutive elements of a row as loaded (decoded when they are used, so that an edge in flight holds one
+// register for 16-bit rows)
+template <int DT> struct RawPair {
+    typedef uint32_t type;
+};
+template <> struct RawPair<MAXSIM_F32> {
+    typedef float type __attribute__((ext_vector_type(2)));
+};
+template <int DT> __device__ __forceinline__ void decode_pair(typename RawPair<DT>::type r, float &x0, float &x1)
+{
+    if constexpr (DT == MAXSIM_F32) {
+        x0 = r.x;
+        x1 = r.y;
+    } else if constexpr (DT == MAXSIM_F16) {
+        x0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(r & 0xffffu));
+        x1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(r >> 16));
+    } else {
+        x0 = __uint_as_float(r << 16);
+        x1 = __uint_as_float(r & 0xffff0000u);
     }
-    return best_k;
 }
 
 // inclusive wave scan
@@ -388,45 +341,163 @@ __device__ __forceinline__ int wave_scan_incl(int v, int lane)
     return v;
 }
 
-// ---------------------------------------------------------------------------------------
-// dD by sorting inside the workgroup.  A workgroup owns R = 32 * PASSES consecutive rows of the (packed) corpus
-// and, for every document with rows in the block and every round of DS_COL argmax entries of that document's
-// column: (A) each wavefront reads a contiguous eighth of the round, notes for every entry the row of the block it
-// lands on (or none) in LDS and counts it into its own histogram over the block's rows; (B) one wavefront turns the
-// histograms into list starts and per-wavefront write cursors; (C) each wavefront walks its eighth again, 64 entries at
-// a time, ranks equal rows inside the 64 by ballots and writes the entry numbers to the row lists: a stable counting
-// sort, so every list is in entry order; (D) sixteen lanes per row (8 columns each), four rows per wavefront, walk
-// the lists with four Q rows in flight each; lists much longer than the others of their wavefront (hot tokens) are
-// walked by the whole wavefront, one after the other.  The gradient of a row stays in registers until all its
-// document's rounds are done and is written once.  Same edges in the same order with the same fused multiply-add as
-// bwd_dd_kernel, hence the same bits; the difference is parallelism: every edge is touched by one wavefront
-// (bwd_dd_kernel lets all eight walk all lists) and four rows advance per load instruction.
-// ---------------------------------------------------------------------------------------
-constexpr int DS_COL = 8192;               // entries per round: an entry's number within the round fits 16 bits
-constexpr int DS_SEG = DS_COL / DD_WAVES;  // entries each wavefront sorts per round
-constexpr int DS_NONE = 0xffff;
-#ifndef DD_SORT_MIN_EDGES
-#define DD_SORT_MIN_EDGES 20 // average edges per dD row from which the sorting kernel is used
-#endif
+template <int N> struct RowVec {
+    typedef float type __attribute__((ext_vector_type(N)));
+};
 
-template <int DT, int PASSES>
-__global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p, uint32_t lq_magic, int lq_shift)
+// Raw buffer descriptor over the Q tensor (base, size in bytes; untyped dwords): loads take a per-lane byte
+// offset from a vector register plus a per-edge byte offset from a scalar register, so an edge's row costs one
+// lane read and one load instruction; offsets past the size read as zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t q_resource(const char *Q, uint32_t bytes)
 {
-    constexpr int R = 32 * PASSES;
-    constexpr int RBITS = PASSES == 1 ? 5 : PASSES == 2 ? 6 : 7;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Q), 0, (int)bytes, 0x00020000);
+}
+template <int DT> __device__ __forceinline__ typename RawPair<DT>::type load_raw_pair(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t row_off)
+{
+    if constexpr (DT == MAXSIM_F32) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(typename RawPair<DT>::type,
+                                  (u32x2)__builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)row_off, 0));
+    } else {
+        return __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)lane_off, (int)row_off, 0);
+    }
+}
+
+// The walk shared by bwd_dd_kernel and csr_apply_kernel.  Edges k_lo .. k_hi of an array sorted by row belong to
+// NROWS consecutive lists; lane s of `boundv` holds where the list of row slot s starts (s = 0 .. NROWS, the last
+// one = k_hi).  rx[s], ry[s] are the lane's two columns of row slot s.  Per 64 edges (one per lane) a vector step
+// looks up the Q row and the weight (`lookup(k, valid, n, gv)`) and finds the edge's row slot by a binary search
+// over boundv; the edges are then applied one after the other by all 64 lanes, 16 Q-row loads in flight while the
+// 16 before them are added (two register sets); the row's byte offset and the weight reach the instructions
+// through scalar registers.  The running row lives in two fixed registers and moves to / from its slot (register
+// index from a scalar) at the edges where a ballot says the row changes, so the per-edge work is a compare, two
+// lane reads, a load and two fused multiply-adds, and the chain holds no memory operation besides the loads.
+// Edges past the last one (the rest of the last batch) carry weight 0; their Q rows are rows of other lists, or,
+// past the end of the edge array, whatever offset the lookup makes of it: the buffer descriptor turns a read
+// outside Q into zeros.
+template <int DT, int NROWS, typename Lookup>
+__device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int lane, uint32_t lane_off, int k_lo,
+                                          int k_hi, int boundv, Lookup lookup, typename RowVec<NROWS>::type &rx,
+                                          typename RowVec<NROWS>::type &ry)
+{
+    typedef typename RawPair<DT>::type raw_t;
+    static_assert(DD_BATCH == 16, "four batches per vector step");
+    if (k_lo >= k_hi)
+        return;
+    auto look = [&](int k0, uint32_t &off, float &gv, int &sv) {
+        const int kk = k0 + lane;
+        uint32_t n;
+        lookup(kk, kk < k_hi, n, gv);
+        off = n * row_bytes; // < 2^32 (checked by the caller)
+        int s = 0;           // the largest slot whose list starts at or before kk
+#pragma unroll
+        for (int step = NROWS / 2; step > 0; step >>= 1) {
+            const int bnd = __shfl(boundv, s + step);
+            s = bnd <= kk ? s + step : s;
+        }
+        sv = s;
+    };
+    auto issue = [&](raw_t(&dst)[DD_BATCH], uint32_t offv, int e0) {
+#pragma unroll
+        for (int u = 0; u < DD_BATCH; ++u)
+            dst[u] = load_raw_pair<DT>(rsrc, lane_off, (uint32_t)__builtin_amdgcn_readlane((int)offv, e0 + u));
+    };
+    uint32_t o_cur, o_nxt;
+    float g_cur, g_nxt;
+    int sv_cur, sv_nxt;
+    raw_t xb[2][DD_BATCH];
+    look(k_lo, o_cur, g_cur, sv_cur);
+    issue(xb[0], o_cur, 0);
+    int s_now = __builtin_amdgcn_readlane(sv_cur, 0);
+    int s_carry = s_now;
+    float ax = rx[s_now], ay = ry[s_now];
+    // One batch of 16 edges: the lane reads use compile-time lanes; edges past k_hi have weight 0.
+    auto consume = [&](const raw_t(&src)[DD_BATCH], int e0, uint64_t &bmask, int &next_b) {
+#pragma unroll
+        for (int u = 0; u < DD_BATCH; ++u) {
+            const int e = e0 + u;
+            if (e == next_b) {
+                const int s_new = __builtin_amdgcn_readlane(sv_cur, e);
+                rx[s_now] = ax;
+                ry[s_now] = ay;
+                ax = rx[s_new];
+                ay = ry[s_new];
+                s_now = s_new;
+                bmask &= bmask - 1;
+                next_b = bmask ? (int)__builtin_ctzll(bmask) : 64;
+            }
+            const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g_cur), e));
+            float x0, x1;
+            decode_pair<DT>(src[u], x0, x1);
+            ax = fmaf(gg, x0, ax);
+            ay = fmaf(gg, x1, ay);
+        }
+    };
+    // Every step issues the loads of the next batch, then adds the current one; the loop is left (never
+    // rejoined) once the batch that holds the last edge has been added, so the only loads wasted are one batch.
+    for (int k0 = k_lo;; k0 += 64) {
+        look(k0 + 64, o_nxt, g_nxt, sv_nxt);
+        int prev = __shfl_up(sv_cur, 1);
+        prev = lane == 0 ? s_carry : prev;
+        uint64_t bmask = __ballot(sv_cur != prev); // edges that begin another row's list
+        int next_b = bmask ? (int)__builtin_ctzll(bmask) : 64;
+        issue(xb[1], o_cur, DD_BATCH);
+        consume(xb[0], 0, bmask, next_b);
+        if (k0 + DD_BATCH >= k_hi)
+            break;
+        issue(xb[0], o_cur, 2 * DD_BATCH);
+        consume(xb[1], DD_BATCH, bmask, next_b);
+        if (k0 + 2 * DD_BATCH >= k_hi)
+            break;
+        issue(xb[1], o_cur, 3 * DD_BATCH);
+        consume(xb[0], 2 * DD_BATCH, bmask, next_b);
+        if (k0 + 3 * DD_BATCH >= k_hi)
+            break;
+        issue(xb[0], o_nxt, 0);
+        consume(xb[1], 3 * DD_BATCH, bmask, next_b);
+        if (k0 + 4 * DD_BATCH >= k_hi)
+            break;
+        s_carry = __builtin_amdgcn_readlane(sv_cur, 63);
+        o_cur = o_nxt;
+        g_cur = g_nxt;
+        sv_cur = sv_nxt;
+    }
+    rx[s_now] = ax;
+    ry[s_now] = ay;
+}
+
+template <int DT, int RPW, int W>
+__global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr off, Magic lq_magic, int n_blocks)
+{
+    constexpr int R = W * RPW;          // rows of the block
+    constexpr int WBITS = W == 16 ? 4 : 3;
+    constexpr int RBITS = WBITS + (RPW == 16 ? 4 : RPW == 8 ? 3 : 2);
+    constexpr int SEG = DW_COL / W;     // entries each wavefront filters per round
+    constexpr int KPL = (R + 63) / 64;  // keys per lane in the scan
+    static_assert(RPW == 16 || RPW == 8 || RPW == 4, "rows per wavefront");
+    static_assert(W == 8 || W == 16, "wavefronts per workgroup");
     constexpr int EB = Elem<DT>::BYTES;
-    constexpr int ROWB = D_MODEL * EB;
-    __shared__ uint16_t ent[DS_COL];   // per entry of the round: row of the block it lands on, or DS_NONE
-    __shared__ uint16_t list[DS_COL];  // entry numbers (within the round) by row, in entry order
-    __shared__ int hist[DD_WAVES][R];  // per wavefront: entries per row, then write cursors
-    __shared__ int start[R + 1];       // list of row r: list[start[r] .. start[r + 1])
-    __shared__ float xfer[DD_WAVES][D_MODEL]; // one gradient row per wavefront on its way between register layouts
+    __shared__ uint32_t seg[W][SEG]; // per filtering wavefront: kept entries, (number in round) | key << 16
+    __shared__ uint16_t list[DW_COL];          // entry numbers by key, in entry order
+    __shared__ int hist[W][R];          // per filtering wavefront: entries per key, then write cursors
+    __shared__ int start[R + 1];               // list of key k: list[start[k] .. start[k + 1])
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int grp = lane >> 4, c = lane & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t row0 = (int64_t)blockIdx.x * R;
+    // Workgroup ids are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of blocks, so that the
+    // blocks of one document, which all read that document's argmax column, share an L2.
+    const int per_xcd = (n_blocks + 7) >> 3;
+    const int blk = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (blk >= n_blocks)
+        return;
+    const int64_t row0 = (int64_t)blk * R;
     const int64_t row_end = min(row0 + R, p.total_tokens);
+    const int col = (int)blockIdx.y * SLAB + 2 * lane;
+    const bool col_ok = col < p.d;
+    // lanes past the row's end re-read its first columns and store nothing
+    const uint32_t lane_off = (uint32_t)((col_ok ? 2 * lane : 0) + (int)blockIdx.y * SLAB) * EB;
+    const uint32_t row_bytes = (uint32_t)p.d * EB;
+    const __amdgpu_buffer_rsrc_t rsrc = q_resource(p.Q, (uint32_t)p.n_q * (uint32_t)p.l_q * row_bytes); // < 2^32 (checked by the caller)
 
     int64_t j_first, j_last;
     if (p.offsets) {
@@ -439,20 +510,25 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
         j_last = (row_end - 1) / p.l_d;
     }
 
-    float acc[PASSES][8];
+    // the gradient rows of this wavefront (slot s = row row0 + W * s + w), two columns per lane
+    typename RowVec<RPW>::type rx, ry;
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps)
-#pragma unroll
-        for (int x = 0; x < 8; ++x)
-            acc[ps][x] = 0.0f;
+    for (int s = 0; s < RPW; ++s) {
+        rx[s] = 0.0f;
+        ry[s] = 0.0f;
+    }
 
     const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
+    // argmax entries 64 apart in a document's column: dq64 queries and di64 tokens (one more query if the token wraps)
+    const int dq64 = 64 / p.l_q, di64 = 64 % p.l_q;
+    const int64_t inc_plain = (int64_t)dq64 * p.b * p.l_q + di64;
+    const int64_t inc_wrap = inc_plain + (int64_t)p.b * p.l_q - p.l_q;
     for (int64_t j = j_first; j <= j_last; ++j) {
         int64_t first;
         int len;
         if (p.offsets) {
-            first = p.offsets[j];
-            len = p.offsets[j + 1] - (int)first;
+            first = off[j];
+            len = off[j + 1] - (int)first;
         } else {
             first = j * p.l_d;
             len = p.l_d;
@@ -460,65 +536,93 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
         if (len <= 0)
             continue;
         const int t_base = (int)(row0 - first); // document-local index of the block's first row (may be negative)
+        // rows of the block that belong to document j: [lo_rel, hi_rel)
+        const int lo_rel = (int)max((int64_t)0, first - row0);
+        const int hi_rel = (int)min(row_end - row0, first + len - row0);
+        if (hi_rel <= lo_rel)
+            continue; // only offsets that break their contract get here
 
-        for (int64_t c64 = 0; c64 < n_entries; c64 += DS_COL) { // 64-bit: n_entries may be within DS_COL of 2^31
+        for (int64_t c64 = 0; c64 < n_entries; c64 += DW_COL) { // 64-bit: n_entries may be within DW_COL of 2^31
             const int c0 = (int)c64;
-            const int cn = min(DS_COL, n_entries - c0);
+            const int cn = min(DW_COL, n_entries - c0);
             __syncthreads(); // the previous round's lists have been walked
-            for (int x = tid; x < DD_WAVES * R; x += DD_WAVES * 64)
+            for (int x = tid; x < W * R; x += W * 64)
                 (&hist[0][0])[x] = 0;
             __syncthreads();
+            int kept = 0;
             {
-                // (A) entry n = c0 + x -> (q, i); all loads are issued before the first result is used
-                constexpr int PER = DS_SEG / 64;
-                int x = w * DS_SEG + lane;
-                int n = (int)((unsigned)c0 + (unsigned)x); // entries past the end of the column are masked below
-                int q = n / p.l_q, i = n - q * p.l_q;
-                const int dq = 64 / p.l_q, di = 64 % p.l_q;
+                // (1) entry n = c0 + x -> (q, i); all loads are issued before the first result is used.  The entry 64
+                // further on is dq queries and di tokens ahead: its address is one of two increments away.
+                constexpr int PER = SEG / 64;
+                const int x = w * SEG + lane;
+                const uint32_t n = (uint32_t)c0 + (uint32_t)x; // entries past the end of the column are masked below
+                const uint32_t q0 = magic_div(n < (uint32_t)n_entries ? n : 0u, lq_magic);
+                int i = (int)((n < (uint32_t)n_entries ? n : 0u) - q0 * (uint32_t)p.l_q);
+                const int32_t *ptr = p.A + ((int64_t)q0 * p.b + j) * p.l_q + i;
                 int t[PER];
+                if (cn == DW_COL) {
 #pragma unroll
-                for (int k = 0; k < PER; ++k) {
-                    t[k] = (x + k * 64) < cn ? p.A[((int64_t)q * p.b + j) * p.l_q + i] : -1;
-                    q += dq;
-                    i += di;
-                    if (i >= p.l_q) {
-                        i -= p.l_q;
-                        q += 1;
+                    for (int k = 0; k < PER; ++k) {
+                        t[k] = *ptr;
+                        i += di64;
+                        const bool wrap = i >= p.l_q;
+                        i -= wrap ? p.l_q : 0;
+                        ptr += wrap ? inc_wrap : inc_plain;
+                    }
+                } else {
+                    const int32_t *const ptr0 = ptr;
+#pragma unroll
+                    for (int k = 0; k < PER; ++k) {
+                        const bool live = (x + k * 64) < cn;
+                        const int v = *(live ? ptr : ptr0); // past the end of the column: a harmless re-read
+                        t[k] = live ? v : -1;
+                        i += di64;
+                        const bool wrap = i >= p.l_q;
+                        i -= wrap ? p.l_q : 0;
+                        ptr += wrap ? inc_wrap : inc_plain;
                     }
                 }
 #pragma unroll
                 for (int k = 0; k < PER; ++k) {
-                    int rel = t[k] - t_base;
-                    bool in = t[k] >= 0 && t[k] < len && rel >= 0 && rel < R;
-                    ent[x + k * 64] = (uint16_t)(in ? rel : DS_NONE);
-                    if (in)
-                        atomicAdd(&hist[w][rel], 1);
+                    const int rel = t[k] - t_base;
+                    const bool in = t[k] >= 0 && t[k] < len && rel >= lo_rel && rel < hi_rel;
+                    const unsigned long long mask = __ballot(in);
+                    const int before =
+                        __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+                    if (in) {
+                        const int key = (rel & (W - 1)) * RPW + (rel >> WBITS); // the owner's rows are consecutive keys
+                        seg[w][kept + before] = (uint32_t)(x + k * 64) | ((uint32_t)key << 16);
+                        atomicAdd(&hist[w][key], 1);
+                    }
+                    kept += __builtin_popcountll(mask);
                 }
             }
             __syncthreads();
             if (w == 0) {
-                // (B) rows lane and lane + 64: list starts, then each wavefront's cursor within the list
-                int tot[2], cur[2];
+                // (2) keys lane, lane + 64, ...: list starts, then each filtering wavefront's cursor within the list
+                int tot[KPL], cur[KPL];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < KPL; ++u) {
                     const int r = lane + 64 * u;
                     tot[u] = 0;
                     if (r < R)
-                        for (int sw = 0; sw < DD_WAVES; ++sw)
+                        for (int sw = 0; sw < W; ++sw)
                             tot[u] += hist[sw][r];
                 }
-                const int inc0 = wave_scan_incl(tot[0], lane);
-                const int all0 = __builtin_amdgcn_readlane(inc0, 63);
-                const int inc1 = wave_scan_incl(tot[1], lane);
-                cur[0] = inc0 - tot[0];
-                cur[1] = all0 + inc1 - tot[1];
+                int before = 0;
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < KPL; ++u) {
+                    const int inc = wave_scan_incl(tot[u], lane);
+                    cur[u] = before + inc - tot[u];
+                    before += __builtin_amdgcn_readlane(inc, 63);
+                }
+#pragma unroll
+                for (int u = 0; u < KPL; ++u) {
                     const int r = lane + 64 * u;
                     if (r < R) {
                         start[r] = cur[u];
                         int run = cur[u];
-                        for (int sw = 0; sw < DD_WAVES; ++sw) {
+                        for (int sw = 0; sw < W; ++sw) {
                             int cnt = hist[sw][r];
                             hist[sw][r] = run;
                             run += cnt;
@@ -530,195 +634,124 @@ __global__ void __launch_bounds__(DD_WAVES * 64) bwd_dd_sort_kernel(BwdParams p,
             }
             __syncthreads();
             {
-                // (C) stable placement: entries in order, equal rows ranked by lane
-                volatile int *cursor = &hist[w][0];
-                for (int k = 0; k < DS_SEG / 64; ++k) {
-                    const int x = w * DS_SEG + k * 64 + lane;
-                    const int rel = ent[x];
-                    const bool valid = rel != DS_NONE;
+                // (3) stable placement: kept entries in order, equal keys ranked by lane
+                typedef volatile __attribute__((address_space(3))) int *lds_int; // LDS, not a generic pointer
+                lds_int cursor = (lds_int)&hist[w][0];
+                for (int e0 = 0; e0 < kept; e0 += 64) {
+                    const bool valid = e0 + lane < kept;
+                    const uint32_t ent = valid ? seg[w][e0 + lane] : 0u;
+                    const int key = (int)(ent >> 16);
                     uint64_t same = __ballot(valid);
-                    if (same == 0)
-                        continue;
 #pragma unroll
                     for (int bit = 0; bit < RBITS; ++bit) {
-                        const bool one = (rel >> bit) & 1;
+                        const bool one = (key >> bit) & 1;
                         const uint64_t bm = __ballot(one);
                         same &= one ? bm : ~bm;
                     }
                     if (valid) {
                         const int rank = __popcll(same & ((uint64_t(1) << lane) - 1));
-                        const int pos = cursor[rel] + rank;
-                        list[pos] = (uint16_t)x;
+                        const int pos = cursor[key] + rank;
+                        list[pos] = (uint16_t)(ent & 0xffffu);
                         if (rank == 0)
-                            cursor[rel] = pos + __popcll(same);
+                            cursor[key] = pos + __popcll(same);
                     }
                     __builtin_amdgcn_wave_barrier();
                 }
             }
             __syncthreads();
-            // (D) walk the lists
-#pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                const int r = ps * 32 + grp * DD_WAVES + w; // neighbouring rows (hot tokens often are) go to different wavefronts
-                int beg = start[r], end = start[r + 1];
-                // A list much longer than the others of the wavefront (a hot token) would leave 48 lanes idle for
-                // most of its length: the whole wavefront walks such lists instead, one after the other, one Q row per
-                // load instruction and 16 in flight, in the same order and with the same arithmetic.  The row's gradient moves between the two
-                // register layouts (8 columns per lane of its group <-> 2 columns per lane of the wavefront) through LDS.
-                {
-                    int len_g[4], order[4];
-#pragma unroll
-                    for (int gi = 0; gi < 4; ++gi)
-                        len_g[gi] = __builtin_amdgcn_readlane(end - beg, 16 * gi);
-                    const int n_long = pick_long_lists(len_g, order);
-                    for (int t = 0; t < n_long; ++t) {
-                        const int who = t == 0 ? order[0] : t == 1 ? order[1] : t == 2 ? order[2] : order[3];
-                        const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
-                        const int le = __builtin_amdgcn_readlane(end, 16 * who);
-                        float *xf = &xfer[w][0];
-                        if (grp == who) {
-#pragma unroll
-                            for (int x = 0; x < 8; ++x)
-                                xf[c * 8 + x] = acc[ps][x];
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        float ax = xf[2 * lane], ay = xf[2 * lane + 1];
-                        for (int k = lb; k < le; k += DD_BATCH) {
-                            // lanes 0 .. 15 look up one edge each
-                            const int kk = k + (lane & (DD_BATCH - 1));
-                            const uint32_t n = (uint32_t)c0 + (kk < le ? (uint32_t)list[kk] : 0u);
-                            const uint32_t q = (uint32_t)(((uint64_t)n * lq_magic) >> lq_shift);
-                            const bool ok = kk < le && q < (uint32_t)p.n_q;
-                            const float gv = ok ? p.g[(int64_t)q * p.b + j] : 0.0f;
-                            const int64_t roff = (int64_t)(ok ? n : 0u) * ROWB;
-                            const int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
-                            const int okv = ok ? 1 : 0;
-                            float x0[DD_BATCH], x1[DD_BATCH];
-#pragma unroll
-                            for (int u = 0; u < DD_BATCH; ++u) {
-                                const int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, u) << 32) |
-                                                    (uint32_t)__builtin_amdgcn_readlane(rlo, u);
-                                load_pair<DT>(p.Q + off, lane, x0[u], x1[u]);
-                            }
-#pragma unroll
-                            for (int u = 0; u < DD_BATCH; ++u) {
-                                if (__builtin_amdgcn_readlane(okv, u)) {
-                                    const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), u));
-                                    ax = fmaf(gg, x0[u], ax);
-                                    ay = fmaf(gg, x1[u], ay);
-                                }
-                            }
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        xf[2 * lane] = ax;
-                        xf[2 * lane + 1] = ay;
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        if (grp == who) {
-#pragma unroll
-                            for (int x = 0; x < 8; ++x)
-                                acc[ps][x] = xf[c * 8 + x];
-                            end = beg; // done
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // xfer is written again by the next list
-                        __builtin_amdgcn_wave_barrier();
-                    }
-                }
-                constexpr int UNROLL = 4;
-                for (int k = beg; k < end; k += UNROLL) {
-                    int64_t qrow[UNROLL];
-                    float gg[UNROLL];
-                    bool on[UNROLL];
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) {
-                        on[u] = k + u < end;
-                        const uint32_t n = (uint32_t)c0 + (on[u] ? (uint32_t)list[k + u] : 0u); // = q * l_q + i: the Q row
-                        const uint32_t q = (uint32_t)(((uint64_t)n * lq_magic) >> lq_shift);
-                        on[u] = on[u] && q < (uint32_t)p.n_q;
-                        qrow[u] = on[u] ? (int64_t)n : 0;
-                        gg[u] = on[u] ? p.g[(int64_t)q * p.b + j] : 0.0f;
-                    }
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) {
-                        float v[8];
-                        load8<DT>(p.Q + qrow[u] * ROWB + c * 8 * EB, v);
-#pragma unroll
-                        for (int x = 0; x < 8; ++x)
-                            acc[ps][x] = on[u] ? fmaf(gg[u], v[x], acc[ps][x]) : acc[ps][x];
-                    }
-                }
+            {
+                // (4) walk this wavefront's keys w * RPW .. w * RPW + RPW - 1
+                const int startv = start[w * RPW + (lane < RPW ? lane : RPW)];
+                const int k_lo = __builtin_amdgcn_readlane(startv, 0);
+                const int k_hi = __builtin_amdgcn_readlane(startv, RPW);
+                auto lookup = [&](int kk, bool valid, uint32_t &n, float &gv) {
+                    n = (uint32_t)c0 + (valid ? (uint32_t)list[kk] : 0u); // = q * l_q + i: the Q row
+                    const uint32_t q = magic_div(n, lq_magic);
+                    gv = valid ? p.g[(int64_t)q * p.b + j] : 0.0f;
+                };
+                walk_rows<DT, RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, startv, lookup, rx, ry);
             }
         }
     }
-
+    if (col_ok) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) {
-        const int64_t row = row0 + ps * 32 + grp * DD_WAVES + w;
-        if (row < row_end) {
-            float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
-            dst[0] = make_float4(acc[ps][0], acc[ps][1], acc[ps][2], acc[ps][3]);
-            dst[1] = make_float4(acc[ps][4], acc[ps][5], acc[ps][6], acc[ps][7]);
+        for (int s = 0; s < RPW; ++s) {
+            const int64_t row = row0 + W * s + w;
+            if (row < row_end)
+                *reinterpret_cast<float2 *>(p.dD + row * p.d + col) = make_float2(rx[s], ry[s]);
         }
     }
+}
+
+// The partial sums of dQ live in the dD buffer until the dD kernel overwrites it (dD is an output that the call
+// fully overwrites, and its n_part * n_q * l_q rows of d floats are free until then), so the library needs no
+// scratch memory.  n_part = the largest power of two <= 8 that fits there and leaves every partition a document.
+static int dq_partitions(const BwdParams &p)
+{
+    int n_part = 8;
+    const int64_t nql = (int64_t)p.n_q * p.l_q;
+    while (n_part > 1 && ((int64_t)n_part * nql > p.total_tokens || n_part > p.b))
+        n_part >>= 1;
+    return n_part;
+}
+
+template <int DT> static hipError_t launch_dq(const BwdParams &p, hipStream_t stream)
+{
+    const int64_t nql = (int64_t)p.n_q * p.l_q;
+    const int n_part = dq_partitions(p);
+    const int64_t dpp = (p.b + n_part - 1) / n_part;
+    const unsigned slabs = (unsigned)((p.d + SLAB - 1) / SLAB);
+    float *out = n_part > 1 ? p.dD : p.dQ;
+    // four query tokens per group of sixteen lanes once that still gives every SIMD a wavefront or two
+    if (nql * n_part >= 16384 && p.l_q % 4 == 0 && (reinterpret_cast<uintptr_t>(p.A) & 15) == 0) {
+        const int64_t groups = (nql + 63) / 64; // workgroups of four wavefronts x four groups x four query tokens
+        if (groups * n_part >= (int64_t(1) << 31))
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((bwd_dq_kernel<DT, 4>), dim3((unsigned)(groups * n_part), slabs), dim3(256), 0, stream, p, out, n_part, dpp);
+    } else {
+        const int64_t groups = (nql + 15) / 16;
+        hipLaunchKernelGGL((bwd_dq_kernel<DT, 1>), dim3((unsigned)(groups * n_part), slabs), dim3(256), 0, stream, p, out, n_part, dpp);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_part == 1)
+        return e;
+    const int64_t n4 = nql * p.d / 4;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 65536)
+        blocks = 65536;
+    hipLaunchKernelGGL(bwd_dq_combine_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       reinterpret_cast<const float4 *>(p.dD), reinterpret_cast<float4 *>(p.dQ), n4, n_part);
+    return hipGetLastError();
 }
 
 template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, hipStream_t stream)
 {
-    int64_t waves = (int64_t)p.n_q * p.l_q;
-    int grid_q = (int)((waves + 3) / 4);
-    hipLaunchKernelGGL((bwd_dq_kernel<DT>), dim3(grid_q), dim3(256), 0, stream, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_dq<DT>(p, stream);
     if (e != hipSuccess)
         return e;
     // blocks of 128 rows unless that leaves the chip short of workgroups (about 4 per CU wanted)
     const int64_t want = (int64_t)num_cu * 4;
-    // Many edges per dD row (short documents, many queries) or a corpus of fewer than 128 rows per wanted workgroup:
-    // the kernel that sorts inside the workgroup; few edges per row on a large corpus: the kernel whose wavefronts
-    // filter the lists.  Same bits either way.  Measured (L_q = 32, fp16, whole backward, sort / filter):
-    // 512 x 128 tokens 0.40 / 0.90 ms, 256 x 300 0.17 / 0.27, 256 x 64 0.13 / 0.19, 192 x 256 0.10 / 0.12,
-    // 128 x 512 0.072 / 0.097, 256 x 512 0.157 / 0.166, 128 x 300 0.082 / 0.080, 64 x 180 0.050 / 0.044,
-    // 512 x 1024 0.74 / 0.66, 256 x 1024 0.206 / 0.188.  With a quarter or more of a document's edges on a few hot
-    // tokens the sorting kernel is ahead everywhere except 256 x 1024 (0.30 / 0.28 ms).
-    const int64_t avg_len = p.total_tokens / p.b > 0 ? p.total_tokens / p.b : 1;
-    const int64_t edges = (int64_t)p.n_q * p.l_q; // per document
-    if (edges >= (int64_t)DD_SORT_MIN_EDGES * avg_len || (edges >= 8 * avg_len && p.total_tokens / 128 < want)) {
-        // q = n / l_q for n < 2^31 as (n * magic) >> shift
-        int lg = 0;
-        while ((1 << lg) < p.l_q)
-            ++lg;
-        const int shift = 31 + lg;
-        const uint32_t magic = (uint32_t)((((uint64_t)1 << shift) + (uint64_t)p.l_q - 1) / (uint64_t)p.l_q);
-        if (p.total_tokens / 128 >= want) {
-            int64_t grid_d = (p.total_tokens + 127) / 128;
-            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 4>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
-        } else if (p.total_tokens / 64 >= want) {
-            int64_t grid_d = (p.total_tokens + 63) / 64;
-            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 2>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
-        } else {
-            int64_t grid_d = (p.total_tokens + 31) / 32;
-            hipLaunchKernelGGL((bwd_dd_sort_kernel<DT, 1>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p, magic, shift);
-        }
-        return hipGetLastError();
-    }
-    if (p.total_tokens / (DD_WAVES * 16) >= want) {
-        int64_t grid_d = (p.total_tokens + DD_WAVES * 16 - 1) / (DD_WAVES * 16);
-        hipLaunchKernelGGL((bwd_dd_kernel<DT, 16>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
-    } else if (p.total_tokens / (DD_WAVES * 8) >= want) {
-        int64_t grid_d = (p.total_tokens + DD_WAVES * 8 - 1) / (DD_WAVES * 8);
-        hipLaunchKernelGGL((bwd_dd_kernel<DT, 8>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
-    } else {
-        int64_t grid_d = (p.total_tokens + DD_WAVES * 4 - 1) / (DD_WAVES * 4);
-        hipLaunchKernelGGL((bwd_dd_kernel<DT, 4>), dim3((unsigned)grid_d), dim3(DD_WAVES * 64), 0, stream, p);
-    }
+    const Magic lq_magic = magic_u31((uint32_t)p.l_q);
+    const unsigned slabs = (unsigned)((p.d + SLAB - 1) / SLAB);
+    auto go = [&](auto rpw_tag, auto w_tag) {
+        constexpr int RPW = decltype(rpw_tag)::value;
+        constexpr int W = decltype(w_tag)::value;
+        const int64_t n_blocks = (p.total_tokens + W * RPW - 1) / (W * RPW);
+        const int64_t grid = (n_blocks + 7) / 8 * 8;
+        hipLaunchKernelGGL((bwd_dd_kernel<DT, RPW, W>), dim3((unsigned)grid, slabs), dim3(W * 64), 0, stream, p, p.offsets,
+                           lq_magic, (int)n_blocks);
+    };
+    if (p.total_tokens / (DD_WAVES * 16) >= want)
+        go(std::integral_constant<int, 16>(), std::integral_constant<int, 8>());
+    else if (p.total_tokens / (DD_WAVES * 8) >= want)
+        go(std::integral_constant<int, 8>(), std::integral_constant<int, 8>());
+    else
+        go(std::integral_constant<int, 4>(), std::integral_constant<int, 8>());
     return hipGetLastError();
 }
 
 hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const int32_t *offsets, int64_t b, int l_d,
-                           int64_t total_tokens, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
+                           int64_t total_tokens, int d, int dtype, const int32_t *argmax, const float *dscore, float *dQ,
                            float *dD, int num_cu, hipStream_t stream)
 {
     BwdParams p;
@@ -734,6 +767,7 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
     p.n_q = n_q;
     p.l_q = l_q;
     p.l_d = l_d;
+    p.d = d;
     switch (dtype) {
     case MAXSIM_F32: return launch_bwd<MAXSIM_F32>(p, num_cu, stream);
     case MAXSIM_F16: return launch_bwd<MAXSIM_F16>(p, num_cu, stream);
@@ -758,14 +792,11 @@ hipError_t backward_launch(const void *Q, int n_q, int l_q, const void *D, const
 //                      again, 64 at a time, ranks equal t within the 64 by ballots and writes
 //                      the edge ids.  No atomics decide an order, so the CSR is the same on
 //                      every run.
-//   csr_apply_kernel   sixteen lanes per dD row walk the row's list in order (Eq. 3).
+//   csr_apply_kernel   a wavefront per 8 consecutive dD rows walks their lists in order (Eq. 3).
 // ---------------------------------------------------------------------------------------
 constexpr int CSR_WAVES = 8;
 constexpr int CSR_MAX_LD = 4096;
 constexpr int CSR_LOADS = 8;      // argmax entries a lane fetches before it uses the first
-#ifndef CSR_APPLY_WAVES
-#define CSR_APPLY_WAVES 8 // wavefronts per workgroup of csr_apply_kernel (4 rows each)
-#endif
 constexpr int CSR_LDS_EXTRA = 16; // ints after the histograms: one sum per wavefront for the block scan
 
 struct CsrParams {
@@ -939,119 +970,61 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
     }
 }
 
-// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :].  Sixteen lanes per row; lists
-// much longer than the others of their wavefront are walked by the whole wavefront (as in bwd_dd_sort_kernel:
-// same order, same arithmetic).
+// dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :]: the walk of bwd_dd_kernel over the
+// CSR in global memory.  A wavefront owns CSR_RPW consecutive rows, whose lists are one contiguous range of
+// col_idx; per 64 edges one vector step decodes the edge ids (e = (i * b + j) * l_q + s) into Q row and weight,
+// then all 64 lanes (two columns each) apply the edges in order.  Same order and arithmetic as bwd_dd_kernel:
+// same bits.
+constexpr int CSR_RPW = 8;
+constexpr int CSR_APPLY_WAVES = 4;
+
 template <int DT>
 __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
-                                                        const int32_t *__restrict__ col_idx)
+                                                        const int32_t *__restrict__ col_idx, Magic bl_magic, Magic lq_magic)
 {
-    constexpr int ROWB = D_MODEL * Elem<DT>::BYTES;
-    __shared__ float xfer[CSR_APPLY_WAVES][D_MODEL];
+    constexpr int EB = Elem<DT>::BYTES;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
-    const int grp = lane >> 4;
-    const int c = lane & 15;
-    const int64_t row = (int64_t)blockIdx.x * (4 * CSR_APPLY_WAVES) + grp * CSR_APPLY_WAVES + w; // neighbouring rows go to different wavefronts
-    const bool live = row < p.total_tokens;
-    const int64_t rr = live ? row : p.total_tokens - 1;
-    const int64_t j = rr / p.l_d;
-    const int64_t n_edges = (int64_t)p.n_q * p.l_q * p.b;
-    int beg = row_ptr[rr] > 0 ? row_ptr[rr] : 0;
-    int end = row_ptr[rr + 1] < n_edges ? row_ptr[rr + 1] : (int)n_edges;
-    if (!live || end < beg)
-        end = beg;
+    const int64_t r0 = ((int64_t)blockIdx.x * CSR_APPLY_WAVES + w) * CSR_RPW;
+    if (r0 >= p.total_tokens)
+        return;
+    const int n_rows = (int)(p.total_tokens - r0 < CSR_RPW ? p.total_tokens - r0 : CSR_RPW);
+    const int col = (int)blockIdx.y * SLAB + 2 * lane;
+    const bool col_ok = col < p.d;
+    const uint32_t lane_off = (uint32_t)((col_ok ? 2 * lane : 0) + (int)blockIdx.y * SLAB) * EB;
+    const uint32_t row_bytes = (uint32_t)p.d * EB;
+    const __amdgpu_buffer_rsrc_t rsrc = q_resource(p.Q, (uint32_t)p.n_q * (uint32_t)p.l_q * row_bytes); // < 2^32 (checked by the caller)
+    const int64_t n_edges = (int64_t)p.n_q * p.l_q * p.b; // < 2^31 (checked by the caller)
+    int rp = row_ptr[r0 + (lane < n_rows ? lane : n_rows)];
+    rp = rp < 0 ? 0 : (rp > n_edges ? (int)n_edges : rp); // device data the host cannot check
+    const int k_lo = __builtin_amdgcn_readlane(rp, 0);
+    int k_hi = __builtin_amdgcn_readlane(rp, n_rows);
+    k_hi = k_hi < k_lo ? k_lo : k_hi;
+    rp = lane >= n_rows ? k_hi : rp;
     const uint32_t bl = (uint32_t)(p.b * p.l_q); // edge ids of one query
-    const int64_t jl = j * p.l_q;
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-
-    // edge id -> (usable, Q row, weight) for a row of document jd
-    auto decode = [&](bool want, int e, int64_t jd, int64_t jld, bool &ok, int64_t &qrow, float &gv) {
-        int64_t rem = (want ? (int64_t)e : jld) - jld; // i * (b * l_q) + s
-        uint32_t i = (uint32_t)rem / bl;
-        uint32_t s_ = (uint32_t)rem - i * bl;
-        ok = want && rem >= 0 && rem < (int64_t(1) << 31) && i < (uint32_t)p.n_q && s_ < (uint32_t)p.l_q;
-        qrow = ok ? (int64_t)i * p.l_q + s_ : 0;
-        gv = ok ? p.g[(int64_t)i * p.b + jd] : 0.0f;
+    typename RowVec<CSR_RPW>::type rx, ry;
+#pragma unroll
+    for (int s = 0; s < CSR_RPW; ++s) {
+        rx[s] = 0.0f;
+        ry[s] = 0.0f;
+    }
+    auto lookup = [&](int kk, bool valid, uint32_t &n, float &gv) {
+        const int e = valid ? col_idx[kk] : 0;
+        const uint32_t ue = e < 0 ? 0u : (uint32_t)e;
+        const uint32_t i = magic_div(ue, bl_magic);
+        const uint32_t rem = ue - i * bl; // j * l_q + s
+        const uint32_t jj = magic_div(rem, lq_magic);
+        const uint32_t s_ = rem - jj * (uint32_t)p.l_q;
+        const bool ok = valid && e >= 0 && i < (uint32_t)p.n_q;
+        n = ok ? i * (uint32_t)p.l_q + s_ : 0u;
+        gv = ok ? p.g[(int64_t)i * p.b + jj] : 0.0f;
     };
-
-    {
-        int len_g[4], order[4];
+    walk_rows<DT, CSR_RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, rp, lookup, rx, ry);
+    if (col_ok) {
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi)
-            len_g[gi] = __builtin_amdgcn_readlane(end - beg, 16 * gi);
-        const int n_long = pick_long_lists(len_g, order);
-        for (int t = 0; t < n_long; ++t) {
-            const int who = t == 0 ? order[0] : t == 1 ? order[1] : t == 2 ? order[2] : order[3];
-            const int lb = __builtin_amdgcn_readlane(beg, 16 * who);
-            const int le = __builtin_amdgcn_readlane(end, 16 * who);
-            const int64_t row_w = (int64_t)blockIdx.x * (4 * CSR_APPLY_WAVES) + who * CSR_APPLY_WAVES + w; // a live row
-            const int64_t jw = row_w / p.l_d;
-            const int64_t jlw = jw * p.l_q;
-            float ax = 0.0f, ay = 0.0f;
-            for (int k = lb; k < le; k += DD_BATCH) {
-                const int kk = k + (lane & (DD_BATCH - 1));
-                bool ok;
-                int64_t qrow;
-                float gv;
-                decode(kk < le, kk < le ? col_idx[kk] : 0, jw, jlw, ok, qrow, gv);
-                const int64_t roff = qrow * ROWB;
-                const int rlo = (int)(roff & 0xffffffff), rhi = (int)(roff >> 32);
-                const int okv = ok ? 1 : 0;
-                float x0[DD_BATCH], x1[DD_BATCH];
-#pragma unroll
-                for (int u = 0; u < DD_BATCH; ++u) {
-                    const int64_t off = ((int64_t)__builtin_amdgcn_readlane(rhi, u) << 32) |
-                                        (uint32_t)__builtin_amdgcn_readlane(rlo, u);
-                    load_pair<DT>(p.Q + off, lane, x0[u], x1[u]);
-                }
-#pragma unroll
-                for (int u = 0; u < DD_BATCH; ++u) {
-                    if (__builtin_amdgcn_readlane(okv, u)) {
-                        const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gv), u));
-                        ax = fmaf(gg, x0[u], ax);
-                        ay = fmaf(gg, x1[u], ay);
-                    }
-                }
-            }
-            float *xf = &xfer[w][0];
-            xf[2 * lane] = ax;
-            xf[2 * lane + 1] = ay;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (grp == who) {
-#pragma unroll
-                for (int x = 0; x < 8; ++x)
-                    acc[x] = xf[c * 8 + x];
-                end = beg; // done
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // xfer is written again by the next list
-            __builtin_amdgcn_wave_barrier();
-        }
-    }
-
-    constexpr int UNROLL = 4;
-    for (int k = beg; k < end; k += UNROLL) {
-        int64_t qrow[UNROLL];
-        float gg[UNROLL];
-        bool on[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
-            decode(k + u < end, k + u < end ? col_idx[k + u] : 0, j, jl, on[u], qrow[u], gg[u]);
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            float v[8];
-            load8<DT>(p.Q + qrow[u] * ROWB + c * 8 * Elem<DT>::BYTES, v);
-#pragma unroll
-            for (int x = 0; x < 8; ++x)
-                acc[x] = on[u] ? fmaf(gg[u], v[x], acc[x]) : acc[x];
-        }
-    }
-    if (live) {
-        float4 *dst = reinterpret_cast<float4 *>(p.dD + row * D_MODEL + c * 8);
-        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        for (int s = 0; s < CSR_RPW; ++s)
+            if (s < n_rows)
+                *reinterpret_cast<float2 *>(p.dD + (r0 + s) * p.d + col) = make_float2(rx[s], ry[s]);
     }
 }
 
@@ -1097,21 +1070,22 @@ hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, 
     return hipGetLastError();
 }
 
+
 template <int DT> static hipError_t launch_bwd_csr(const BwdParams &p, const int32_t *row_ptr, const int32_t *col_idx,
                                                    hipStream_t stream)
 {
-    int64_t waves = (int64_t)p.n_q * p.l_q;
-    hipLaunchKernelGGL((bwd_dq_kernel<DT>), dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, stream, p);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_dq<DT>(p, stream);
     if (e != hipSuccess)
         return e;
-    constexpr int ROWS = 4 * CSR_APPLY_WAVES; // rows per workgroup
-    int64_t groups = (p.total_tokens + ROWS - 1) / ROWS;
-    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups), dim3(CSR_APPLY_WAVES * 64), 0, stream, p, row_ptr, col_idx);
+    constexpr int ROWS = CSR_RPW * CSR_APPLY_WAVES; // rows per workgroup
+    const int64_t groups = (p.total_tokens + ROWS - 1) / ROWS;
+    const unsigned slabs = (unsigned)((p.d + SLAB - 1) / SLAB);
+    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups, slabs), dim3(CSR_APPLY_WAVES * 64), 0, stream, p, row_ptr,
+                       col_idx, magic_u31((uint32_t)(p.b * p.l_q)), magic_u31((uint32_t)p.l_q));
     return hipGetLastError();
 }
 
-hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, int dtype,
                                const int32_t *argmax, const float *dscore, int32_t *row_ptr, int32_t *col_idx, float *dQ,
                                float *dD, int num_cu, hipStream_t stream)
 {
@@ -1131,6 +1105,7 @@ hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, i
     p.n_q = n_q;
     p.l_q = l_q;
     p.l_d = l_d;
+    p.d = d;
     switch (dtype) {
     case MAXSIM_F32: return launch_bwd_csr<MAXSIM_F32>(p, row_ptr, col_idx, stream);
     case MAXSIM_F16: return launch_bwd_csr<MAXSIM_F16>(p, row_ptr, col_idx, stream);
@@ -1182,7 +1157,7 @@ bool csr_static_fits(int n_q, int64_t b, int l_q, int l_d)
     return b * (int64_t)l_d <= CSR_STATIC_MAX_ROWS && (int64_t)n_q * l_q * b <= CSR_STATIC_MAX_EDGES;
 }
 
-hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int dtype,
+hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d, int dtype,
                                       const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
                                       hipStream_t stream)
 {
@@ -1192,7 +1167,7 @@ hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const voi
     hipError_t e = csr_static_buffer(&buf);
     if (e != hipSuccess)
         return e;
-    return backward_csr_launch(Q, n_q, l_q, D, b, l_d, dtype, argmax, dscore, buf, buf + CSR_STATIC_COL_AT, dQ, dD, num_cu,
+    return backward_csr_launch(Q, n_q, l_q, D, b, l_d, d, dtype, argmax, dscore, buf, buf + CSR_STATIC_COL_AT, dQ, dD, num_cu,
                                stream);
 }
 

@@ -45,7 +45,8 @@ def test_error_codes_without_touching_a_gpu():
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 100, 1, p, None, None) == -2      # rows must be a multiple of 64 bytes
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 16, 1, p, None, None) == -2       # d < 32
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 16384, 1, p, None, None) == -2    # rows above 16 KB
-    assert L.maxsim_backward(p, 1, 1, p, 1, 1, 64, 1, p, p, p, p, None) == -2      # backward is built for d = 128 only
+    assert L.maxsim_backward(p, 1, 1, p, 1, 1, 100, 1, p, p, p, p, None) == -2     # backward: d must be a multiple of 8
+    assert L.maxsim_backward(p, 1, 1, p, 1, 1, 16384, 1, p, p, p, p, None) == -2   # ... of at most 8192
     assert L.maxsim_forward_i8(p, p, 1, 2000, p, p, 1, 1, 128, p, None) == -2      # int8 queries above 1024 tokens
     assert L.maxsim_forward_streamed(p, 1, 32, p, 4, 40, 128, 1, 0, p, p, None) == -1  # block_docs < 1
     assert L.maxsim_forward_i8_ragged(p, p, 1, 32, p, p, None, 4, 100, 128, p, None) == -1  # no offsets
@@ -55,7 +56,7 @@ def test_error_codes_without_touching_a_gpu():
     assert L.maxsim_csr_build(p, 2, 3, 4, 4097, p, p, None) == -2                  # documents above 4096 tokens
     assert L.maxsim_csr_build(p, 70000, 40000, 32, 8, p, p, None) == -2            # more than 2^31 edges
     assert L.maxsim_backward_csr(p, 1, 1, p, 1, 1, 128, 1, p, p, None, p, p, p, None) == -1   # no row_ptr
-    assert L.maxsim_backward_csr(p, 1, 1, p, 1, 1, 64, 1, p, p, p, p, p, p, None) == -2      # d = 128 only
+    assert L.maxsim_backward_csr(p, 1, 1, p, 1, 1, 60, 1, p, p, p, p, p, p, None) == -2      # d must be a multiple of 8
     assert L.maxsim_forward(p, 0, 32, p, 4, 40, 128, 1, p, None, None) == -1      # n_q < 1
     assert L.maxsim_forward(p, 1, 32, p, 4, 40, 128, 7, p, None, None) == -1      # bad dtype
     assert L.maxsim_forward(ctypes.c_void_p(addr + 2), 1, 32, p, 4, 40, 128, 1, p, None, None) == -1  # misaligned

@@ -29,9 +29,9 @@ def close(gpu, ref, what):
     assert not g.reshape(-1, g.shape[-1])[untouched].any(), what
 
 
-def run_case(n_q, l_q, b, l_d, dtype, seed, holes=False):
-    Q = W.unit_rows((n_q, l_q, 128), dtype, seed, DEV)
-    D = W.unit_rows((b, l_d, 128), dtype, seed + 1, DEV)
+def run_case(n_q, l_q, b, l_d, dtype, seed, holes=False, d=128):
+    Q = W.unit_rows((n_q, l_q, d), dtype, seed, DEV)
+    D = W.unit_rows((b, l_d, d), dtype, seed + 1, DEV)
     _, A, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype)
     rng = np.random.default_rng(seed)
     g = rng.standard_normal((n_q, b)).astype(np.float32)
@@ -51,6 +51,32 @@ def run_case(n_q, l_q, b, l_d, dtype, seed, holes=False):
                                    (2, 100, 5, 64), (4, 64, 9, 128), (1, 130, 2, 31)])
 def test_backward_parity(shape, dtype):
     run_case(*shape, dtype, 7)
+
+
+# Embedding widths other than 128 (App. "Split-d Speedup": training verified at d = 512 .. 2048): every multiple of 8;
+# columns beyond 128 are further slabs of the same kernels.  The explicit CSR must give the same bits.
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("d", [8, 64, 200, 256, 768, 2048])
+def test_backward_other_widths(d, dtype):
+    dQ, dD = run_case(3, 33, 5, 70, dtype, 31, holes=True, d=d)
+    Q = W.unit_rows((3, 33, d), dtype, 31, DEV)
+    D = W.unit_rows((5, 70, d), dtype, 32, DEV)
+    _, A, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype)
+    rng = np.random.default_rng(31)
+    g = rng.standard_normal((3, 5)).astype(np.float32)
+    A = A.copy()
+    A[rng.random(A.shape) < 0.2] = -1
+    cQ, cD, _, _ = M.maxsim_backward_csr(Q, D, torch.from_numpy(A).to(DEV), torch.from_numpy(g).to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(cQ, dQ) and torch.equal(cD, dD)
+
+
+@pytest.mark.parametrize("d", [64, 512, 1024])
+def test_backward_other_widths_many_queries(d):
+    """Enough query tokens for the document-partitioned dQ (partial sums combined in partition order) and for
+    four query tokens per group of sixteen lanes."""
+    run_case(72, 32, 40, 80, "f16", 37, d=d)
+    run_case(130, 36, 9, 600, "bf16", 38, d=d)
 
 
 # Twenty or more edges per dD row on average (n_q * l_q >= 20 * l_d): the kernel that sorts the edges inside the

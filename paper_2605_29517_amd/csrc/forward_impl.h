@@ -331,6 +331,63 @@ __device__ __forceinline__ void fold_step(const f32x16 &acc, int u, float &m, in
     }
 }
 
+// The fold with argmax for 16-bit inputs (the running maximum is an fp32 sum of 128 products).  Compare-and-select
+// per cell is three VALU operations against half an operation for the plain maximum, which makes the argmax
+// variant VALU-bound.  Here every cell's low four mantissa bits are replaced by 15 - r (r = the accumulator
+// register, which grows with the row), one operation per cell, and the tile's maximum is again a v_max3 chain:
+// among cells that agree in the upper 28 bits the lowest row wins.  Once per tile and column block the tile's
+// maximum, with those four bits cleared, is compared (strictly: an earlier tile keeps a tie) with the running one
+// and the row is read back from the four bits.  Consequences: the maxima that enter the score are truncated by at
+// most 2^-19 relative (the score tolerance is 2e-3); cells closer than that to each other count as tied and the
+// earlier one wins (the argmax rule asks for the exact winner only where the margin exceeds 1e-3).  The ordering
+// of the patched values is right among non-negative cells only, which is all that matters once the running
+// maximum is non-negative (a negative cell cannot beat it); if any lane of the wavefront has a negative tile
+// maximum while its running maximum is still negative, that tile is folded again, exactly, with compare-and-select
+// (the first tiles of a document whose similarities with a query token are all negative).  The same exact fold
+// takes every tile in which a lane's maximum reaches 512 in magnitude: above that, 2^-19 relative would no longer be
+// inside the 1e-3 margin below which the argmax rule lets near-ties go either way.  The running winner is
+// kept as a key, the tile's first row (a multiple of 32) | the four bits, and turned into a row at the end of the
+// document.
+template <int NU>
+__device__ __forceinline__ void fold_step_packed(const f32x16 &acc, int u, float &tmax, float &m, int &key, int row_base)
+{
+    constexpr int LAG = NU >= 4 ? 2 : NU / 2;
+    if (u < LAG)
+        return;
+    const int lo = 2 * (8 * (u - LAG) / (NU - LAG)), hi = 2 * (8 * (u - LAG + 1) / (NU - LAG));
+    if (u == LAG)
+        tmax = neg_inf();
+#pragma unroll
+    for (int r = lo; r < hi; r += 2) {
+        const float p0 = __uint_as_float((__float_as_uint(acc[r]) & 0xfffffff0u) | (uint32_t)(15 - r));
+        const float p1 = __uint_as_float((__float_as_uint(acc[r + 1]) & 0xfffffff0u) | (uint32_t)(14 - r));
+        tmax = fmaxf(fmaxf(tmax, p0), p1); // one v_max3_f32
+    }
+    if (u == NU - 1) {
+        const uint32_t tb = __float_as_uint(tmax);
+        if (__builtin_expect(__ballot(((int)tb < 0 && m < 0.0f) || fabsf(tmax) >= 512.0f) != 0, 0)) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const bool up = acc[r] > m; // strict: the first occurrence keeps a tie
+                m = up ? acc[r] : m;
+                key = up ? (row_base | (15 - r)) : key;
+            }
+        } else {
+            const float ts = __uint_as_float(tb & 0xfffffff0u);
+            const bool up = ts > m;
+            m = up ? ts : m;
+            key = up ? (int)((tb & 15u) | (uint32_t)row_base) : key;
+        }
+    }
+}
+
+// The document-local row behind a key of fold_step_packed in lane half h
+__device__ __forceinline__ int packed_key_row(int key, int h)
+{
+    const int r = 15 - (key & 15);
+    return (key & ~31) + h * 4 + (((r & 12) << 1) | (r & 3));
+}
+
 // The main loop is software-pipelined by hand and pinned with scheduling barriers, one MFMA
 // (16-bit inputs) per step:
 //   * the MFMA chain of column block cb runs while the previous block's result tile is folded
@@ -522,6 +579,13 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
             }
             __builtin_amdgcn_sched_barrier(0);
             f32x16 acc[NCB];
+            float tmax[NCB]; // the tile's maximum per column block (argmax with 16-bit inputs only)
+            auto fold = [&](int cbx, int u) {
+                if constexpr (ARGMAX && TR::DT != MAXSIM_F32)
+                    fold_step_packed<NU>(acc[cbx], u, tmax[cbx], m[cbx], idx[cbx], ci.t0);
+                else
+                    fold_step<ARGMAX, NU>(acc[cbx], u, m[cbx], idx[cbx], ci.t0, h);
+            };
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
@@ -547,20 +611,23 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                             gload();
                         }
                     } else {
-                        fold_step<ARGMAX, NU>(acc[cb - 1], u, m[cb - 1], idx[cb - 1], ci.t0, h);
+                        fold(cb - 1, u);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
             for (int u = 0; u < NU; ++u)
-                fold_step<ARGMAX, NU>(acc[NCB - 1], u, m[NCB - 1], idx[NCB - 1], ci.t0, h);
+                fold(NCB - 1, u);
 
             if (fin_doc >= 0) {
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
                     int lb = w * NCB + cb;
-                    float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
+                    int row = idx[cb];
+                    if constexpr (ARGMAX && TR::DT != MAXSIM_F32)
+                        row = packed_key_row(row, h);
+                    float sum = finish_block<ARGMAX>(p, m[cb], row, col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
                     if (lane == 0) {
                         if (direct) {
                             if (lb < nb)

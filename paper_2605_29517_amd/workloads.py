@@ -28,6 +28,21 @@ def unit_rows(shape, dtype: str, seed: int, device="cpu", generator=None) -> tor
     return x.to(TORCH_DTYPE[dtype]).contiguous()
 
 
+def biased_rows(shape, dtype: str, seed: int, device="cpu", bias: float = 0.0, scale: float = 1.0,
+                direction_seed: int = 7) -> torch.Tensor:
+    """Rows (noise + bias * v) / norm * scale: noise i.i.d. N(0, 1/d) (norm about 1), v one fixed unit direction
+    shared by every call with the same direction_seed.  bias > 0 pulls all rows towards v, bias < 0 away from it
+    (two tensors with opposite biases have negative inner products throughout); scale gives rows that are not
+    unit-norm.  Normalised in fp32, then scaled and rounded to dtype."""
+    d = shape[-1]
+    v = torch.randn(d, generator=_gen(direction_seed, device), device=device, dtype=torch.float32)
+    v = v / v.norm()
+    x = torch.randn(*shape, generator=_gen(seed, device), device=device, dtype=torch.float32) / math.sqrt(d)
+    x = x + bias * v
+    x = x / x.norm(dim=-1, keepdim=True).clamp_min(1e-30) * scale
+    return x.to(TORCH_DTYPE[dtype]).contiguous()
+
+
 def tiny_forward(seed: int = 0, n_docs: int = 1000, l_q: int = 32, l_d: int = 128, d: int = 128):
     """Config 1: one query, fp32, numpy default_rng(seed); Q drawn first, then D; rows l2-normalised."""
     rng = np.random.default_rng(seed)

@@ -91,6 +91,42 @@ def test_duplicate_tokens_keep_first_index():
     assert torch.equal(a, a1) and torch.equal(s, s1)
 
 
+# Similarities that are negative throughout, partly, or shifted per document (token rows of real encoders share a
+# mean direction): the argmax fold of the tile kernel orders cells through their bit patterns, which is only right
+# among non-negative values, and falls back to compare-and-select while a running maximum is negative.
+# (n_q, l_q, b, l_d): tile kernel with 4, 2 and 1 blocks per wavefront; streaming kernel; ragged
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("shape", [(40, 32, 6, 200), (2, 256, 5, 130), (1, 1024, 3, 100), (1, 200, 4, 90), (2, 32, 9, 70)])
+@pytest.mark.parametrize("q_bias,d_bias", [(1.0, -1.0), (0.6, 0.6), (0.4, -0.2)])
+def test_argmax_with_negative_and_shifted_similarities(shape, q_bias, d_bias, dtype):
+    n_q, l_q, b, l_d = shape
+    Q = W.biased_rows((n_q, l_q, 128), dtype, 61, DEV, bias=q_bias)
+    D = W.biased_rows((b, l_d, 128), dtype, 62, DEV, bias=d_bias)
+    D[b // 2:] = W.biased_rows((b - b // 2, l_d, 128), dtype, 63, DEV, bias=-d_bias)   # half of the documents the other way
+    rtol = RTOL_F32 if dtype == "f32" else RTOL_16
+    forward_parity_uniform(Q, D.contiguous(), M.maxsim_forward, True, rtol)
+    lens = np.array([l_d, 1, 33, 0, l_d // 2, 70])
+    off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+    Dp = W.biased_rows((int(lens.sum()), 128), dtype, 64, DEV, bias=d_bias)
+    forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, True, rtol)
+
+
+# Rows that are not unit-norm (the ABI does not ask for it): similarities of 1e-6 and of 1e+6
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("want_argmax", [False, True])
+@pytest.mark.parametrize("scale", [1e-3, 30.0, 1e3])
+@pytest.mark.parametrize("shape", [(40, 32, 6, 200), (1, 32, 20, 100), (3, 300, 4, 70)])
+def test_rows_that_are_not_unit_norm(shape, scale, want_argmax, dtype):
+    if dtype == "f16" and scale > 100:
+        pytest.skip("fp16 cannot hold rows of that magnitude times each other")
+    n_q, l_q, b, l_d = shape
+    Q = W.biased_rows((n_q, l_q, 128), dtype, 71, DEV, bias=0.3, scale=scale)
+    D = W.biased_rows((b, l_d, 128), dtype, 72, DEV, bias=-0.1, scale=scale)
+    # the absolute slack for scores that sit at zero scales with the similarities (scale^2)
+    forward_parity_uniform(Q, D, M.maxsim_forward, want_argmax, RTOL_F32 if dtype == "f32" else RTOL_16,
+                           atol_per_token=1e-6 * scale * scale)
+
+
 def test_argument_errors():
     Q = W.unit_rows((1, 32, 128), "f16", 1, DEV)
     D = W.unit_rows((4, 40, 128), "f16", 2, DEV)

@@ -80,6 +80,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_29517_amd import binding as M
+    from paper_2605_29517_amd import probe as P
     from paper_2605_29517_amd import workloads as W
 
     if not torch.cuda.is_available():
@@ -379,15 +380,15 @@ def main():
         zeros = torch.zeros(1 << 20, dtype=torch.float16, device=dev)
         for name, kind, ops, iters in (("mfma_f16_unit_norm_operands", 0, rows16, 60000), ("mfma_bf16_unit_norm_operands", 1, rowsbf, 60000),
                                        ("mfma_i8_random_operands", 2, rows8, 60000), ("mfma_f16_zero_operands", 0, zeros, 60000)):
-            n_ops = M.PROBE_MFMA_OPS_PER_ITER[kind] * iters
-            w, a, m, mn = time_launches(lambda: M.maxsim_probe_mfma(kind, ops, iters, sink), 8, 3)
+            n_ops = P.PROBE_MFMA_OPS_PER_ITER[kind] * iters
+            w, a, m, mn = time_launches(lambda: P.maxsim_probe_mfma(kind, ops, iters, sink), 8, 3)
             ceil[name] = {"ms": round(a, 3), "tera_ops_per_s": round(n_ops / (a * 1e-3) / 1e12, 1)}
         big = torch.empty(1 << 30, dtype=torch.int32, device=dev)   # 4 GiB
         big.fill_(1)
         dst = torch.empty(1 << 28, dtype=torch.int32, device=dev)   # 1 GiB
-        w, a, m, mn = time_launches(lambda: M.maxsim_probe_read(big, sink), 10, 3)
+        w, a, m, mn = time_launches(lambda: P.maxsim_probe_read(big, sink), 10, 3)
         ceil["hbm_read_stream"] = {"ms": round(a, 3), "GB_per_s": round(big.numel() * 4 / (a * 1e-3) / 1e9, 1)}
-        w, a, m, mn = time_launches(lambda: M.maxsim_probe_copy(big[:1 << 28], dst), 10, 3)
+        w, a, m, mn = time_launches(lambda: P.maxsim_probe_copy(big[:1 << 28], dst), 10, 3)
         ceil["hbm_copy_1GiB"] = {"ms": round(a, 3), "GB_per_s_read_plus_write": round(2 * dst.numel() * 4 / (a * 1e-3) / 1e9, 1),
                                  "bytes_read": dst.numel() * 4, "bytes_written": dst.numel() * 4}
         out["ceilings"] = ceil

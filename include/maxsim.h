@@ -17,22 +17,26 @@
  *   - Tensors are row-major with the innermost stride 1 and no gaps.  Base
  *     pointers of Q, D and the int8 tensors must be 16-byte aligned, all other
  *     pointers 4-byte aligned.
- *   - d (embedding width): 128 everywhere (the paper's setting, Tab. "shapes").  The float
- *     forward entry points (maxsim_forward, _ragged, _streamed) also take any width whose rows are
- *     a multiple of 64 bytes, from d = 32 up to rows of 16 KB: d = 32, 64, 96, ... , 8192 for
- *     fp16/bf16 and d = 32, 48, 64, ... , 4096 for fp32 (the paper's "fat embedding" extension,
- *     App. "split-d").  Rows of 128, 256 and 512 bytes can keep the queries in registers; every
- *     other width streams both operands in slabs of the embedding dimension (the paper's inner loop
- *     over d).  Other widths must be zero-padded by the caller; they, and any width other than 128
- *     at the backward and int8 entry points, return MAXSIM_ERR_UNSUPPORTED.
- *   - Two kernels use more than 64 KB of LDS (the float forward for the wide rows above and the int8
- *     forward for corpora of 4096 documents or more); the library allows that once per device, at
- *     the first such call, which therefore must not be made while `stream` is being captured into
- *     a HIP graph.  Every later call may be captured.
+ *   - d (embedding width).  The paper's setting is 128 (Tab. "shapes"); its "fat embedding" extension
+ *     (App. "split-d") goes to 2048.  Here:
+ *       float forward (maxsim_forward, _ragged, _streamed): any width whose rows are a multiple of 64 bytes, from
+ *         d = 32 up to rows of 16 KB: d = 32, 64, 96, ... , 8192 for fp16/bf16 and d = 32, 48, 64, ... , 4096 for
+ *         fp32.  Rows of 128, 256 and 512 bytes can keep the queries in registers; every other width streams both
+ *         operands in slabs of the embedding dimension (the paper's inner loop over d).
+ *       backward (maxsim_backward, _ragged, _csr, _csr_static): any multiple of 8 from 8 to 8192; Q must stay
+ *         below 4 GiB and D below 64 GiB.
+ *       int8 entry points and the quantiser: 128 only.
+ *     Other widths must be zero-padded by the caller; anything else returns MAXSIM_ERR_UNSUPPORTED.
+ *   - Four kernel families use more than 64 KB of LDS, which HIP wants allowed per kernel and device before the
+ *     first launch.  maxsim_init() does that (and all other per-device set-up) for the current device; an entry
+ *     point whose device has not been set up does it itself first, which is not possible while `stream` is being
+ *     captured into a HIP graph: call maxsim_init() once per device before capturing anything.
  *   - L_q and L_d are arbitrary positive integers (no tile multiples needed).
  *   - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
- *   - Return value: MAXSIM_OK (0) or a negative error code; on error nothing
- *     was enqueued.  No exceptions, no abort, nothing printed.
+ *   - Return value: MAXSIM_OK (0) or a negative error code.  MAXSIM_ERR_INVALID, _UNSUPPORTED and _SCRATCH
+ *     are found before anything is enqueued.  MAXSIM_ERR_LAUNCH means the HIP runtime refused a step of the
+ *     call: earlier steps of the same call (kernels, copies, waits between streams) may already be queued and the
+ *     outputs are then undefined.  No exceptions, no abort, nothing printed.
  */
 #ifndef MAXSIM_H
 #define MAXSIM_H
@@ -55,6 +59,14 @@ typedef enum { MAXSIM_F32 = 0, MAXSIM_F16 = 1, MAXSIM_BF16 = 2 } maxsim_dtype;
 const char *maxsim_strerror(int code);
 
 /*
+ * Per-device set-up for the CURRENT device: raises the LDS limit of the kernels that need it and looks up
+ * the library's static scratch array.  Allocates nothing, enqueues nothing, may be called any number of times
+ * and from several host threads.  Optional unless entry points are to be captured into HIP graphs (see above).
+ * Returns MAXSIM_OK or MAXSIM_ERR_LAUNCH (the HIP runtime refused).
+ */
+int maxsim_init(void);
+
+/*
  * Fused forward over a uniform corpus (Eq. 1; Alg. 1; Prop. 1).
  *   Q       [n_q, l_q, d]  dtype          query token embeddings
  *   D       [b,   l_d, d]  dtype          document token embeddings
@@ -63,6 +75,9 @@ const char *maxsim_strerror(int code);
  *                                         the document (Sec. "Closed-Form Gradients");
  *                                         ties go to the lowest index ("Tied maxima")
  * Products are formed in the input dtype's exact values and accumulated in fp32.
+ * With fp16/bf16 inputs and argmax requested, similarities below 512 in magnitude that differ by less than
+ * 2^-19 relative count as tied (the lower index wins) and the maxima that enter the score may be truncated by
+ * that much; without argmax, and for fp32 inputs, the maxima are the exact fp32 sums.
  */
 int maxsim_forward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                    maxsim_dtype dtype, float *scores, int32_t *argmax, void *stream);
@@ -107,9 +122,10 @@ int maxsim_forward_ragged(const void *Q, int n_q, int l_q, const void *D_packed,
  *   dQ      [n_q, l_q, d] float32 fully overwritten:  dQ[q,i,:] = sum_b dscore[q,b] D[b, A[q,b,i], :]
  *   dD      [b,  l_d, d]  float32 fully overwritten:  dD[b,t,:] = sum_{(q,i): A[q,b,i]=t} dscore[q,b] Q[q,i,:]
  * Accumulation is fp32 in a fixed order: results are bitwise reproducible from run to run
- * (no atomics; every dD row has one owner, a wavefront or a group of sixteen lanes, which adds
- * the row's edges in argmax order: the role of the paper's inverse-grid CSR, without building it
- * in global memory).
+ * (no atomics; every dD row has one owner, a wavefront, which adds the row's edges by increasing edge id
+ * (q * b + j) * l_q + i: the role of the paper's inverse-grid CSR, without building it in global memory;
+ * dQ adds the documents of each of up to eight contiguous partitions in order and then the partitions in order).
+ * dD doubles as work space during the call: it holds partial sums of dQ until its own rows are written.
  */
 int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                     maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ,
@@ -143,8 +159,7 @@ int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed
  *                                           increasing id within a row; only the first
  *                                           row_ptr[b * l_d] entries are written
  * Limits: l_d <= 4096 and n_q * b * l_q < 2^31 (MAXSIM_ERR_UNSUPPORTED beyond).  The result is
- * the same on every run.  argmax must not change while the call is in flight.  The first call
- * on a device must not be made under stream capture (it raises the kernel's LDS limit).
+ * the same on every run.  argmax must not change while the call is in flight.
  */
 int maxsim_csr_build(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d, int32_t *row_ptr,
                      int32_t *col_idx, void *stream);
@@ -171,7 +186,8 @@ int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t 
  *   as maxsim_backward_csr (identical bits); the CSR itself is not returned.
  *   All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different
  *   streams, different host threads) race; calls on one stream are ordered and safe.  Nothing has to be
- *   cleared between calls.  The first call on a device looks up the array's address (no allocation).
+ *   cleared between calls.  The array's address is looked up by the per-device set-up (maxsim_init, or the first
+ *   call of any entry point on the device): no allocation there either.
  */
 int maxsim_backward_csr_static(const void *Q, int n_q, int l_q, const void *D, int64_t b, int l_d, int d,
                                maxsim_dtype dtype, const int32_t *argmax, const float *dscore, float *dQ,
@@ -232,25 +248,6 @@ int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q
  */
 int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss,
                    void *stream);
-
-/*
- * Diagnostics (not part of the paper's operator): what the device sustains, for roofline context.
- *
- * maxsim_probe_mfma: a register-only loop of 32x32 MFMAs with four independent accumulators,
- *   512 workgroups x 4 wavefronts, `iters` rounds of 4 instructions per wavefront.
- *   kind 0 = fp16 (32x32x16), 1 = bf16 (32x32x16), 2 = int8 (32x32x32), 3 = fp16 with ONE
- *   accumulator (each MFMA waits for the one before: the cost of a dependent chain).  `operands` is >= 1 MiB of
- *   device memory whose bits are used as MFMA operands (random bits give the rate under realistic
- *   switching activity, zeros the rate at full clocks).  Operations per launch:
- *   512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1/3, 2*32*32*32 for kind 2).
- * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them.
- * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
- *   traffic for calibrating profiler byte counters.
- * `sink` is 4 bytes of device memory that is (practically) never written.
- */
-int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream);
-int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream);
-int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -16,10 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libmaxsim.so")
 MAXSIM_F32, MAXSIM_F16, MAXSIM_BF16 = 0, 1, 2
 _DTYPE = {torch.float32: MAXSIM_F32, torch.float16: MAXSIM_F16, torch.bfloat16: MAXSIM_BF16}
 
-SYMBOLS = ("maxsim_strerror", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
+SYMBOLS = ("maxsim_strerror", "maxsim_init", "maxsim_forward", "maxsim_forward_ragged", "maxsim_forward_streamed", "maxsim_backward", "maxsim_backward_ragged",
            "maxsim_csr_build", "maxsim_backward_csr", "maxsim_backward_csr_static",
-           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_forward_i8_streamed", "maxsim_ce_grad",
-           "maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
+           "maxsim_quantize_rows_i8", "maxsim_forward_i8", "maxsim_forward_i8_ragged", "maxsim_forward_i8_streamed", "maxsim_ce_grad")
 
 _lib = None
 
@@ -67,12 +66,8 @@ def load():
     L.maxsim_forward_i8_streamed.argtypes = [p, p, i, i, p, p, l, i, i, l, p, p, p, p]
     L.maxsim_ce_grad.restype = i
     L.maxsim_ce_grad.argtypes = [p, i, i, f, p, p, p]
-    L.maxsim_probe_mfma.restype = i
-    L.maxsim_probe_mfma.argtypes = [i, p, i, p, p]
-    L.maxsim_probe_read.restype = i
-    L.maxsim_probe_read.argtypes = [p, l, p, p]
-    L.maxsim_probe_copy.restype = i
-    L.maxsim_probe_copy.argtypes = [p, p, l, p]
+    L.maxsim_init.restype = i
+    L.maxsim_init.argtypes = []
     _lib = L
     return L
 
@@ -90,6 +85,27 @@ def _dev(t: torch.Tensor, name: str, dtype=None):
     if dtype is not None and t.dtype != dtype:
         raise MaxSimError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _same(t: torch.Tensor, name: str, shape, dtype=None):
+    """Shape (and dtype) of a tensor the C side will index with the sizes of the others."""
+    if tuple(t.shape) != tuple(shape):
+        raise MaxSimError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    if dtype is not None and t.dtype != dtype:
+        raise MaxSimError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+
+
+def _same_device(ref: torch.Tensor, **tensors):
+    for name, t in tensors.items():
+        if t is not None and t.device != ref.device:
+            raise MaxSimError("%s must be on %s like the other tensors, got %s" % (name, ref.device, t.device))
+
+
+def maxsim_init(device=None):
+    """Per-device set-up (LDS limits, static scratch): needed before entry points are captured into a HIP graph."""
+    L = load()
+    with torch.cuda.device(device if device is not None else torch.cuda.current_device()):
+        _check(L.maxsim_init(), "maxsim_init")
 
 
 def _stream(t: torch.Tensor):
@@ -121,6 +137,10 @@ def maxsim_forward(Q, D, scores=None, argmax=None, want_argmax=False):
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
     if argmax is None and want_argmax:
         argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
+    _same(scores, "scores", (n_q, b), torch.float32)
+    if argmax is not None:
+        _same(argmax, "argmax", (n_q, b, l_q), torch.int32)
+    _same_device(Q, D=D, scores=scores, argmax=argmax)
     with _on_device(Q, "Q"):
         rc = L.maxsim_forward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                               _dev(scores, "scores", torch.float32),
@@ -143,6 +163,12 @@ def maxsim_forward_ragged(Q, D_packed, doc_offsets, total_tokens=None, scores=No
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
     if argmax is None and want_argmax:
         argmax = torch.empty(n_q, b, l_q, dtype=torch.int32, device=Q.device)
+    if b < 1 or int(total_tokens) > T:
+        raise MaxSimError("doc_offsets must hold b + 1 >= 2 entries and total_tokens may not exceed the rows of D_packed")
+    _same(scores, "scores", (n_q, b), torch.float32)
+    if argmax is not None:
+        _same(argmax, "argmax", (n_q, b, l_q), torch.int32)
+    _same_device(Q, D_packed=D_packed, doc_offsets=doc_offsets, scores=scores, argmax=argmax)
     with _on_device(Q, "Q"):
         rc = L.maxsim_forward_ragged(_dev(Q, "Q"), n_q, l_q, _dev(D_packed, "D_packed"),
                                      _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
@@ -169,6 +195,8 @@ def maxsim_forward_streamed(Q, D_host, block_docs, staging=None, scores=None):
         raise MaxSimError("staging must hold 2 * block_docs documents of the corpus dtype")
     if scores is None:
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q.device)
+    _same(scores, "scores", (n_q, b), torch.float32)
+    _same_device(Q, staging=staging, scores=scores)
     with _on_device(Q, "Q"):
         rc = L.maxsim_forward_streamed(_dev(Q, "Q"), n_q, l_q, ctypes.c_void_p(D_host.data_ptr()), b, l_d, d,
                                        _DTYPE[Q.dtype], block_docs, _dev(staging, "staging"),
@@ -182,12 +210,17 @@ def maxsim_backward(Q, D, argmax, dscore, dQ=None, dD=None):
     L = load()
     n_q, l_q, d = Q.shape
     b, l_d, _ = D.shape
+    if D.shape[2] != d or D.dtype != Q.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
     if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
         raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
     if dQ is None:
         dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
     if dD is None:
         dD = torch.empty(b, l_d, d, dtype=torch.float32, device=Q.device)
+    _same(dQ, "dQ", (n_q, l_q, d), torch.float32)
+    _same(dD, "dD", (b, l_d, d), torch.float32)
+    _same_device(Q, D=D, argmax=argmax, dscore=dscore, dQ=dQ, dD=dD)
     with _on_device(Q, "Q"):
         rc = L.maxsim_backward(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                                _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
@@ -206,10 +239,17 @@ def maxsim_backward_ragged(Q, D_packed, doc_offsets, argmax, dscore, total_token
         raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
     if total_tokens is None:
         total_tokens = T
+    if D_packed.dim() != 2 or D_packed.shape[1] != d or D_packed.dtype != Q.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D_packed must share d and a dtype in {fp32, fp16, bf16}")
+    if b < 1 or int(total_tokens) > T:
+        raise MaxSimError("doc_offsets must hold b + 1 >= 2 entries and total_tokens may not exceed the rows of D_packed")
     if dQ is None:
         dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
     if dD is None:
         dD = torch.empty(T, d, dtype=torch.float32, device=Q.device)
+    _same(dQ, "dQ", (n_q, l_q, d), torch.float32)
+    _same(dD, "dD", (T, d), torch.float32)
+    _same_device(Q, D_packed=D_packed, doc_offsets=doc_offsets, argmax=argmax, dscore=dscore, dQ=dQ, dD=dD)
     with _on_device(Q, "Q"):
         rc = L.maxsim_backward_ragged(_dev(Q, "Q"), n_q, l_q, _dev(D_packed, "D_packed"),
                                       _dev(doc_offsets, "doc_offsets", torch.int32), b, int(total_tokens), d,
@@ -256,6 +296,11 @@ def maxsim_backward_csr(Q, D, argmax, dscore, row_ptr=None, col_idx=None, dQ=Non
         dQ = torch.empty(n_q, l_q, d, dtype=torch.float32, device=Q.device)
     if dD is None:
         dD = torch.empty(b, l_d, d, dtype=torch.float32, device=Q.device)
+    if D.shape[2] != d or D.dtype != Q.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
+    _same(dQ, "dQ", (n_q, l_q, d), torch.float32)
+    _same(dD, "dD", (b, l_d, d), torch.float32)
+    _same_device(Q, D=D, argmax=argmax, dscore=dscore, row_ptr=row_ptr, col_idx=col_idx, dQ=dQ, dD=dD)
     with _on_device(Q, "Q"):
         rc = L.maxsim_backward_csr(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                                    _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
@@ -273,8 +318,11 @@ def maxsim_backward_csr_static(Q, D, argmax, dscore, dQ, dD):
     b, l_d, _ = D.shape
     if tuple(argmax.shape) != (n_q, b, l_q) or tuple(dscore.shape) != (n_q, b):
         raise MaxSimError("argmax must be [n_q,b,l_q] and dscore [n_q,b]")
-    if tuple(dQ.shape) != (n_q, l_q, d) or tuple(dD.shape) != (b, l_d, d) or D.dtype != Q.dtype or D.shape[2] != d:
-        raise MaxSimError("dQ must be [n_q,l_q,d], dD [b,l_d,d], and D must share Q's dtype and d")
+    if D.shape[2] != d or D.dtype != Q.dtype or Q.dtype not in _DTYPE:
+        raise MaxSimError("Q and D must share d and a dtype in {fp32, fp16, bf16}")
+    _same(dQ, "dQ", (n_q, l_q, d), torch.float32)
+    _same(dD, "dD", (b, l_d, d), torch.float32)
+    _same_device(Q, D=D, argmax=argmax, dscore=dscore, dQ=dQ, dD=dD)
     with _on_device(Q, "Q"):
         rc = L.maxsim_backward_csr_static(_dev(Q, "Q"), n_q, l_q, _dev(D, "D"), b, l_d, d, _DTYPE[Q.dtype],
                                           _dev(argmax, "argmax", torch.int32), _dev(dscore, "dscore", torch.float32),
@@ -292,6 +340,12 @@ def maxsim_quantize_rows_i8(X, X_i8=None, scale=None):
         X_i8 = torch.empty(X.shape, dtype=torch.int8, device=X.device)
     if scale is None:
         scale = torch.empty(X.shape[:-1], dtype=torch.float32, device=X.device)
+    if X.dtype not in _DTYPE:
+        raise MaxSimError("X must have a dtype in {fp32, fp16, bf16}")
+    _same(X_i8, "X_i8", X.shape, torch.int8)
+    if scale.numel() != rows:
+        raise MaxSimError("scale must hold one entry per row of X")
+    _same_device(X, X_i8=X_i8, scale=scale)
     with _on_device(X, "X"):
         rc = L.maxsim_quantize_rows_i8(_dev(X, "X"), rows, d, _DTYPE[X.dtype], _dev(X_i8, "X_i8", torch.int8),
                                        _dev(scale, "scale", torch.float32), _stream(X))
@@ -303,9 +357,15 @@ def maxsim_forward_i8(Q_i8, q_scale, D_i8, d_scale, scores=None):
     """int8 scoring: Q_i8 [n_q,l_q,d] + q_scale [n_q,l_q], D_i8 [b,l_d,d] + d_scale [b,l_d] -> scores [n_q,b]."""
     L = load()
     n_q, l_q, d = Q_i8.shape
-    b, l_d, _ = D_i8.shape
+    b, l_d, d2 = D_i8.shape
     if scores is None:
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
+    if d2 != d:
+        raise MaxSimError("Q_i8 and D_i8 must share d")
+    _same(q_scale, "q_scale", (n_q, l_q), torch.float32)
+    _same(d_scale, "d_scale", (b, l_d), torch.float32)
+    _same(scores, "scores", (n_q, b), torch.float32)
+    _same_device(Q_i8, q_scale=q_scale, D_i8=D_i8, d_scale=d_scale, scores=scores)
     with _on_device(Q_i8, "Q_i8"):
         rc = L.maxsim_forward_i8(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
                                  _dev(D_i8, "D_i8", torch.int8), _dev(d_scale, "d_scale", torch.float32), b, l_d, d,
@@ -324,6 +384,12 @@ def maxsim_forward_i8_ragged(Q_i8, q_scale, D_i8_packed, d_scale_packed, doc_off
         total_tokens = T
     if scores is None:
         scores = torch.empty(n_q, b, dtype=torch.float32, device=Q_i8.device)
+    if D_i8_packed.dim() != 2 or D_i8_packed.shape[1] != d or b < 1 or int(total_tokens) > T:
+        raise MaxSimError("D_i8_packed must be [T,d] with Q_i8's d, doc_offsets [b+1], total_tokens <= T")
+    _same(q_scale, "q_scale", (n_q, l_q), torch.float32)
+    _same(d_scale_packed, "d_scale_packed", (T,), torch.float32)
+    _same(scores, "scores", (n_q, b), torch.float32)
+    _same_device(Q_i8, q_scale=q_scale, D_i8_packed=D_i8_packed, d_scale_packed=d_scale_packed, doc_offsets=doc_offsets, scores=scores)
     with _on_device(Q_i8, "Q_i8"):
         rc = L.maxsim_forward_i8_ragged(_dev(Q_i8, "Q_i8", torch.int8), _dev(q_scale, "q_scale", torch.float32), n_q, l_q,
                                         _dev(D_i8_packed, "D_i8_packed", torch.int8),
@@ -367,44 +433,10 @@ def maxsim_ce_grad(scores, tau, g=None, loss=None):
         g = torch.empty(n, b, dtype=torch.float32, device=scores.device)
     if loss is None:
         loss = torch.empty(1, dtype=torch.float32, device=scores.device)
+    _same(g, "g", (n, b), torch.float32)
+    _same_device(scores, g=g, loss=loss)
     with _on_device(scores, "scores"):
         rc = L.maxsim_ce_grad(_dev(scores, "scores", torch.float32), n, b, float(tau), _dev(g, "g", torch.float32),
                               _dev(loss, "loss", torch.float32), _stream(scores))
     _check(rc, "maxsim_ce_grad")
     return g, loss
-
-
-PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32,
-                           3: 512 * 4 * 4 * 2 * 32 * 32 * 16}
-
-
-def maxsim_probe_mfma(kind, operands, iters, sink):
-    """Register-only MFMA loop (diagnostic).  Returns the number of operations one launch performs."""
-    L = load()
-    if operands.numel() * operands.element_size() < (1 << 20):
-        raise MaxSimError("operands must hold at least 1 MiB")
-    with _on_device(operands, "operands"):
-        rc = L.maxsim_probe_mfma(int(kind), _dev(operands, "operands"), int(iters), _dev(sink, "sink", torch.float32),
-                                 _stream(operands))
-    _check(rc, "maxsim_probe_mfma")
-    return PROBE_MFMA_OPS_PER_ITER[int(kind)] * int(iters)
-
-
-def maxsim_probe_read(buf, sink):
-    """Streaming read of a whole tensor (diagnostic).  Returns the bytes read."""
-    L = load()
-    nbytes = buf.numel() * buf.element_size() // 16 * 16
-    with _on_device(buf, "buf"):
-        rc = L.maxsim_probe_read(_dev(buf, "buf"), nbytes, _dev(sink, "sink", torch.float32), _stream(buf))
-    _check(rc, "maxsim_probe_read")
-    return nbytes
-
-
-def maxsim_probe_copy(src, dst):
-    """Plain copy of a whole tensor (diagnostic).  Returns the bytes copied."""
-    L = load()
-    nbytes = min(src.numel() * src.element_size(), dst.numel() * dst.element_size()) // 16 * 16
-    with _on_device(src, "src"):
-        rc = L.maxsim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream(src))
-    _check(rc, "maxsim_probe_copy")
-    return nbytes

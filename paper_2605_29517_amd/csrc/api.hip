@@ -25,9 +25,9 @@ hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
                              int64_t ld, int num_cu, hipStream_t stream);
 hipError_t ce_grad_launch(const float *scores, int n, int b, float tau, float *g, float *loss, hipStream_t stream);
-hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream);
-hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream);
-hipError_t probe_copy_launch(const void *src, void *dst, int64_t bytes, int num_cu, hipStream_t stream);
+hipError_t forward_splitd_init_device();
+hipError_t forward_i8_init_device();
+hipError_t backward_init_device();
 } // namespace maxsim
 
 namespace {
@@ -60,6 +60,28 @@ bool backward_q_ok(int n_q, int l_q, int d, int dtype, int64_t total_tokens)
 {
     const int64_t row_bytes = (int64_t)d * (dtype == MAXSIM_F32 ? 4 : 2);
     return (int64_t)n_q * l_q * row_bytes < (int64_t(1) << 32) && total_tokens <= ((int64_t(1) << 36) - 1) / row_bytes;
+}
+
+// Per-device set-up, done once per device under a lock (two host threads may make their first call at once):
+// the kernels that use more than 64 KB of LDS are allowed to (every instantiation), and the static scratch
+// array's device address is looked up.  maxsim_init runs it for the current device; every entry point runs it
+// after its argument checks, so that callers who never call maxsim_init lose nothing but the freedom to make
+// their first call on a device under stream capture.
+int ensure_init()
+{
+    static bool done[64] = {};
+    static std::mutex guard;
+    std::lock_guard<std::mutex> lock(guard);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return MAXSIM_ERR_LAUNCH;
+    if (done[dev])
+        return MAXSIM_OK;
+    if (maxsim::forward_splitd_init_device() != hipSuccess || maxsim::forward_i8_init_device() != hipSuccess ||
+        maxsim::backward_init_device() != hipSuccess)
+        return MAXSIM_ERR_LAUNCH;
+    done[dev] = true;
+    return MAXSIM_OK;
 }
 
 int finish(hipError_t e) { return e == hipSuccess ? MAXSIM_OK : MAXSIM_ERR_LAUNCH; }
@@ -107,6 +129,8 @@ int forward_common(const void *Q, int n_q, int l_q, const void *D, const int32_t
     p.n_q = n_q;
     p.l_q = l_q;
     p.l_d = l_d;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::forward_launch(p, dtype, d, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
@@ -167,6 +191,8 @@ int stream_blocks(hipStream_t compute, int64_t b, int64_t block_docs, Copy copy_
 
 extern "C" {
 
+int maxsim_init(void) { return ensure_init(); }
+
 const char *maxsim_strerror(int code)
 {
     switch (code) {
@@ -204,6 +230,8 @@ int maxsim_forward_streamed(const void *Q, int n_q, int l_q, const void *D_host,
     if (block_docs > ((int64_t(1) << 31) - 1) / l_d || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24))
         return MAXSIM_ERR_UNSUPPORTED;
     const int64_t doc_bytes = (int64_t)l_d * d * ((int)dtype == MAXSIM_F32 ? 4 : 2);
+    if (int rc = ensure_init())
+        return rc;
     hipStream_t compute = static_cast<hipStream_t>(stream);
     const int cus = num_cu();
     return stream_blocks(
@@ -245,6 +273,8 @@ int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q
     if (block_docs > ((int64_t(1) << 31) - 1) / l_d || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
         return MAXSIM_ERR_UNSUPPORTED;
     const int64_t doc_bytes = (int64_t)l_d * d;
+    if (int rc = ensure_init())
+        return rc;
     hipStream_t compute = static_cast<hipStream_t>(stream);
     const int cus = num_cu();
     return stream_blocks(
@@ -285,6 +315,8 @@ int maxsim_backward(const void *Q, int n_q, int l_q, const void *D, int64_t b, i
         return MAXSIM_ERR_UNSUPPORTED;
     if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, b * (int64_t)l_d))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::backward_launch(Q, n_q, l_q, D, nullptr, b, l_d, b * (int64_t)l_d, d, (int)dtype, argmax, dscore,
                                           dQ, dD, num_cu(), static_cast<hipStream_t>(stream)));
 }
@@ -304,6 +336,8 @@ int maxsim_backward_ragged(const void *Q, int n_q, int l_q, const void *D_packed
     if (total_tokens >= (int64_t(1) << 31) || b >= (int64_t(1) << 31) || (int64_t)n_q * l_q >= (int64_t(1) << 31) ||
         (int64_t)n_q * b >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::backward_launch(Q, n_q, l_q, D_packed, doc_offsets, b, 0, total_tokens, d, (int)dtype, argmax,
                                           dscore, dQ, dD_packed, num_cu(), static_cast<hipStream_t>(stream)));
 }
@@ -323,6 +357,8 @@ int maxsim_csr_build(const int32_t *argmax, int n_q, int64_t b, int l_q, int l_d
         return MAXSIM_ERR_INVALID;
     if (!csr_shape_ok(n_q, b, l_q, l_d))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::csr_build_launch(argmax, n_q, b, l_q, l_d, row_ptr, col_idx, num_cu(),
                                            static_cast<hipStream_t>(stream)));
 }
@@ -341,6 +377,8 @@ int maxsim_backward_csr(const void *Q, int n_q, int l_q, const void *D, int64_t 
         return MAXSIM_ERR_UNSUPPORTED;
     if (!backward_width_ok(d) || !backward_q_ok(n_q, l_q, d, (int)dtype, b * (int64_t)l_d))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::backward_csr_launch(Q, n_q, l_q, D, b, l_d, d, (int)dtype, argmax, dscore, row_ptr, col_idx, dQ,
                                               dD, num_cu(), static_cast<hipStream_t>(stream)));
 }
@@ -360,6 +398,8 @@ int maxsim_backward_csr_static(const void *Q, int n_q, int l_q, const void *D, i
         return MAXSIM_ERR_UNSUPPORTED;
     if (!maxsim::csr_static_fits(n_q, b, l_q, l_d))
         return MAXSIM_ERR_SCRATCH;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::backward_csr_static_launch(Q, n_q, l_q, D, b, l_d, d, (int)dtype, argmax, dscore, dQ, dD, num_cu(),
                                                      static_cast<hipStream_t>(stream)));
 }
@@ -375,6 +415,8 @@ int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dty
         return MAXSIM_ERR_UNSUPPORTED;
     if (rows >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::quantize_launch(X, rows, (int)dtype, X_i8, scale, static_cast<hipStream_t>(stream)));
 }
 
@@ -390,6 +432,8 @@ int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q
     if (b >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) ||
         l_q > 1024 || b * (int64_t)l_d >= (int64_t(1) << 31))
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, nullptr, b, l_d, b * (int64_t)l_d,
                                             scores, b, num_cu(), static_cast<hipStream_t>(stream)));
 }
@@ -409,6 +453,8 @@ int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, 
     if (b >= (int64_t(1) << 31) || total_tokens >= (int64_t(1) << 31) ||
         (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
         return MAXSIM_ERR_UNSUPPORTED;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8_packed, d_scale_packed, doc_offsets, b, 0,
                                             total_tokens, scores, b, num_cu(), static_cast<hipStream_t>(stream)));
 }
@@ -417,28 +463,9 @@ int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float
 {
     if (!scores || !g || n < 1 || b < n || !(tau > 0.0f))
         return MAXSIM_ERR_INVALID;
+    if (int rc = ensure_init())
+        return rc;
     return finish(maxsim::ce_grad_launch(scores, n, b, tau, g, loss, static_cast<hipStream_t>(stream)));
-}
-
-int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream)
-{
-    if (!operands || !sink || iters < 1 || kind < 0 || kind > 3 || !aligned(operands, 16))
-        return MAXSIM_ERR_INVALID;
-    return finish(maxsim::probe_mfma_launch(kind, operands, iters, sink, static_cast<hipStream_t>(stream)));
-}
-
-int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream)
-{
-    if (!buf || !sink || bytes < 16 || !aligned(buf, 16))
-        return MAXSIM_ERR_INVALID;
-    return finish(maxsim::probe_read_launch(buf, bytes, sink, num_cu(), static_cast<hipStream_t>(stream)));
-}
-
-int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
-{
-    if (!src || !dst || bytes < 16 || !aligned(src, 16) || !aligned(dst, 16))
-        return MAXSIM_ERR_INVALID;
-    return finish(maxsim::probe_copy_launch(src, dst, bytes, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 } // extern "C"

@@ -12,7 +12,6 @@
 // pass over dD, and the summation order is fixed (a row's edges by increasing edge id), so the result is
 // bitwise reproducible and equal to that of the explicit CSR of the paper, which is there as an opt-in
 // (built in global memory, then walked the same way).
-#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -1041,22 +1040,7 @@ hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, 
     c.n_q = n_q;
     c.l_q = l_q;
     c.l_d = l_d;
-    // more than 64 KB of dynamic LDS has to be allowed once per device
-    static bool allowed[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess)
-        return e;
-    if (dev < 0 || dev >= 64)
-        return hipErrorInvalidDevice;
-    if (!allowed[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&csr_place_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (CSR_WAVES * CSR_MAX_LD + CSR_LDS_EXTRA) * (int)sizeof(int));
-        if (e != hipSuccess)
-            return e;
-        allowed[dev] = true;
-    }
+    hipError_t e = hipSuccess;
     const int64_t cap = (int64_t)num_cu * 64;
     const unsigned grid = (unsigned)(b < cap ? b : cap);
     hipLaunchKernelGGL(csr_count_kernel, dim3(grid), dim3(1024), 0, stream, c);
@@ -1126,28 +1110,38 @@ static __device__ __align__(256) int32_t scratch[CSR_STATIC_COL_AT + CSR_STATIC_
 
 namespace {
 int32_t *scratch_ptr[64] = {nullptr}; // device address of `scratch` on each GPU (the array's name is no address on the host)
-std::mutex scratch_guard;
 } // namespace
 
-// Once per device, with that device current: the address of the device's copy of `scratch`.
-static hipError_t csr_static_buffer(int32_t **out)
+// Per-device set-up of this file (called once per device, under the library's lock, with that device current):
+// the address of the device's copy of `scratch`, and the LDS limit of csr_place_kernel.
+hipError_t backward_init_device()
 {
-    std::lock_guard<std::mutex> lock(scratch_guard);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess)
         return e;
     if (dev < 0 || dev >= 64)
         return hipErrorInvalidDevice;
-    if (!scratch_ptr[dev]) {
-        void *ptr = nullptr;
-        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
-        if (e != hipSuccess)
-            return e;
-        if (!ptr)
-            return hipErrorInvalidSymbol;
-        scratch_ptr[dev] = static_cast<int32_t *>(ptr);
-    }
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess)
+        return e;
+    if (!ptr)
+        return hipErrorInvalidSymbol;
+    scratch_ptr[dev] = static_cast<int32_t *>(ptr);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&csr_place_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (CSR_WAVES * CSR_MAX_LD + CSR_LDS_EXTRA) * (int)sizeof(int));
+}
+
+// The device's copy of `scratch` (set up by backward_init_device before any entry point gets here).
+static hipError_t csr_static_buffer(int32_t **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= 64 || !scratch_ptr[dev])
+        return hipErrorInvalidDevice;
     *out = scratch_ptr[dev];
     return hipSuccess;
 }

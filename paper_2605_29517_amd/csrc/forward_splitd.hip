@@ -376,26 +376,29 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
 template <int DT, bool ARGMAX>
 hipError_t launch_splitd(const FwdParams &p, int row_bytes, int grid, hipStream_t stream)
 {
-    // more than 64 KB of dynamic LDS has to be allowed once per device
-    static bool allowed[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess)
-        return e;
-    if (dev < 0 || dev >= 64)
-        return hipErrorInvalidDevice;
-    if (!allowed[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_splitd_kernel<DT, ARGMAX>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, SD_LDS);
-        if (e != hipSuccess)
-            return e;
-        allowed[dev] = true;
-    }
     hipLaunchKernelGGL((fwd_splitd_kernel<DT, ARGMAX>), dim3(grid), dim3(SD_W * 64), SD_LDS, stream, p, p.offsets, row_bytes);
     return hipGetLastError();
 }
 
+template <int DT, bool ARGMAX> hipError_t allow_splitd_lds()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_splitd_kernel<DT, ARGMAX>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, SD_LDS);
+}
+
 } // namespace
+
+// More than 64 KB of dynamic LDS has to be allowed per kernel and device: every instantiation, for the current
+// device (called once per device by the library's set-up).
+hipError_t forward_splitd_init_device()
+{
+    hipError_t e = hipSuccess;
+    if ((e = allow_splitd_lds<MAXSIM_F32, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_F32, true>()) != hipSuccess ||
+        (e = allow_splitd_lds<MAXSIM_F16, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_F16, true>()) != hipSuccess ||
+        (e = allow_splitd_lds<MAXSIM_BF16, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_BF16, true>()) != hipSuccess)
+        return e;
+    return hipSuccess;
+}
 
 // Any row width that is a multiple of 64 bytes.  `num_cu` is the device's CU count.
 hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_cu, hipStream_t stream)

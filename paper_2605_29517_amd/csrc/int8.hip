@@ -32,9 +32,7 @@ constexpr int I8_NU = 4;          // 16-byte chunks per lane per row (chunks 2u 
 constexpr int I8_TILE_ROWS = 64;  // document tokens staged per barrier (two MFMA row tiles)
 constexpr int I8_ROW_STRIDE = I8_ROW_BYTES + 16;
 constexpr int I8_NCB = 4;
-#ifndef I8_PIPE
-#define I8_PIPE 1 // result blocks between a block's MFMAs and its epilogue (2 needs more registers than there are)
-#endif
+constexpr int I8_PIPE = 1; // result blocks between a block's MFMAs and its epilogue (2 needs more registers than there are)
 
 struct I8Params {
     const char *Q;      // [n_q, l_q, 128] int8
@@ -303,9 +301,7 @@ __device__ __forceinline__ void i8d_tile_scales(float *w_scale, float *w_bias, f
     }
 }
 
-#ifndef I8D_LAG_STEPS
-#define I8D_LAG_STEPS 2
-#endif
+constexpr int I8D_LAG_STEPS = 2; // steps between a block's MFMAs and its epilogue in the document-stationary kernels
 
 // One document tile (operands `a`, row scales sc / biases bi) against the NB column blocks in LDS, folded into
 // the running maxima m.  Step t: MFMA (t % 4) of block t / 4, the LDS read of the same chunk of the next block,
@@ -635,24 +631,13 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_split_kernel(I8Params P
     }
 }
 
+// dynamic LDS of the document-stationary kernels for NB column blocks
+constexpr size_t i8_doc_lds(int nb) { return (size_t)nb * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float); }
+constexpr size_t i8_split_lds(int nb) { return i8_doc_lds(nb) + (size_t)2 * I8D_WAVES * nb * BLOCK_COLS * sizeof(float); }
+
 template <int NB> static hipError_t launch_i8_split(const I8Params &P, int grid, hipStream_t s)
 {
-    const size_t lds = (size_t)NB * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float) +
-                       (size_t)2 * I8D_WAVES * NB * BLOCK_COLS * sizeof(float);
-    if (lds > 64 * 1024) { // to be allowed once per device (see launch_i8_doc)
-        static bool allowed[64] = {false};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
-            return hipErrorInvalidDevice;
-        if (!allowed[dev]) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_split_kernel<NB>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess)
-                return e;
-            allowed[dev] = true;
-        }
-    }
-    hipLaunchKernelGGL((fwd_i8_split_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P);
+    hipLaunchKernelGGL((fwd_i8_split_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), i8_split_lds(NB), s, P);
     return hipGetLastError();
 }
 
@@ -664,22 +649,37 @@ template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStr
 
 template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, hipStream_t s)
 {
-    const size_t lds = (size_t)NB * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float);
-    // more than 64 KB of dynamic LDS has to be allowed once per device; afterwards the launch is all there is
-    // (so that later calls can be captured into a graph)
-    static bool allowed[64] = {false};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
-        return hipErrorInvalidDevice;
-    if (!allowed[dev]) {
+    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), i8_doc_lds(NB), s, P, P.f.offsets);
+    return hipGetLastError();
+}
+
+// More than 64 KB of dynamic LDS has to be allowed per kernel and device: every instantiation that needs it, for
+// the current device (called once per device by the library's set-up).
+template <int NB> static hipError_t allow_i8_lds()
+{
+    if (i8_doc_lds(NB) > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)i8_doc_lds(NB));
         if (e != hipSuccess)
             return e;
-        allowed[dev] = true;
     }
-    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), lds, s, P, P.f.offsets);
-    return hipGetLastError();
+    if (NB <= 16 && i8_split_lds(NB) > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_split_kernel<(NB <= 16 ? NB : 16)>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)i8_split_lds(NB <= 16 ? NB : 16));
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t forward_i8_init_device()
+{
+    hipError_t e = hipSuccess;
+    if ((e = allow_i8_lds<1>()) != hipSuccess || (e = allow_i8_lds<2>()) != hipSuccess || (e = allow_i8_lds<4>()) != hipSuccess ||
+        (e = allow_i8_lds<8>()) != hipSuccess || (e = allow_i8_lds<16>()) != hipSuccess || (e = allow_i8_lds<24>()) != hipSuccess ||
+        (e = allow_i8_lds<32>()) != hipSuccess)
+        return e;
+    return hipSuccess;
 }
 
 // offsets == nullptr: uniform corpus [b, l_d, 128]; otherwise packed [total_tokens, 128] with int32 offsets [b + 1]

@@ -1,4 +1,5 @@
-// Diagnostic kernels: what the machine sustains, measured beside the real kernels.
+// Diagnostic kernels for the benchmark (libmaxsim_probe.so, declared in include/maxsim_probe.h; not part of the
+// operator's library): what the machine sustains, measured beside the real kernels.
 //   probe_mfma   register-only MFMA loop on caller-supplied operand bits (random data makes the
 //                part run at the clocks it holds under load; zeros show the unthrottled rate)
 //   probe_read   pure streaming read of a buffer
@@ -29,12 +30,7 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(const uint4 *in, int it
     } else {
         f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
         for (int it = 0; it < iters; ++it) {
-            if (KIND == 3) { // one dependent chain: every MFMA needs the result of the one before
-                Traits<MAXSIM_F16>::mma(a, b0, c0);
-                Traits<MAXSIM_F16>::mma(a, b1, c0);
-                Traits<MAXSIM_F16>::mma(a, b2, c0);
-                Traits<MAXSIM_F16>::mma(a, b3, c0);
-            } else if (KIND == 0) {
+            if (KIND == 0) {
                 Traits<MAXSIM_F16>::mma(a, b0, c0);
                 Traits<MAXSIM_F16>::mma(a, b1, c1);
                 Traits<MAXSIM_F16>::mma(a, b2, c2);
@@ -58,9 +54,14 @@ __global__ void __launch_bounds__(256) probe_read_kernel(const uint4 *p, int64_t
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * 256;
     uint32_t acc = 0;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        uint4 v0 = p[i], v1 = p[i + stride], v2 = p[i + 2 * stride], v3 = p[i + 3 * stride];
-        acc ^= v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+    for (; i + 7 * stride < n_vec; i += 8 * stride) { // eight 16-byte loads in flight per lane
+        uint4 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            v[k] = p[i + k * stride];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }
     for (; i < n_vec; i += stride) {
         uint4 v = p[i];
@@ -77,26 +78,25 @@ __global__ void __launch_bounds__(256) probe_copy_kernel(const uint4 *src, uint4
         dst[i] = src[i];
 }
 
-hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream)
+static hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream)
 {
     const uint4 *in = static_cast<const uint4 *>(operands);
     switch (kind) {
     case 0: hipLaunchKernelGGL((probe_mfma_kernel<0>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     case 1: hipLaunchKernelGGL((probe_mfma_kernel<1>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
-    case 3: hipLaunchKernelGGL((probe_mfma_kernel<3>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     default: hipLaunchKernelGGL((probe_mfma_kernel<2>), dim3(PROBE_BLOCKS), dim3(256), 0, stream, in, iters, sink); break;
     }
     return hipGetLastError();
 }
 
-hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream)
+static hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream)
 {
     hipLaunchKernelGGL(probe_read_kernel, dim3(num_cu * 8), dim3(256), 0, stream, static_cast<const uint4 *>(buf),
                        bytes / 16, sink);
     return hipGetLastError();
 }
 
-hipError_t probe_copy_launch(const void *src, void *dst, int64_t bytes, int num_cu, hipStream_t stream)
+static hipError_t probe_copy_launch(const void *src, void *dst, int64_t bytes, int num_cu, hipStream_t stream)
 {
     hipLaunchKernelGGL(probe_copy_kernel, dim3(num_cu * 8), dim3(256), 0, stream, static_cast<const uint4 *>(src),
                        static_cast<uint4 *>(dst), bytes / 16);
@@ -104,3 +104,46 @@ hipError_t probe_copy_launch(const void *src, void *dst, int64_t bytes, int num_
 }
 
 } // namespace maxsim
+
+#include "../../include/maxsim_probe.h"
+
+namespace {
+int probe_num_cu()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        return 256;
+    return n;
+}
+bool probe_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+} // namespace
+
+extern "C" {
+
+int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream)
+{
+    if (!operands || !sink || iters < 1 || kind < 0 || kind > 2 || !probe_aligned16(operands))
+        return MAXSIM_ERR_INVALID;
+    return maxsim::probe_mfma_launch(kind, operands, iters, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? MAXSIM_OK
+                                                                                                         : MAXSIM_ERR_LAUNCH;
+}
+
+int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream)
+{
+    if (!buf || !sink || bytes < 16 || !probe_aligned16(buf))
+        return MAXSIM_ERR_INVALID;
+    return maxsim::probe_read_launch(buf, bytes, sink, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MAXSIM_OK
+               : MAXSIM_ERR_LAUNCH;
+}
+
+int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
+{
+    if (!src || !dst || bytes < 16 || !probe_aligned16(src) || !probe_aligned16(dst))
+        return MAXSIM_ERR_INVALID;
+    return maxsim::probe_copy_launch(src, dst, bytes, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MAXSIM_OK
+               : MAXSIM_ERR_LAUNCH;
+}
+
+} // extern "C"

@@ -6,8 +6,8 @@ import re
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "maxsim.h")).read()
+def declared_symbols(header="maxsim.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(maxsim_[a-z0-9_]+)\s*\(", text)))
 
@@ -27,6 +27,20 @@ def test_library_exports_every_declared_symbol():
     for name in declared_symbols():
         assert hasattr(lib, name), name
     assert sorted(binding.SYMBOLS) == declared_symbols()
+    assert "maxsim_init" in declared_symbols()
+
+
+def test_probe_library_exports_its_header():
+    """The benchmark's diagnostics live in a library of their own, outside the operator's ABI."""
+    from paper_2605_29517_amd import probe
+    assert os.path.exists(probe.LIB_PATH), "build the libraries first: python -m paper_2605_29517_amd.build"
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(probe.LIB_PATH)
+    for name in declared_symbols("maxsim_probe.h"):
+        assert hasattr(lib, name), name
+    assert sorted(probe.SYMBOLS) == declared_symbols("maxsim_probe.h")
+    assert not [n for n in declared_symbols() if "probe" in n]
+    assert lib.maxsim_probe_mfma(3, None, 1, None, None) == -1      # nothing but argument checks without a GPU
 
 
 def test_error_codes_without_touching_a_gpu():
@@ -34,6 +48,8 @@ def test_error_codes_without_touching_a_gpu():
     L = binding.load()
     assert L.maxsim_strerror(0) == b"ok"
     assert b"invalid" in L.maxsim_strerror(-1)
+    assert b"128" not in L.maxsim_strerror(-2) and b"width" in L.maxsim_strerror(-2)
+    assert b"scratch" in L.maxsim_strerror(-4)
     # null pointers and bad sizes are rejected before any HIP call
     assert L.maxsim_forward(None, 1, 32, None, 4, 40, 128, 1, None, None, None) == -1
     assert L.maxsim_backward(None, 1, 1, None, 1, 1, 128, 1, None, None, None, None, None) == -1

@@ -117,6 +117,31 @@ def test_backward_skewed_argmax(n_q, l_q, b, l_d, adjacent):
     assert torch.equal(cD, dD)      # long lists are walked by a whole wavefront: same order, same bits
 
 
+# Rows that are not unit-norm and similarities that are negative throughout: the backward only moves rows and
+# multiplies by the upstream gradient, but the forward that feeds it (argmax from the GPU here) has to pick the
+# right winners there as well.  Compared with the oracle's backward through the SAME (GPU) argmax, after that
+# argmax has itself been checked against the oracle's under the margin rule.
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("scale,q_bias,d_bias", [(1e-3, 0.3, -0.1), (1.0, 1.0, -1.0), (30.0, 0.5, 0.5)])
+def test_forward_backward_chain_on_shifted_and_scaled_rows(scale, q_bias, d_bias, dtype):
+    n_q, l_q, b, l_d = 40, 32, 7, 150
+    Q = W.biased_rows((n_q, l_q, 128), dtype, 81, DEV, bias=q_bias, scale=scale)
+    D = W.biased_rows((b, l_d, 128), dtype, 82, DEV, bias=d_bias, scale=scale)
+    s, a = M.maxsim_forward(Q, D, want_argmax=True)
+    torch.cuda.synchronize()
+    _, ra, rm = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype)
+    clear = rm > 1e-3
+    assert np.array_equal(a.cpu().numpy()[clear], ra[clear])
+    rng = np.random.default_rng(83)
+    g = rng.standard_normal((n_q, b)).astype(np.float32)
+    A = a.cpu().numpy()
+    rQ, rD = O.backward(W.to_raw_numpy(Q), W.to_raw_numpy(D), dtype, A, g.astype(np.float64))
+    dQ, dD = M.maxsim_backward(Q, D, a, torch.from_numpy(g).to(DEV))
+    torch.cuda.synchronize()
+    close(dQ, rQ, "dQ")
+    close(dD, rD, "dD")
+
+
 def test_negative_indices_are_skipped():
     run_case(4, 32, 6, 70, "f16", 9, holes=True)
 

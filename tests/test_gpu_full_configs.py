@@ -12,7 +12,7 @@ from oracle import cpu_oracle as O
 from paper_2605_29517_amd import binding as M
 from paper_2605_29517_amd import workloads as W
 
-from parity import ARGMAX_MARGIN, RTOL_16, check_scores
+from parity import ARGMAX_MARGIN, RTOL_16, check_argmax, check_scores, decode
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -53,15 +53,52 @@ def test_config2_ragged_rerank_full_size(config2, n_q):
     assert float(s.abs().max()) <= 32.0 * 1.001
 
 
+def test_config2_full_size_with_argmax_four_queries(config2):
+    """Config 2 with four queries and the argmax output (the tile kernel's ragged argmax path at full size)."""
+    Q, Dp, off, lens = config2
+    Qn = Q[:4].contiguous()
+    n_docs = lens.shape[0]
+    s, a = M.maxsim_forward_ragged(Qn, Dp, off, want_argmax=True)
+    s_plain = M.maxsim_forward_ragged(Qn, Dp, off)
+    torch.cuda.synchronize()
+    a_np = a.cpu().numpy()
+    assert a_np.min() >= 0 and bool((a_np < lens[None, :, None]).all())
+    assert float((s - s_plain).abs().max()) <= 2e-3 * 32      # with and without argmax: the same scores within the bar
+    pick = sample_docs(n_docs, lens, k=60, seed=44)
+    off_c = off.cpu().numpy().astype(np.int64)
+    rows = np.concatenate([np.arange(off_c[d], off_c[d + 1]) for d in pick])
+    sub_off = np.concatenate([[0], np.cumsum(lens[pick])]).astype(np.int32)
+    Dsub = Dp[torch.from_numpy(rows).to(DEV)]
+    ref, ra, rm = O.forward(W.to_raw_numpy(Qn), W.to_raw_numpy(Dsub), "f16", offsets=sub_off)
+    pick_t = torch.from_numpy(pick).to(DEV)
+    check_scores(s[:, pick_t], ref, 32, RTOL_16)
+    Dd = decode(Dsub)
+    check_argmax(a[:, pick_t], ra, rm, Qn, lambda b: Dd[sub_off[b]:sub_off[b + 1]])
+
+
 def test_config3_colpali_page_as_query_full_size():
     Q, D = W.colpali_page_as_query(device=DEV)
+    n_docs = D.shape[0]
     s = M.maxsim_forward(Q, D)
+    s_a, a = M.maxsim_forward(Q, D, want_argmax=True)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(s).all())
-    pick = sample_docs(D.shape[0], k=8, seed=3)
-    ref, _, _ = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(D[torch.from_numpy(pick).to(DEV)]), "bf16",
-                          want_argmax=False, want_margin=False)
-    check_scores(s[:, torch.from_numpy(pick).to(DEV)], ref, 1024, RTOL_16)
+    # 64 documents: first, last, drawn ones, and both sides of the borders between the runs of documents that
+    # workgroups take (a run is ceil(10000 / n) documents for n a small multiple of the CU count)
+    pick = set(int(x) for x in sample_docs(n_docs, k=24, seed=3))
+    for per_run in (10, 20, 40, 79, 157):
+        for k in (1, 3, n_docs // per_run):
+            pick |= {min(n_docs - 1, k * per_run - 1), min(n_docs - 1, k * per_run)}
+    pick = np.array(sorted(pick))[:64]
+    pick_t = torch.from_numpy(pick).to(DEV)
+    Dsub = D[pick_t]
+    ref, ra, rm = O.forward(W.to_raw_numpy(Q), W.to_raw_numpy(Dsub), "bf16")
+    check_scores(s[:, pick_t], ref, 1024, RTOL_16)
+    check_scores(s_a[:, pick_t], ref, 1024, RTOL_16)
+    Dd = decode(Dsub)
+    check_argmax(a[:, pick_t], ra, rm, Q, lambda b: Dd[b])
+    a_min, a_max = int(a.min()), int(a.max())
+    assert a_min >= 0 and a_max < 1024
     # a score is a sum of 1024 cosines of unit-norm rows
     assert float(s.abs().max()) <= 1024.0 * 1.01
 

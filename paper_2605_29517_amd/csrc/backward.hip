@@ -122,7 +122,8 @@ template <int DT> __device__ __forceinline__ void decode8(const Raw8 &r, float (
 // order; the n_part partial sums of a query token are then added in partition order by bwd_dq_combine_kernel
 // (fixed order: bitwise reproducible).  n_part = 1 writes dQ directly.
 // ---------------------------------------------------------------------------------------
-constexpr int DQ_SB = 16; // documents per index fetch: one per lane of a group of sixteen
+constexpr int DQ_SB = 16;   // documents per index fetch: one per lane of a group of sixteen
+constexpr int DQ_AHEAD = 4; // documents between the rows being gathered and the rows being read ahead in order
 
 // TPG = query tokens per group of sixteen lanes: 1, or 4 consecutive tokens of one query (l_q a multiple of 4: their
 // argmax entries are one 16-byte load and they share the weight).  With 4 the whole grid is resident at once at
@@ -204,6 +205,22 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p, float *out, in
                 o[t] = ok ? (uint32_t)(first + tt[t]) * row16 : 0xffffffffu;
             }
         };
+        // Gathering rows straight from HBM would be random 256-byte reads.  With four tokens per group the whole grid
+        // is resident and the wavefronts of a partition walk its documents side by side, so (uniform corpora) they
+        // also read the documents a few steps ahead in order, one kilobyte per wavefront and step (wavefront k of the
+        // partition the k-th kilobyte of the step's DPB documents): by the time rows of those documents are
+        // gathered, they sit in the XCD's L2.  Nothing depends on it but speed.
+        const bool ahead = TPG == 4 && !p.offsets;
+        const int64_t step_bytes = (int64_t)DPB * p.l_d * row_bytes;
+        const char *t_safe = p.D + j0 * p.l_d * row_bytes;             // a valid address of the partition
+        const char *t_lim = p.D + j1 * p.l_d * row_bytes - 16;          // last 16 bytes of the partition
+        int64_t t_at = (wave % ((int64_t)(gridDim.x / (unsigned)n_part) * 4)) * 1024 + lane * 16;
+        const char *tp = t_safe + (int64_t)DQ_AHEAD * p.l_d * row_bytes + (t_at < step_bytes - 16 ? t_at : step_bytes - 16);
+        auto touch = [&]() {
+            const char *at = (ahead && tp <= t_lim) ? tp : t_safe;
+            tp += step_bytes;
+            return *reinterpret_cast<const uint4 *>(at);
+        };
         fetch(j0);
         for (int64_t jb = j0; jb < j1; jb += DQ_SB) {
             uint32_t co[TPG];
@@ -245,9 +262,14 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p, float *out, in
             issue(std::integral_constant<int, 0>(), raw[0], gc[0]);
             static_for<0, NBATCH>([&](auto b_tag) {
                 constexpr int bi = decltype(b_tag)::value;
+                uint4 touched = make_uint4(0, 0, 0, 0);
+                if constexpr (TPG == 4)
+                    touched = touch();
                 if constexpr (bi + 1 < NBATCH)
                     issue(std::integral_constant<int, bi + 1>(), raw[(bi + 1) & 1], gc[(bi + 1) & 1]);
                 consume(raw[bi & 1], gc[bi & 1]);
+                if constexpr (TPG == 4)
+                    asm volatile("" ::"v"(touched.x), "v"(touched.y), "v"(touched.z), "v"(touched.w)); // the load is the point
             });
         }
     }
@@ -369,14 +391,15 @@ template <int DT> __device__ __forceinline__ typename RawPair<DT>::type load_raw
 // over boundv; the edges are then applied one after the other by all 64 lanes, 16 Q-row loads in flight while the
 // 16 before them are added (two register sets); the row's byte offset and the weight reach the instructions
 // through scalar registers.  The running row lives in two fixed registers and moves to / from its slot (register
-// index from a scalar) at the edges where a ballot says the row changes, so the per-edge work is a compare, two
-// lane reads, a load and two fused multiply-adds, and the chain holds no memory operation besides the loads.
+// index from a scalar) at the edges where a ballot says the row changes, so the per-edge work is a compare, one
+// lane read, a load, a quarter of an LDS read and two fused multiply-adds, and the chain holds no global memory
+// operation besides the loads.
 // Edges past the last one (the rest of the last batch) carry weight 0; their Q rows are rows of other lists, or,
 // past the end of the edge array, whatever offset the lookup makes of it: the buffer descriptor turns a read
 // outside Q into zeros.
 template <int DT, int NROWS, typename Lookup>
 __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int lane, uint32_t lane_off, int k_lo,
-                                          int k_hi, int boundv, Lookup lookup, typename RowVec<NROWS>::type &rx,
+                                          int k_hi, int boundv, float *gstage, Lookup lookup, typename RowVec<NROWS>::type &rx,
                                           typename RowVec<NROWS>::type &ry)
 {
     typedef typename RawPair<DT>::type raw_t;
@@ -402,16 +425,22 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
             dst[u] = load_raw_pair<DT>(rsrc, lane_off, (uint32_t)__builtin_amdgcn_readlane((int)offv, e0 + u));
     };
     uint32_t o_cur, o_nxt;
-    float g_cur, g_nxt;
+    float g_nxt;
     int sv_cur, sv_nxt;
     raw_t xb[2][DD_BATCH];
-    look(k_lo, o_cur, g_cur, sv_cur);
+    // the weights of a step's 64 edges go through this wavefront's own LDS words (two sets of 64), from where four at a
+    // time are read back into all lanes: a broadcast read instead of a lane read per edge
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    int gpar = 0;
+    look(k_lo, o_cur, g_nxt, sv_cur);
+    gstage[lane] = g_nxt;
     issue(xb[0], o_cur, 0);
     int s_now = __builtin_amdgcn_readlane(sv_cur, 0);
     int s_carry = s_now;
     float ax = rx[s_now], ay = ry[s_now];
     // One batch of 16 edges: the lane reads use compile-time lanes; edges past k_hi have weight 0.
     auto consume = [&](const raw_t(&src)[DD_BATCH], int e0, uint64_t &bmask, int &next_b) {
+        f32x4 g4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int u = 0; u < DD_BATCH; ++u) {
             const int e = e0 + u;
@@ -425,7 +454,9 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
                 bmask &= bmask - 1;
                 next_b = bmask ? (int)__builtin_ctzll(bmask) : 64;
             }
-            const float gg = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(g_cur), e));
+            if ((u & 3) == 0)
+                g4 = *reinterpret_cast<const f32x4 *>(gstage + gpar * 64 + e);
+            const float gg = g4[u & 3];
             float x0, x1;
             decode_pair<DT>(src[u], x0, x1);
             ax = fmaf(gg, x0, ax);
@@ -436,6 +467,7 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
     // rejoined) once the batch that holds the last edge has been added, so the only loads wasted are one batch.
     for (int k0 = k_lo;; k0 += 64) {
         look(k0 + 64, o_nxt, g_nxt, sv_nxt);
+        gstage[(gpar ^ 1) * 64 + lane] = g_nxt;
         int prev = __shfl_up(sv_cur, 1);
         prev = lane == 0 ? s_carry : prev;
         uint64_t bmask = __ballot(sv_cur != prev); // edges that begin another row's list
@@ -458,7 +490,7 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
             break;
         s_carry = __builtin_amdgcn_readlane(sv_cur, 63);
         o_cur = o_nxt;
-        g_cur = g_nxt;
+        gpar ^= 1;
         sv_cur = sv_nxt;
     }
     rx[s_now] = ax;
@@ -466,7 +498,8 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
 }
 
 template <int DT, int RPW, int W>
-__global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr off, Magic lq_magic, int n_blocks)
+__global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr off, Magic lq_magic, Magic ld_magic, int dq64,
+                                                        int di64, int n_blocks)
 {
     constexpr int R = W * RPW;          // rows of the block
     constexpr int WBITS = W == 16 ? 4 : 3;
@@ -480,6 +513,7 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
     __shared__ uint16_t list[DW_COL];          // entry numbers by key, in entry order
     __shared__ int hist[W][R];          // per filtering wavefront: entries per key, then write cursors
     __shared__ int start[R + 1];               // list of key k: list[start[k] .. start[k + 1])
+    __shared__ __attribute__((aligned(16))) float gstage[W][128]; // per wavefront: the weights of the edges being walked
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -504,9 +538,9 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
         j_last = lower_bound_offsets(p.offsets, p.b, row_end) - 1;
         j_first = j_first < 0 ? 0 : j_first; // only offsets that break their contract get here
         j_last = j_last > p.b - 1 ? p.b - 1 : j_last;
-    } else {
-        j_first = row0 / p.l_d;
-        j_last = (row_end - 1) / p.l_d;
+    } else { // rows are below 2^31 (checked by the caller)
+        j_first = magic_div((uint32_t)row0, ld_magic);
+        j_last = magic_div((uint32_t)(row_end - 1), ld_magic);
     }
 
     // the gradient rows of this wavefront (slot s = row row0 + W * s + w), two columns per lane
@@ -518,8 +552,8 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
     }
 
     const int n_entries = p.n_q * p.l_q; // < 2^31 (checked by the caller)
-    // argmax entries 64 apart in a document's column: dq64 queries and di64 tokens (one more query if the token wraps)
-    const int dq64 = 64 / p.l_q, di64 = 64 % p.l_q;
+    // argmax entries 64 apart in a document's column: dq64 = 64 / l_q queries and di64 = 64 % l_q tokens (one more query
+    // if the token wraps)
     const int64_t inc_plain = (int64_t)dq64 * p.b * p.l_q + di64;
     const int64_t inc_wrap = inc_plain + (int64_t)p.b * p.l_q - p.l_q;
     for (int64_t j = j_first; j <= j_last; ++j) {
@@ -559,7 +593,13 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                 int i = (int)((n < (uint32_t)n_entries ? n : 0u) - q0 * (uint32_t)p.l_q);
                 const int32_t *ptr = p.A + ((int64_t)q0 * p.b + j) * p.l_q + i;
                 int t[PER];
-                if (cn == DW_COL) {
+                if (cn == DW_COL && di64 == 0) { // l_q divides 64: the same increment every time
+#pragma unroll
+                    for (int k = 0; k < PER; ++k) {
+                        t[k] = *ptr;
+                        ptr += inc_plain;
+                    }
+                } else if (cn == DW_COL) {
 #pragma unroll
                     for (int k = 0; k < PER; ++k) {
                         t[k] = *ptr;
@@ -668,7 +708,7 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                     const uint32_t q = magic_div(n, lq_magic);
                     gv = valid ? p.g[(int64_t)q * p.b + j] : 0.0f;
                 };
-                walk_rows<DT, RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, startv, lookup, rx, ry);
+                walk_rows<DT, RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, startv, &gstage[w][0], lookup, rx, ry);
             }
         }
     }
@@ -738,7 +778,7 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, h
         const int64_t n_blocks = (p.total_tokens + W * RPW - 1) / (W * RPW);
         const int64_t grid = (n_blocks + 7) / 8 * 8;
         hipLaunchKernelGGL((bwd_dd_kernel<DT, RPW, W>), dim3((unsigned)grid, slabs), dim3(W * 64), 0, stream, p, p.offsets,
-                           lq_magic, (int)n_blocks);
+                           lq_magic, magic_u31((uint32_t)(p.l_d > 0 ? p.l_d : 1)), 64 / p.l_q, 64 % p.l_q, (int)n_blocks);
     };
     if (p.total_tokens / (DD_WAVES * 16) >= want)
         go(std::integral_constant<int, 16>(), std::integral_constant<int, 8>());
@@ -982,6 +1022,7 @@ __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdPara
                                                         const int32_t *__restrict__ col_idx, Magic bl_magic, Magic lq_magic)
 {
     constexpr int EB = Elem<DT>::BYTES;
+    __shared__ __attribute__((aligned(16))) float gstage[CSR_APPLY_WAVES][128]; // per wavefront: the weights of the edges being walked
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const int64_t r0 = ((int64_t)blockIdx.x * CSR_APPLY_WAVES + w) * CSR_RPW;
@@ -1018,7 +1059,7 @@ __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdPara
         n = ok ? i * (uint32_t)p.l_q + s_ : 0u;
         gv = ok ? p.g[(int64_t)i * p.b + jj] : 0.0f;
     };
-    walk_rows<DT, CSR_RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, rp, lookup, rx, ry);
+    walk_rows<DT, CSR_RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, rp, &gstage[w][0], lookup, rx, ry);
     if (col_ok) {
 #pragma unroll
         for (int s = 0; s < CSR_RPW; ++s)

@@ -127,11 +127,26 @@ def main():
     def stats():
         return dict(last_stats)
 
-    def clock_under_load(fn, seconds=1.5):
-        """Shader clock (MHz) that rocm-smi reports while `fn` is launched back to back for about `seconds`
-        (a child process reads it; None if rocm-smi is missing or prints something else)."""
+    def read_shader_clock():
+        """Current shader clock in MHz from the driver's sysfs table (the line rocm-smi marks as active), or None.
+        Read from a file: no child process is started from this GPU-initialised process."""
+        import glob
         import re
-        import subprocess
+        best = None
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+            try:
+                for line in open(path):
+                    if line.rstrip().endswith("*"):
+                        m = re.search(r"(\d+)\s*mhz", line, re.I)
+                        if m:
+                            best = max(best or 0, int(m.group(1)))
+            except OSError:
+                pass
+        return best
+
+    def clock_under_load(fn, seconds=1.0):
+        """Shader clock (MHz) read while `fn` is launched back to back for about `seconds` (None if the driver does
+        not expose it)."""
         fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -141,13 +156,10 @@ def main():
         n = max(4, min(20000, int(seconds / per)))
         for _ in range(n):
             fn()
-        try:
-            txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
-        except Exception:
-            txt = ""
+        time.sleep(min(0.5 * seconds, 0.5 * n * per))    # the queue is still draining when the clock is read
+        mhz = read_shader_clock()
         torch.cuda.synchronize()
-        m = re.search(r"sclk clock level:?\s*\d*:?\s*\(?(\d+)\s*Mhz", txt, re.I)
-        return int(m.group(1)) if m else None
+        return mhz
 
     def roof(bound, work, avg_ms, peak, unit, key):
         achieved = work / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)

@@ -96,18 +96,24 @@ def main():
         """W untimed steps, then K timed steps between synchronisations; one event pair per launch.
         cold=True: 512 MB are written before every timed launch (outside its event pair) so that a working set
         small enough for the L2s and the 256 MB Infinity Cache is read from HBM, as in the paper's method;
-        the returned wall time is then the mean of the event times.
+        the returned wall time is then the mean of the event times.  cold="read": the 512 MB are read instead, which
+        also empties the caches of the operands but leaves no modified lines behind whose write-back the timed kernel
+        would have to wait for.
         Returns (ms per step, average, median, minimum) of the event times; the last call's full statistics
         (with the interquartile range) are kept in `last_stats`."""
         if cold and not flush_buf:
             flush_buf.append(torch.empty(512 << 20, dtype=torch.uint8, device=dev))
+            flush_buf[0].fill_(1)
+            flush_buf.append(torch.zeros(1, dtype=torch.float32, device=dev))
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         t0 = time.perf_counter()
         for a, b in ev:
-            if cold:
+            if cold == "read":
+                P.maxsim_probe_read(flush_buf[0], flush_buf[1])
+            elif cold:
                 flush_buf[0].fill_(1)
             a.record()
             fn()
@@ -119,7 +125,8 @@ def main():
         q1, q3 = k[len(k) // 4], k[(3 * len(k)) // 4]
         last_stats.clear()
         last_stats.update({"avg": round(avg, 4), "median": round(k[len(k) // 2], 4), "min": round(k[0], 4),
-                           "iqr": round(q3 - q1, 4), "timed": steps, "warmup": warmup, "cold": bool(cold)})
+                           "iqr": round(q3 - q1, 4), "timed": steps, "warmup": warmup,
+                           "cold": "read-flush" if cold == "read" else bool(cold)})
         return (avg if cold else wall_ms), avg, k[len(k) // 2], k[0]
 
     last_stats = {}
@@ -407,6 +414,7 @@ def main():
                          "max_rel_err_scores_gpu": rel4, "max_err_dQ_over_max": eq, "max_err_dD_over_max": ed,
                          "ok": bool(rel4 <= 2e-3 and eq <= 1e-4 and ed <= 1e-4)}
         wbw, _, _, _ = time_launches(lambda: M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4), 50, 5)
+        wbr, _, _, _ = time_launches(lambda: M.maxsim_backward(Q4, D4, a4, g4, dQ=dQ4, dD=dD4), 50, 5, cold="read")
         # the same backward with dD through the explicit CSR (Alg. 2), and the CSR build alone
         rp4 = torch.empty(n4 * ld4 + 1, dtype=torch.int32, device=dev)
         ci4 = torch.empty(n4 * n4 * lq4, dtype=torch.int32, device=dev)
@@ -429,10 +437,15 @@ def main():
         wsw, _, _, _ = time_launches(step4, 50, 5)
         extra.append({"leg": "c4", "workload": "configs[3]: contrastive step, 256 queries (L_q=32) x 256 docs (L_d=1024), fp16, "
                                                "forward+argmax, CE tau=0.02, backward dQ/dD",
-                      "timing": "cold: 512 MB written before every timed launch; *_warm_ms: back to back, operands in cache",
+                      "timing": "cold: 512 MB written before every timed launch; *_cold_read_flush_ms: 512 MB read instead "
+                                "(operands evicted, no modified lines left to write back); *_warm_ms: back to back, operands in cache",
                       "forward_kernel_ms": c4_fwd_stats, "backward_kernel_ms": c4_bwd_stats, "cpu_oracle": c4_oracle,
                       "step_ms": round(ws, 4), "forward_ms": round(wf, 4), "ce_ms": round(wc, 4), "backward_ms": round(wb, 4),
-                      "step_warm_ms": round(wsw, 4), "backward_warm_ms": round(wbw, 4),
+                      "step_warm_ms": round(wsw, 4), "backward_warm_ms": round(wbw, 4), "backward_cold_read_flush_ms": round(wbr, 4),
+                      # every edge gathers one row of D (dQ) and one row of Q (dD) through the L2: the traffic that
+                      # bounds this formulation, next to the `l2_gather_*` ceilings
+                      "backward_gathered_bytes": 2 * n4 * n4 * lq4 * D_MODEL * 2,
+                      "backward_gather_TB_per_s": round(2 * n4 * n4 * lq4 * D_MODEL * 2 / (ab * 1e-3) / 1e12, 2),
                       "backward_csr_ms": round(wcsr, 4), "csr_build_ms": round(wcb, 4),
                       "backward_skewed_argmax_ms": round(wsk, 4),
                       "pairs_per_s": round(n4 * n4 / (ws * 1e-3), 1),
@@ -516,6 +529,19 @@ def main():
         w, a, m, mn = time_launches(lambda: P.maxsim_probe_copy(big[:1 << 28], dst), 10, 3)
         ceil["hbm_copy_1GiB"] = {"ms": round(a, 3), "GB_per_s_read_plus_write": round(2 * dst.numel() * 4 / (a * 1e-3) / 1e9, 1),
                                  "bytes_read": dst.numel() * 4, "bytes_written": dst.numel() * 4}
+        # random gathers of whole 256-byte rows (the backward's access pattern: a row of D or Q per edge) from a table
+        # that fits every XCD's L2 (2 MiB, the size of config 4's Q), one as large as config 4's D (64 MiB) and one
+        # far beyond the caches (1 GiB): one row per load instruction (dD's walk) and four (dQ's gather)
+        for label, nbytes in (("2MiB", 2 << 20), ("64MiB", 64 << 20), ("1GiB", 1 << 30)):
+            table = big[:nbytes // 4]
+            for kind, name in ((0, "row_per_load"), (1, "four_rows_per_load")):
+                iters = 64 if kind == 0 else 32
+                gathered = [0]
+
+                def gather():
+                    gathered[0] = P.maxsim_probe_gather(kind, table, iters, sink)
+                w, a, m, mn = time_launches(gather, 10, 3)
+                ceil["l2_gather_256B_rows_%s_table_%s" % (label, name)] = {"ms": round(a, 4), "TB_per_s": round(gathered[0] / (a * 1e-3) / 1e12, 2)}
         out["ceilings"] = ceil
         del big, dst
 

@@ -1,7 +1,7 @@
 /*
  * maxsim_probe.h -- diagnostics for the benchmark of the fused MaxSim library (libmaxsim_probe.so).
  *
- * Not part of the operator and not ABI-stable: three kernels that show what an MI355X sustains, for roofline
+ * Not part of the operator and not ABI-stable: four kernels that show what an MI355X sustains, for roofline
  * context beside the library's own kernels.  Conventions (device pointers, `stream`, return codes) as in maxsim.h.
  *
  * maxsim_probe_mfma: a register-only loop of 32x32 MFMAs with four independent accumulators,
@@ -12,6 +12,10 @@
  * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them (a reference read rate).
  * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
  *   traffic for calibrating profiler byte counters.
+ * maxsim_probe_gather: every wavefront (sixteen per CU) gathers iters x 16 pseudo-random whole rows of 256 bytes from
+ *   `table` (`rows` rows, a power of two; rows * 256 bytes of device memory), sixteen loads in flight.  kind 0 = one row
+ *   per load instruction (a dword per lane), kind 1 = four rows per load instruction (sixteen lanes x 16 bytes per
+ *   row).  Returns the number of rows the launch gathers (> 0), or a negative error code.
  * `sink` is 4 bytes of device memory that is (practically) never written.
  */
 #ifndef MAXSIM_PROBE_H
@@ -28,6 +32,7 @@ extern "C" {
 int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream);
 int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream);
 int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+int64_t maxsim_probe_gather(int kind, const void *table, int64_t rows, int iters, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -123,7 +123,6 @@ template <int DT> __device__ __forceinline__ void decode8(const Raw8 &r, float (
 // (fixed order: bitwise reproducible).  n_part = 1 writes dQ directly.
 // ---------------------------------------------------------------------------------------
 constexpr int DQ_SB = 16;   // documents per index fetch: one per lane of a group of sixteen
-constexpr int DQ_AHEAD = 4; // documents between the rows being gathered and the rows being read ahead in order
 
 // TPG = query tokens per group of sixteen lanes: 1, or 4 consecutive tokens of one query (l_q a multiple of 4: their
 // argmax entries are one 16-byte load and they share the weight).  With 4 the whole grid is resident at once at
@@ -205,22 +204,6 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p, float *out, in
                 o[t] = ok ? (uint32_t)(first + tt[t]) * row16 : 0xffffffffu;
             }
         };
-        // Gathering rows straight from HBM would be random 256-byte reads.  With four tokens per group the whole grid
-        // is resident and the wavefronts of a partition walk its documents side by side, so (uniform corpora) they
-        // also read the documents a few steps ahead in order, one kilobyte per wavefront and step (wavefront k of the
-        // partition the k-th kilobyte of the step's DPB documents): by the time rows of those documents are
-        // gathered, they sit in the XCD's L2.  Nothing depends on it but speed.
-        const bool ahead = TPG == 4 && !p.offsets;
-        const int64_t step_bytes = (int64_t)DPB * p.l_d * row_bytes;
-        const char *t_safe = p.D + j0 * p.l_d * row_bytes;             // a valid address of the partition
-        const char *t_lim = p.D + j1 * p.l_d * row_bytes - 16;          // last 16 bytes of the partition
-        int64_t t_at = (wave % ((int64_t)(gridDim.x / (unsigned)n_part) * 4)) * 1024 + lane * 16;
-        const char *tp = t_safe + (int64_t)DQ_AHEAD * p.l_d * row_bytes + (t_at < step_bytes - 16 ? t_at : step_bytes - 16);
-        auto touch = [&]() {
-            const char *at = (ahead && tp <= t_lim) ? tp : t_safe;
-            tp += step_bytes;
-            return *reinterpret_cast<const uint4 *>(at);
-        };
         fetch(j0);
         for (int64_t jb = j0; jb < j1; jb += DQ_SB) {
             uint32_t co[TPG];
@@ -262,14 +245,9 @@ __global__ void __launch_bounds__(256) bwd_dq_kernel(BwdParams p, float *out, in
             issue(std::integral_constant<int, 0>(), raw[0], gc[0]);
             static_for<0, NBATCH>([&](auto b_tag) {
                 constexpr int bi = decltype(b_tag)::value;
-                uint4 touched = make_uint4(0, 0, 0, 0);
-                if constexpr (TPG == 4)
-                    touched = touch();
                 if constexpr (bi + 1 < NBATCH)
                     issue(std::integral_constant<int, bi + 1>(), raw[(bi + 1) & 1], gc[(bi + 1) & 1]);
                 consume(raw[bi & 1], gc[bi & 1]);
-                if constexpr (TPG == 4)
-                    asm volatile("" ::"v"(touched.x), "v"(touched.y), "v"(touched.z), "v"(touched.w)); // the load is the point
             });
         }
     }
@@ -308,25 +286,25 @@ __global__ void __launch_bounds__(256) bwd_dq_combine_kernel(const float4 *part,
 // wavefront w owns the rows row0 + 8 * s + w (s = 0 .. RPW-1; neighbouring rows, often hot together, go to
 // different wavefronts).  For every document with rows in the block and every round of DW_COL entries of that
 // document's argmax column:
-//   (1) filter: each wavefront reads a contiguous eighth of the round, keeps the entries that land in the block,
-//       compacted by ballot in entry order, and counts them per row into its own histogram (LDS);
+//   (1) filter: each wavefront reads a contiguous eighth of the round, keeps the entries that land in the block
+//       (one subtraction and one unsigned compare per entry), compacted by ballot in entry order, and counts them
+//       per row into its own histogram (LDS);
 //   (2) scan: the histograms become list starts per row and a write cursor per (row, filtering wavefront);
 //   (3) place: each wavefront ranks its kept entries, 64 at a time, among equal rows by log2(R) ballots and
 //       writes the entry numbers to the row lists -- a stable counting sort, so a row's list is in entry order and
 //       the lists of a wavefront's rows are contiguous;
 //   (4) walk: every wavefront walks its contiguous range of the sorted entries, ALL 64 lanes on one edge at a
 //       time (two columns per lane): per 64 edges one vector step looks up (Q row, weight), then the edges are
-//       applied in order with 16 Q-row loads in flight, addresses and weights passed through scalar registers;
-//       the running row lives in two fixed registers and is written when the walk crosses into the next row's
-//       list (empty rows get zeros).
+//       applied in order with 8 to 16 Q-row loads in flight; the wavefront's rows stay in registers (two per row and
+//       lane, selected by a scalar index) over all the documents and rounds of the block and are written once, at
+//       the end (rows without edges as zeros).
 // Every row has one owner and its edges are added in entry order with one fused multiply-add each, starting
 // from zero: the same bits as the explicit CSR walk, on every run.  No atomics decide anything, no zero-fill
-// pass.  Columns beyond 128 are further slabs (blockIdx.y) that repeat the integer work.  If a document has more
-// than DW_COL entries, later rounds continue from the value the earlier ones wrote.
+// pass.  Columns beyond 128 are further slabs (blockIdx.y) that repeat the integer work.
 // ---------------------------------------------------------------------------------------
 constexpr int DD_WAVES = 8;
 constexpr int DW_COL = 8192;              // entries per round: an entry's number within the round fits 16 bits
-constexpr int DD_BATCH = 16;              // Q rows in flight while edges are applied
+constexpr int DD_BATCH = 8;                // Q rows per batch of loads (two batches in flight while edges are applied)
 
 // two consecutive elements of a row as loaded (decoded when they are used, so that an edge in flight holds one
 // register for 16-bit rows)
@@ -388,9 +366,10 @@ template <int DT> __device__ __forceinline__ typename RawPair<DT>::type load_raw
 // NROWS consecutive lists; lane s of `boundv` holds where the list of row slot s starts (s = 0 .. NROWS, the last
 // one = k_hi).  rx[s], ry[s] are the lane's two columns of row slot s.  Per 64 edges (one per lane) a vector step
 // looks up the Q row and the weight (`lookup(k, valid, n, gv)`) and finds the edge's row slot by a binary search
-// over boundv; the edges are then applied one after the other by all 64 lanes, 16 Q-row loads in flight while the
-// 16 before them are added (two register sets); the row's byte offset and the weight reach the instructions
-// through scalar registers.  The running row lives in two fixed registers and moves to / from its slot (register
+// over boundv; the edges are then applied one after the other by all 64 lanes, 8 Q-row loads in flight while the
+// 8 before them are added (two register sets; batches of 16 cost 15 more registers and, at seven wavefronts per SIMD
+// in csr_apply_kernel, were 20 % slower); the row's byte offset reaches the load through a scalar register, the
+// weights come four at a time from the wavefront's LDS words.  The running row lives in two fixed registers and moves to / from its slot (register
 // index from a scalar) at the edges where a ballot says the row changes, so the per-edge work is a compare, one
 // lane read, a load, a quarter of an LDS read and two fused multiply-adds, and the chain holds no global memory
 // operation besides the loads.
@@ -403,7 +382,8 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
                                           typename RowVec<NROWS>::type &ry)
 {
     typedef typename RawPair<DT>::type raw_t;
-    static_assert(DD_BATCH == 16, "four batches per vector step");
+    static_assert(DD_BATCH == 8, "eight batches per vector step");
+    constexpr int NB = 64 / DD_BATCH;
     if (k_lo >= k_hi)
         return;
     auto look = [&](int k0, uint32_t &off, float &gv, int &sv) {
@@ -438,7 +418,7 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
     int s_now = __builtin_amdgcn_readlane(sv_cur, 0);
     int s_carry = s_now;
     float ax = rx[s_now], ay = ry[s_now];
-    // One batch of 16 edges: the lane reads use compile-time lanes; edges past k_hi have weight 0.
+    // One batch of edges: the lane reads use compile-time lanes; edges past k_hi have weight 0.
     auto consume = [&](const raw_t(&src)[DD_BATCH], int e0, uint64_t &bmask, int &next_b) {
         f32x4 g4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -472,22 +452,20 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
         prev = lane == 0 ? s_carry : prev;
         uint64_t bmask = __ballot(sv_cur != prev); // edges that begin another row's list
         int next_b = bmask ? (int)__builtin_ctzll(bmask) : 64;
-        issue(xb[1], o_cur, DD_BATCH);
-        consume(xb[0], 0, bmask, next_b);
-        if (k0 + DD_BATCH >= k_hi)
-            break;
-        issue(xb[0], o_cur, 2 * DD_BATCH);
-        consume(xb[1], DD_BATCH, bmask, next_b);
-        if (k0 + 2 * DD_BATCH >= k_hi)
-            break;
-        issue(xb[1], o_cur, 3 * DD_BATCH);
-        consume(xb[0], 2 * DD_BATCH, bmask, next_b);
-        if (k0 + 3 * DD_BATCH >= k_hi)
-            break;
-        issue(xb[0], o_nxt, 0);
-        consume(xb[1], 3 * DD_BATCH, bmask, next_b);
-        if (k0 + 4 * DD_BATCH >= k_hi)
-            break;
+#define WALK_STEP(bi)                                                                                                  \
+    issue(xb[((bi) + 1) & 1], (bi) + 1 < NB ? o_cur : o_nxt, (((bi) + 1) % NB) * DD_BATCH);                           \
+    consume(xb[(bi)&1], (bi)*DD_BATCH, bmask, next_b);                                                                \
+    if (k0 + ((bi) + 1) * DD_BATCH >= k_hi)                                                                           \
+        break;
+        WALK_STEP(0)
+        WALK_STEP(1)
+        WALK_STEP(2)
+        WALK_STEP(3)
+        WALK_STEP(4)
+        WALK_STEP(5)
+        WALK_STEP(6)
+        WALK_STEP(7)
+#undef WALK_STEP
         s_carry = __builtin_amdgcn_readlane(sv_cur, 63);
         o_cur = o_nxt;
         gpar ^= 1;
@@ -509,11 +487,13 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
     static_assert(RPW == 16 || RPW == 8 || RPW == 4, "rows per wavefront");
     static_assert(W == 8 || W == 16, "wavefronts per workgroup");
     constexpr int EB = Elem<DT>::BYTES;
-    __shared__ uint32_t seg[W][SEG]; // per filtering wavefront: kept entries, (number in round) | key << 16
-    __shared__ uint16_t list[DW_COL];          // entry numbers by key, in entry order
-    __shared__ int hist[W][R];          // per filtering wavefront: entries per key, then write cursors
+    // seg and hist live from the filter to the placement, list and start from the placement to the end of the walk;
+    // the weights staged during the walk reuse the first words of the wavefront's own seg row (dead by then).
+    static_assert(SEG >= 128, "a wavefront's staged weights fit in its seg row");
+    __shared__ __attribute__((aligned(16))) uint32_t seg[W][SEG]; // per filtering wavefront: kept entries, (number in round) | row << 16
+    __shared__ uint16_t list[DW_COL];          // entry numbers by key (= owner wavefront * RPW + slot), in entry order
+    __shared__ int hist[W][R];          // per filtering wavefront: entries per block row, then write cursors
     __shared__ int start[R + 1];               // list of key k: list[start[k] .. start[k + 1])
-    __shared__ __attribute__((aligned(16))) float gstage[W][128]; // per wavefront: the weights of the edges being walked
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -587,7 +567,9 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                 // (1) entry n = c0 + x -> (q, i); all loads are issued before the first result is used.  The entry 64
                 // further on is dq queries and di tokens ahead: its address is one of two increments away.
                 constexpr int PER = SEG / 64;
-                const int x = w * SEG + lane;
+                int x = w * SEG + lane;
+                // (opaque to the optimiser: it would otherwise keep x + 64 k for all k in registers across the rounds)
+                asm volatile("" : "+v"(x));
                 const uint32_t n = (uint32_t)c0 + (uint32_t)x; // entries past the end of the column are masked below
                 const uint32_t q0 = magic_div(n < (uint32_t)n_entries ? n : 0u, lq_magic);
                 int i = (int)((n < (uint32_t)n_entries ? n : 0u) - q0 * (uint32_t)p.l_q);
@@ -621,32 +603,39 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                         ptr += wrap ? inc_wrap : inc_plain;
                     }
                 }
+                // An entry lands in the block iff y = t - (t_base + lo_rel), taken modulo 2^32, is below the number of
+                // the document's rows in the block (that also rules out t < 0, t >= len and the -1 of masked entries);
+                // y counts rows from the document's first row in the block.
+                const uint32_t y_base = (uint32_t)t_base + (uint32_t)lo_rel;
+                const uint32_t n_rows = (uint32_t)(hi_rel - lo_rel);
+                int *const hist_w = &hist[w][lo_rel];
 #pragma unroll
                 for (int k = 0; k < PER; ++k) {
-                    const int rel = t[k] - t_base;
-                    const bool in = t[k] >= 0 && t[k] < len && rel >= lo_rel && rel < hi_rel;
+                    const uint32_t y = (uint32_t)t[k] - y_base;
+                    const bool in = y < n_rows;
                     const unsigned long long mask = __ballot(in);
                     const int before =
                         __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
                     if (in) {
-                        const int key = (rel & (W - 1)) * RPW + (rel >> WBITS); // the owner's rows are consecutive keys
-                        seg[w][kept + before] = (uint32_t)(x + k * 64) | ((uint32_t)key << 16);
-                        atomicAdd(&hist[w][key], 1);
+                        seg[w][kept + before] = (uint32_t)(x | (k * 64)) | (y << 16);
+                        atomicAdd(hist_w + y, 1);
                     }
                     kept += __builtin_popcountll(mask);
                 }
             }
             __syncthreads();
             if (w == 0) {
-                // (2) keys lane, lane + 64, ...: list starts, then each filtering wavefront's cursor within the list
+                // (2) keys lane, lane + 64, ... (key = owner wavefront * RPW + slot, i.e. block row slot * W + owner): list
+                // starts in key order, then each filtering wavefront's cursor within the list; hist is indexed by block row
                 int tot[KPL], cur[KPL];
 #pragma unroll
                 for (int u = 0; u < KPL; ++u) {
                     const int r = lane + 64 * u;
+                    const int rel = (r & (RPW - 1)) * W + r / RPW;
                     tot[u] = 0;
                     if (r < R)
                         for (int sw = 0; sw < W; ++sw)
-                            tot[u] += hist[sw][r];
+                            tot[u] += hist[sw][rel];
                 }
                 int before = 0;
 #pragma unroll
@@ -658,12 +647,13 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
 #pragma unroll
                 for (int u = 0; u < KPL; ++u) {
                     const int r = lane + 64 * u;
+                    const int rel = (r & (RPW - 1)) * W + r / RPW;
                     if (r < R) {
                         start[r] = cur[u];
                         int run = cur[u];
                         for (int sw = 0; sw < W; ++sw) {
-                            int cnt = hist[sw][r];
-                            hist[sw][r] = run;
+                            int cnt = hist[sw][rel];
+                            hist[sw][rel] = run;
                             run += cnt;
                         }
                         if (r == R - 1)
@@ -675,11 +665,11 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
             {
                 // (3) stable placement: kept entries in order, equal keys ranked by lane
                 typedef volatile __attribute__((address_space(3))) int *lds_int; // LDS, not a generic pointer
-                lds_int cursor = (lds_int)&hist[w][0];
+                lds_int cursor = (lds_int)&hist[w][lo_rel];
                 for (int e0 = 0; e0 < kept; e0 += 64) {
                     const bool valid = e0 + lane < kept;
                     const uint32_t ent = valid ? seg[w][e0 + lane] : 0u;
-                    const int key = (int)(ent >> 16);
+                    const int key = (int)(ent >> 16); // the row, counted from the document's first row in the block
                     uint64_t same = __ballot(valid);
 #pragma unroll
                     for (int bit = 0; bit < RBITS; ++bit) {
@@ -708,7 +698,7 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                     const uint32_t q = magic_div(n, lq_magic);
                     gv = valid ? p.g[(int64_t)q * p.b + j] : 0.0f;
                 };
-                walk_rows<DT, RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, startv, &gstage[w][0], lookup, rx, ry);
+                walk_rows<DT, RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, startv, reinterpret_cast<float *>(&seg[w][0]), lookup, rx, ry);
             }
         }
     }

@@ -4,6 +4,8 @@
 //                part run at the clocks it holds under load; zeros show the unthrottled rate)
 //   probe_read   pure streaming read of a buffer
 //   probe_copy   plain copy of known size (calibrates the HBM byte counters of the profiler)
+//   probe_gather random gathers of whole 256-byte rows from a table (what the caches deliver to the access
+//                pattern of the backward: a row per edge)
 #include "common.h"
 
 namespace maxsim {
@@ -78,6 +80,50 @@ __global__ void __launch_bounds__(256) probe_copy_kernel(const uint4 *src, uint4
         dst[i] = src[i];
 }
 
+// Every wavefront gathers iters x 16 pseudo-random 256-byte rows of a table of `rows` rows (a power of two), sixteen
+// loads in flight.  KIND 0: one row per load instruction (a dword per lane), KIND 1: four rows per load instruction
+// (sixteen lanes x 16 bytes per row).
+template <int KIND>
+__global__ void __launch_bounds__(256) probe_gather_kernel(const char *table, uint32_t rows, int iters, float *sink)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane((blockIdx.x * 256 + threadIdx.x) >> 6);
+    const uint32_t seed = KIND == 0 ? wave : wave * 4 + (lane >> 4);
+    const uint32_t lane_off = KIND == 0 ? lane * 4 : (lane & 15) * 16;
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        uint32_t v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            uint32_t h = (seed * 0x9E3779B1u + (uint32_t)(it * 16 + u)) * 0x85EBCA6Bu;
+            h ^= h >> 15;
+            const char *at = table + (uint64_t)(h & (rows - 1)) * 256 + lane_off;
+            if (KIND == 0) {
+                v[u] = *reinterpret_cast<const uint32_t *>(at);
+            } else {
+                const uint4 x = *reinterpret_cast<const uint4 *>(at);
+                v[u] = x.x ^ x.y ^ x.z ^ x.w;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+            acc ^= v[u];
+    }
+    if (acc == 0x12345678u && iters < 0)
+        sink[0] = 1.0f;
+}
+
+static hipError_t probe_gather_launch(int kind, const void *table, uint32_t rows, int iters, float *sink, int num_cu,
+                                      hipStream_t stream)
+{
+    const char *t = static_cast<const char *>(table);
+    if (kind == 0)
+        hipLaunchKernelGGL((probe_gather_kernel<0>), dim3(num_cu * 4), dim3(256), 0, stream, t, rows, iters, sink);
+    else
+        hipLaunchKernelGGL((probe_gather_kernel<1>), dim3(num_cu * 4), dim3(256), 0, stream, t, rows, iters, sink);
+    return hipGetLastError();
+}
+
 static hipError_t probe_mfma_launch(int kind, const void *operands, int iters, float *sink, hipStream_t stream)
 {
     const uint4 *in = static_cast<const uint4 *>(operands);
@@ -144,6 +190,17 @@ int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream)
     return maxsim::probe_copy_launch(src, dst, bytes, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
                ? MAXSIM_OK
                : MAXSIM_ERR_LAUNCH;
+}
+
+int64_t maxsim_probe_gather(int kind, const void *table, int64_t rows, int iters, float *sink, void *stream)
+{
+    if (!table || !sink || iters < 1 || kind < 0 || kind > 1 || rows < 1 || rows > (int64_t(1) << 30) || (rows & (rows - 1)) ||
+        !probe_aligned16(table))
+        return MAXSIM_ERR_INVALID;
+    const int cus = probe_num_cu();
+    if (maxsim::probe_gather_launch(kind, table, (uint32_t)rows, iters, sink, cus, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return MAXSIM_ERR_LAUNCH;
+    return (int64_t)cus * 16 * iters * 16 * (kind == 0 ? 1 : 4); // rows gathered by this launch
 }
 
 } // extern "C"

@@ -8,7 +8,7 @@ from .binding import MaxSimError, _check, _dev, _on_device, _stream
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmaxsim_probe.so")
-SYMBOLS = ("maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy")
+SYMBOLS = ("maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy", "maxsim_probe_gather")
 PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32}
 
 _lib = None
@@ -28,6 +28,8 @@ def load():
     L.maxsim_probe_read.argtypes = [p, l, p, p]
     L.maxsim_probe_copy.restype = i
     L.maxsim_probe_copy.argtypes = [p, p, l, p]
+    L.maxsim_probe_gather.restype = l
+    L.maxsim_probe_gather.argtypes = [i, p, l, i, p, p]
     _lib = L
     return L
 
@@ -62,3 +64,19 @@ def maxsim_probe_copy(src, dst):
         rc = L.maxsim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream(src))
     _check(rc, "maxsim_probe_copy")
     return nbytes
+
+
+def maxsim_probe_gather(kind, table, iters, sink):
+    """Random gathers of 256-byte rows from `table` (the largest power-of-two number of rows it holds is used).
+    Returns the bytes gathered by the launch."""
+    L = load()
+    rows = table.numel() * table.element_size() // 256
+    if rows < 1:
+        raise MaxSimError("table must hold at least one row of 256 bytes")
+    rows = 1 << (rows.bit_length() - 1)
+    with _on_device(table, "table"):
+        n = L.maxsim_probe_gather(int(kind), _dev(table, "table"), rows, int(iters), _dev(sink, "sink", torch.float32),
+                                  _stream(table))
+    if n < 0:
+        _check(int(n), "maxsim_probe_gather")
+    return int(n) * 256

@@ -73,6 +73,34 @@ static Magic magic_u31(uint32_t divisor)
 __device__ __forceinline__ uint32_t magic_div(uint32_t n, Magic m) { return (uint32_t)(((uint64_t)n * m.mul) >> m.shift); }
 
 // f(integral_constant<int, I>) for I = BEGIN .. END-1, unrolled at compile time (for builtins that want constants)
+// Which block of rows a workgroup takes.  Workgroup ids are dealt round-robin to the 8 XCDs and, inside an XCD, (at
+// first) round-robin to its CUs.  Every XCD gets a contiguous range of blocks (the blocks of one document read the
+// same argmax column: one L2), and inside the XCD consecutive ids are a CU's share apart, so that blocks that recur
+// with a period -- the first rows of every document, which collect the most edges -- are spread over the CUs
+// instead of meeting on one (a plain numbering sent all of them to one XCD, or to every fourth CU).
+struct BlockOrder {
+    int n_blocks, per_xcd, per_cu, cus;
+    unsigned grid;
+};
+static BlockOrder block_order(int64_t n_blocks, int num_cu)
+{
+    BlockOrder o;
+    o.n_blocks = (int)n_blocks;
+    o.cus = num_cu >= 8 ? num_cu / 8 : 1;
+    o.per_xcd = (int)((n_blocks + 7) / 8);
+    o.per_cu = (o.per_xcd + o.cus - 1) / o.cus;
+    o.grid = 8u * (unsigned)o.cus * (unsigned)o.per_cu;
+    return o;
+}
+__device__ __forceinline__ int ordered_block(const BlockOrder &o, unsigned id) // -1: nothing to do
+{
+    const int i = (int)(id >> 3);
+    const int r = i / o.cus, c = i - r * o.cus;
+    const int y = c * o.per_cu + r;
+    const int blk = (int)(id & 7) * o.per_xcd + y;
+    return y < o.per_xcd && blk < o.n_blocks ? blk : -1;
+}
+
 template <int BEGIN, int END, typename F> __device__ __forceinline__ void static_for(F &&f)
 {
     if constexpr (BEGIN < END) {
@@ -365,8 +393,8 @@ template <int DT> __device__ __forceinline__ typename RawPair<DT>::type load_raw
 // The walk shared by bwd_dd_kernel and csr_apply_kernel.  Edges k_lo .. k_hi of an array sorted by row belong to
 // NROWS consecutive lists; lane s of `boundv` holds where the list of row slot s starts (s = 0 .. NROWS, the last
 // one = k_hi).  rx[s], ry[s] are the lane's two columns of row slot s.  Per 64 edges (one per lane) a vector step
-// looks up the Q row and the weight (`lookup(k, valid, n, gv)`) and finds the edge's row slot by a binary search
-// over boundv; the edges are then applied one after the other by all 64 lanes, 8 Q-row loads in flight while the
+// finds the edge's row slot by a binary search over boundv and looks up the Q row and the weight
+// (`lookup(k, valid, slot, n, gv)`; the array may be a virtual one that the lookup maps onto the real lists); the edges are then applied one after the other by all 64 lanes, 8 Q-row loads in flight while the
 // 8 before them are added (two register sets; batches of 16 cost 15 more registers and, at seven wavefronts per SIMD
 // in csr_apply_kernel, were 20 % slower); the row's byte offset reaches the load through a scalar register, the
 // weights come four at a time from the wavefront's LDS words.  The running row lives in two fixed registers and moves to / from its slot (register
@@ -388,16 +416,16 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
         return;
     auto look = [&](int k0, uint32_t &off, float &gv, int &sv) {
         const int kk = k0 + lane;
-        uint32_t n;
-        lookup(kk, kk < k_hi, n, gv);
-        off = n * row_bytes; // < 2^32 (checked by the caller)
-        int s = 0;           // the largest slot whose list starts at or before kk
+        int s = 0; // the largest slot whose list starts at or before kk
 #pragma unroll
         for (int step = NROWS / 2; step > 0; step >>= 1) {
             const int bnd = __shfl(boundv, s + step);
             s = bnd <= kk ? s + step : s;
         }
         sv = s;
+        uint32_t n;
+        lookup(kk, kk < k_hi, s, n, gv);
+        off = n * row_bytes; // < 2^32 (checked by the caller)
     };
     auto issue = [&](raw_t(&dst)[DD_BATCH], uint32_t offv, int e0) {
 #pragma unroll
@@ -477,7 +505,7 @@ __device__ __forceinline__ void walk_rows(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
 
 template <int DT, int RPW, int W>
 __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr off, Magic lq_magic, Magic ld_magic, int dq64,
-                                                        int di64, int n_blocks)
+                                                        int di64, BlockOrder order)
 {
     constexpr int R = W * RPW;          // rows of the block
     constexpr int WBITS = W == 16 ? 4 : 3;
@@ -497,11 +525,8 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // Workgroup ids are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of blocks, so that the
-    // blocks of one document, which all read that document's argmax column, share an L2.
-    const int per_xcd = (n_blocks + 7) >> 3;
-    const int blk = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (blk >= n_blocks)
+    const int blk = ordered_block(order, blockIdx.x);
+    if (blk < 0)
         return;
     const int64_t row0 = (int64_t)blk * R;
     const int64_t row_end = min(row0 + R, p.total_tokens);
@@ -693,7 +718,7 @@ __global__ void __launch_bounds__(W * 64) bwd_dd_kernel(BwdParams p, OffsetsPtr 
                 const int startv = start[w * RPW + (lane < RPW ? lane : RPW)];
                 const int k_lo = __builtin_amdgcn_readlane(startv, 0);
                 const int k_hi = __builtin_amdgcn_readlane(startv, RPW);
-                auto lookup = [&](int kk, bool valid, uint32_t &n, float &gv) {
+                auto lookup = [&](int kk, bool valid, int, uint32_t &n, float &gv) {
                     n = (uint32_t)c0 + (valid ? (uint32_t)list[kk] : 0u); // = q * l_q + i: the Q row
                     const uint32_t q = magic_div(n, lq_magic);
                     gv = valid ? p.g[(int64_t)q * p.b + j] : 0.0f;
@@ -765,10 +790,9 @@ template <int DT> static hipError_t launch_bwd(const BwdParams &p, int num_cu, h
     auto go = [&](auto rpw_tag, auto w_tag) {
         constexpr int RPW = decltype(rpw_tag)::value;
         constexpr int W = decltype(w_tag)::value;
-        const int64_t n_blocks = (p.total_tokens + W * RPW - 1) / (W * RPW);
-        const int64_t grid = (n_blocks + 7) / 8 * 8;
-        hipLaunchKernelGGL((bwd_dd_kernel<DT, RPW, W>), dim3((unsigned)grid, slabs), dim3(W * 64), 0, stream, p, p.offsets,
-                           lq_magic, magic_u31((uint32_t)(p.l_d > 0 ? p.l_d : 1)), 64 / p.l_q, 64 % p.l_q, (int)n_blocks);
+        const BlockOrder order = block_order((p.total_tokens + W * RPW - 1) / (W * RPW), num_cu);
+        hipLaunchKernelGGL((bwd_dd_kernel<DT, RPW, W>), dim3(order.grid, slabs), dim3(W * 64), 0, stream, p, p.offsets,
+                           lq_magic, magic_u31((uint32_t)(p.l_d > 0 ? p.l_d : 1)), 64 / p.l_q, 64 % p.l_q, order);
     };
     if (p.total_tokens / (DD_WAVES * 16) >= want)
         go(std::integral_constant<int, 16>(), std::integral_constant<int, 8>());
@@ -1000,37 +1024,46 @@ __global__ void __launch_bounds__(CSR_WAVES * 64) csr_place_kernel(CsrParams p)
 }
 
 // dD[r, :] = sum over the edges of row r, in list order, of g[i, j] * Q[i, s, :]: the walk of bwd_dd_kernel over the
-// CSR in global memory.  A wavefront owns CSR_RPW consecutive rows, whose lists are one contiguous range of
-// col_idx; per 64 edges one vector step decodes the edge ids (e = (i * b + j) * l_q + s) into Q row and weight,
-// then all 64 lanes (two columns each) apply the edges in order.  Same order and arithmetic as bwd_dd_kernel:
-// same bits.
+// CSR in global memory.  A workgroup owns CSR_APPLY_WAVES * CSR_RPW consecutive rows and wavefront w of it the rows
+// w, w + CSR_APPLY_WAVES, ... (neighbouring rows are often hot together -- the first tokens of a document -- and so
+// go to different wavefronts).  The wavefront walks its rows' lists as one virtual array, list after list: slot s
+// starts at the sum of the lengths before it, and the lookup adds the distance between the virtual and the real start
+// of the edge's list.  Per 64 edges one vector step decodes the edge ids (e = (i * b + j) * l_q + s) into Q row and
+// weight, then all 64 lanes (two columns each) apply the edges in order.  Same order and arithmetic as
+// bwd_dd_kernel: same bits.
 constexpr int CSR_RPW = 8;
 constexpr int CSR_APPLY_WAVES = 4;
 
 template <int DT>
 __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdParams p, const int32_t *__restrict__ row_ptr,
-                                                        const int32_t *__restrict__ col_idx, Magic bl_magic, Magic lq_magic)
+                                                        const int32_t *__restrict__ col_idx, Magic bl_magic, Magic lq_magic,
+                                                        BlockOrder order)
 {
     constexpr int EB = Elem<DT>::BYTES;
     __shared__ __attribute__((aligned(16))) float gstage[CSR_APPLY_WAVES][128]; // per wavefront: the weights of the edges being walked
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
-    const int64_t r0 = ((int64_t)blockIdx.x * CSR_APPLY_WAVES + w) * CSR_RPW;
-    if (r0 >= p.total_tokens)
+    const int blk = ordered_block(order, blockIdx.x);
+    const int64_t rb = (int64_t)blk * (CSR_APPLY_WAVES * CSR_RPW) + w; // the wavefront's first row
+    if (blk < 0 || rb >= p.total_tokens)
         return;
-    const int n_rows = (int)(p.total_tokens - r0 < CSR_RPW ? p.total_tokens - r0 : CSR_RPW);
     const int col = (int)blockIdx.y * SLAB + 2 * lane;
     const bool col_ok = col < p.d;
     const uint32_t lane_off = (uint32_t)((col_ok ? 2 * lane : 0) + (int)blockIdx.y * SLAB) * EB;
     const uint32_t row_bytes = (uint32_t)p.d * EB;
     const __amdgpu_buffer_rsrc_t rsrc = q_resource(p.Q, (uint32_t)p.n_q * (uint32_t)p.l_q * row_bytes); // < 2^32 (checked by the caller)
     const int64_t n_edges = (int64_t)p.n_q * p.l_q * p.b; // < 2^31 (checked by the caller)
-    int rp = row_ptr[r0 + (lane < n_rows ? lane : n_rows)];
-    rp = rp < 0 ? 0 : (rp > n_edges ? (int)n_edges : rp); // device data the host cannot check
-    const int k_lo = __builtin_amdgcn_readlane(rp, 0);
-    int k_hi = __builtin_amdgcn_readlane(rp, n_rows);
-    k_hi = k_hi < k_lo ? k_lo : k_hi;
-    rp = lane >= n_rows ? k_hi : rp;
+    // lane s < CSR_RPW: the list of row rb + CSR_APPLY_WAVES * s
+    const int64_t my_row = rb + (int64_t)CSR_APPLY_WAVES * (lane < CSR_RPW ? lane : 0);
+    const bool have = lane < CSR_RPW && my_row < p.total_tokens;
+    int lo = row_ptr[have ? my_row : rb], hi = row_ptr[(have ? my_row : rb) + 1];
+    lo = lo < 0 ? 0 : (lo > n_edges ? (int)n_edges : lo); // device data the host cannot check
+    hi = hi < lo ? lo : (hi > n_edges ? (int)n_edges : hi);
+    const int len = have ? hi - lo : 0;
+    const int incl = wave_scan_incl(len, lane);
+    const int vstart = incl - len; // lanes >= CSR_RPW: the total
+    const int k_hi = __builtin_amdgcn_readlane(incl, 63);
+    const int delta = lo - vstart;
     const uint32_t bl = (uint32_t)(p.b * p.l_q); // edge ids of one query
     typename RowVec<CSR_RPW>::type rx, ry;
 #pragma unroll
@@ -1038,8 +1071,9 @@ __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdPara
         rx[s] = 0.0f;
         ry[s] = 0.0f;
     }
-    auto lookup = [&](int kk, bool valid, uint32_t &n, float &gv) {
-        const int e = valid ? col_idx[kk] : 0;
+    auto lookup = [&](int kk, bool valid, int slot, uint32_t &n, float &gv) {
+        const int at = kk + __shfl(delta, slot);
+        const int e = valid ? col_idx[at] : 0;
         const uint32_t ue = e < 0 ? 0u : (uint32_t)e;
         const uint32_t i = magic_div(ue, bl_magic);
         const uint32_t rem = ue - i * bl; // j * l_q + s
@@ -1049,12 +1083,14 @@ __global__ void __launch_bounds__(CSR_APPLY_WAVES * 64) csr_apply_kernel(BwdPara
         n = ok ? i * (uint32_t)p.l_q + s_ : 0u;
         gv = ok ? p.g[(int64_t)i * p.b + jj] : 0.0f;
     };
-    walk_rows<DT, CSR_RPW>(rsrc, row_bytes, lane, lane_off, k_lo, k_hi, rp, &gstage[w][0], lookup, rx, ry);
+    walk_rows<DT, CSR_RPW>(rsrc, row_bytes, lane, lane_off, 0, k_hi, vstart, &gstage[w][0], lookup, rx, ry);
     if (col_ok) {
 #pragma unroll
-        for (int s = 0; s < CSR_RPW; ++s)
-            if (s < n_rows)
-                *reinterpret_cast<float2 *>(p.dD + (r0 + s) * p.d + col) = make_float2(rx[s], ry[s]);
+        for (int s = 0; s < CSR_RPW; ++s) {
+            const int64_t row = rb + (int64_t)CSR_APPLY_WAVES * s;
+            if (row < p.total_tokens)
+                *reinterpret_cast<float2 *>(p.dD + row * p.d + col) = make_float2(rx[s], ry[s]);
+        }
     }
 }
 
@@ -1087,16 +1123,16 @@ hipError_t csr_build_launch(const int32_t *argmax, int n_q, int64_t b, int l_q, 
 
 
 template <int DT> static hipError_t launch_bwd_csr(const BwdParams &p, const int32_t *row_ptr, const int32_t *col_idx,
-                                                   hipStream_t stream)
+                                                   int num_cu, hipStream_t stream)
 {
     hipError_t e = launch_dq<DT>(p, stream);
     if (e != hipSuccess)
         return e;
     constexpr int ROWS = CSR_RPW * CSR_APPLY_WAVES; // rows per workgroup
-    const int64_t groups = (p.total_tokens + ROWS - 1) / ROWS;
+    const BlockOrder order = block_order((p.total_tokens + ROWS - 1) / ROWS, num_cu);
     const unsigned slabs = (unsigned)((p.d + SLAB - 1) / SLAB);
-    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3((unsigned)groups, slabs), dim3(CSR_APPLY_WAVES * 64), 0, stream, p, row_ptr,
-                       col_idx, magic_u31((uint32_t)(p.b * p.l_q)), magic_u31((uint32_t)p.l_q));
+    hipLaunchKernelGGL((csr_apply_kernel<DT>), dim3(order.grid, slabs), dim3(CSR_APPLY_WAVES * 64), 0, stream, p, row_ptr,
+                       col_idx, magic_u31((uint32_t)(p.b * p.l_q)), magic_u31((uint32_t)p.l_q), order);
     return hipGetLastError();
 }
 
@@ -1122,9 +1158,9 @@ hipError_t backward_csr_launch(const void *Q, int n_q, int l_q, const void *D, i
     p.l_d = l_d;
     p.d = d;
     switch (dtype) {
-    case MAXSIM_F32: return launch_bwd_csr<MAXSIM_F32>(p, row_ptr, col_idx, stream);
-    case MAXSIM_F16: return launch_bwd_csr<MAXSIM_F16>(p, row_ptr, col_idx, stream);
-    default: return launch_bwd_csr<MAXSIM_BF16>(p, row_ptr, col_idx, stream);
+    case MAXSIM_F32: return launch_bwd_csr<MAXSIM_F32>(p, row_ptr, col_idx, num_cu, stream);
+    case MAXSIM_F16: return launch_bwd_csr<MAXSIM_F16>(p, row_ptr, col_idx, num_cu, stream);
+    default: return launch_bwd_csr<MAXSIM_BF16>(p, row_ptr, col_idx, num_cu, stream);
     }
 }
 

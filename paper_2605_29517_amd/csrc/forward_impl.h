@@ -365,7 +365,12 @@ __device__ __forceinline__ void fold_step_packed(const f32x16 &acc, int u, float
     }
     if (u == NU - 1) {
         const uint32_t tb = __float_as_uint(tmax);
-        if (__builtin_expect(__ballot(((int)tb < 0 && m < 0.0f) || fabsf(tmax) >= 512.0f) != 0, 0)) {
+        // one unsigned compare finds the tiles that MAY need the exact fold (a negative maximum has the sign bit set);
+        // the precise condition is looked at only then
+        bool exact = false;
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(tb >= 0x44000000u /* 512.0f */) != 0, 0))
+            exact = __builtin_amdgcn_ballot_w64(((int)tb < 0 && m < 0.0f) || fabsf(tmax) >= 512.0f) != 0;
+        if (exact) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const bool up = acc[r] > m; // strict: the first occurrence keeps a tie
@@ -571,12 +576,6 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                 for (int u = 0; u < 3; ++u)
                     ring[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
             }
-            const bool first = ci.t0 == 0;
-#pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                m[cb] = first ? neg_inf() : m[cb];
-                idx[cb] = first ? 0 : idx[cb];
-            }
             __builtin_amdgcn_sched_barrier(0);
             f32x16 acc[NCB];
             float tmax[NCB]; // the tile's maximum per column block (argmax with 16-bit inputs only)
@@ -636,6 +635,8 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
                             lds_part[par][lb] = sum;
                         }
                     }
+                    m[cb] = neg_inf(); // the next document starts from nothing
+                    idx[cb] = 0;
                 }
             }
             it_next(ci, p, off);

@@ -35,8 +35,8 @@ class _MaxSimRagged(torch.autograd.Function):
 
 
 def maxsim(Q, D, doc_offsets=None):
-    """Differentiable scores [n_q, b] of Q [n_q,l_q,128] against D [b,l_d,128], or against a packed corpus
-    D [T,128] with int32 doc_offsets [b+1] (all on the GPU).  An empty ragged document scores -inf and receives no gradient."""
+    """Differentiable scores [n_q, b] of Q [n_q,l_q,d] against D [b,l_d,d], or against a packed corpus
+    D [T,d] with int32 doc_offsets [b+1] (all on the GPU; d as the forward and backward entry points take it).  An empty ragged document scores -inf and receives no gradient."""
     if doc_offsets is None:
         return _MaxSim.apply(Q, D)
     return _MaxSimRagged.apply(Q, D, doc_offsets)

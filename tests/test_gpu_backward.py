@@ -265,9 +265,11 @@ def test_autograd_wrapper_matches_the_oracle():
     keep = torch.isfinite(s)
     (torch.where(keep, s, torch.zeros_like(s)) * w).sum().backward()
     rQ, rD = O.backward_ragged(W.to_raw_numpy(Q), W.to_raw_numpy(Dp), "f16", off, A, w.cpu().numpy().astype(np.float64))
-    # gradients come back in the input dtype (fp16): compare at fp16 resolution
-    assert np.abs(Qg.grad.float().cpu().numpy() - rQ).max() <= 2e-3 * np.abs(rQ).max()
-    assert np.abs(Dg.grad.float().cpu().numpy() - rD).max() <= 2e-3 * np.abs(rD).max()
+    # torch wants gradients in the input dtype: the fp32 gradients of the C ABI (bar 1e-4 of the maximum, as in `close`)
+    # are rounded to fp16 by the glue, half an ulp = 2^-11 relative per element
+    tol = 1e-4 + 2.0 ** -11
+    assert np.abs(Qg.grad.float().cpu().numpy() - rQ).max() <= tol * np.abs(rQ).max()
+    assert np.abs(Dg.grad.float().cpu().numpy() - rD).max() <= tol * np.abs(rD).max()
     # uniform path, fp32
     Qf = W.unit_rows((3, 16, 128), "f32", 7, DEV).requires_grad_(True)
     Df = W.unit_rows((4, 50, 128), "f32", 8, DEV).requires_grad_(True)

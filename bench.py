@@ -526,6 +526,10 @@ def main():
         dst = torch.empty(1 << 28, dtype=torch.int32, device=dev)   # 1 GiB
         w, a, m, mn = time_launches(lambda: P.maxsim_probe_read(big, sink), 10, 3)
         ceil["hbm_read_stream_reference"] = {"ms": round(a, 3), "GB_per_s": round(big.numel() * 4 / (a * 1e-3) / 1e9, 1)}
+        # the same stream with non-temporal loads (the hint slows the scoring kernels, whose load instructions take 32 bytes
+        # of each of 32 lines and rely on the caches to merge them; whole-line streams gain from it)
+        w, a, m, mn = time_launches(lambda: P.maxsim_probe_read(big, sink, streaming=True), 10, 3)
+        ceil["hbm_read_stream_non_temporal"] = {"ms": round(a, 3), "GB_per_s": round(big.numel() * 4 / (a * 1e-3) / 1e9, 1)}
         w, a, m, mn = time_launches(lambda: P.maxsim_probe_copy(big[:1 << 28], dst), 10, 3)
         ceil["hbm_copy_1GiB"] = {"ms": round(a, 3), "GB_per_s_read_plus_write": round(2 * dst.numel() * 4 / (a * 1e-3) / 1e9, 1),
                                  "bytes_read": dst.numel() * 4, "bytes_written": dst.numel() * 4}

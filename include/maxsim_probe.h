@@ -1,7 +1,7 @@
 /*
  * maxsim_probe.h -- diagnostics for the benchmark of the fused MaxSim library (libmaxsim_probe.so).
  *
- * Not part of the operator and not ABI-stable: four kernels that show what an MI355X sustains, for roofline
+ * Not part of the operator and not ABI-stable: five kernels that show what an MI355X sustains, for roofline
  * context beside the library's own kernels.  Conventions (device pointers, `stream`, return codes) as in maxsim.h.
  *
  * maxsim_probe_mfma: a register-only loop of 32x32 MFMAs with four independent accumulators,
@@ -9,7 +9,8 @@
  *   kind 0 = fp16 (32x32x16), 1 = bf16 (32x32x16), 2 = int8 (32x32x32).  `operands` is >= 1 MiB of device memory
  *   whose bits are used as MFMA operands (random bits give the rate under realistic switching activity, zeros the
  *   rate at full clocks).  Operations per launch: 512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1, 2*32*32*32 for 2).
- * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them (a reference read rate).
+ * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them (a reference read rate);
+ *   maxsim_probe_read_streaming does the same with non-temporal loads (whole lines per instruction, no reuse).
  * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
  *   traffic for calibrating profiler byte counters.
  * maxsim_probe_gather: every wavefront (sixteen per CU) gathers iters x 16 pseudo-random whole rows of 256 bytes from
@@ -31,6 +32,7 @@ extern "C" {
 
 int maxsim_probe_mfma(int kind, const void *operands, int iters, float *sink, void *stream);
 int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream);
+int maxsim_probe_read_streaming(const void *buf, int64_t bytes, float *sink, void *stream);
 int maxsim_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
 int64_t maxsim_probe_gather(int kind, const void *table, int64_t rows, int iters, float *sink, void *stream);
 

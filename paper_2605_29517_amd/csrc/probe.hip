@@ -2,7 +2,7 @@
 // operator's library): what the machine sustains, measured beside the real kernels.
 //   probe_mfma   register-only MFMA loop on caller-supplied operand bits (random data makes the
 //                part run at the clocks it holds under load; zeros show the unthrottled rate)
-//   probe_read   pure streaming read of a buffer
+//   probe_read   pure streaming read of a buffer, with plain loads or with the non-temporal hint
 //   probe_copy   plain copy of known size (calibrates the HBM byte counters of the profiler)
 //   probe_gather random gathers of whole 256-byte rows from a table (what the caches deliver to the access
 //                pattern of the backward: a row per edge)
@@ -51,16 +51,24 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(const uint4 *in, int it
         sink[0] = s;
 }
 
-__global__ void __launch_bounds__(256) probe_read_kernel(const uint4 *p, int64_t n_vec, float *sink)
+// NT: the loads carry the non-temporal hint (the lines are not kept for reuse)
+template <bool NT> __global__ void __launch_bounds__(256) probe_read_kernel(const uint4 *p, int64_t n_vec, float *sink)
 {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * 256;
     uint32_t acc = 0;
     for (; i + 7 * stride < n_vec; i += 8 * stride) { // eight 16-byte loads in flight per lane
         uint4 v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            v[k] = p[i + k * stride];
+        for (int k = 0; k < 8; ++k) {
+            if (NT) {
+                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + i + k * stride));
+                v[k] = make_uint4(t.x, t.y, t.z, t.w);
+            } else {
+                v[k] = p[i + k * stride];
+            }
+        }
 #pragma unroll
         for (int k = 0; k < 8; ++k)
             acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
@@ -135,10 +143,14 @@ static hipError_t probe_mfma_launch(int kind, const void *operands, int iters, f
     return hipGetLastError();
 }
 
-static hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, int num_cu, hipStream_t stream)
+static hipError_t probe_read_launch(const void *buf, int64_t bytes, float *sink, bool streaming, int num_cu, hipStream_t stream)
 {
-    hipLaunchKernelGGL(probe_read_kernel, dim3(num_cu * 8), dim3(256), 0, stream, static_cast<const uint4 *>(buf),
-                       bytes / 16, sink);
+    if (streaming)
+        hipLaunchKernelGGL(probe_read_kernel<true>, dim3(num_cu * 8), dim3(256), 0, stream, static_cast<const uint4 *>(buf),
+                           bytes / 16, sink);
+    else
+        hipLaunchKernelGGL(probe_read_kernel<false>, dim3(num_cu * 8), dim3(256), 0, stream, static_cast<const uint4 *>(buf),
+                           bytes / 16, sink);
     return hipGetLastError();
 }
 
@@ -178,7 +190,16 @@ int maxsim_probe_read(const void *buf, int64_t bytes, float *sink, void *stream)
 {
     if (!buf || !sink || bytes < 16 || !probe_aligned16(buf))
         return MAXSIM_ERR_INVALID;
-    return maxsim::probe_read_launch(buf, bytes, sink, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
+    return maxsim::probe_read_launch(buf, bytes, sink, false, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? MAXSIM_OK
+               : MAXSIM_ERR_LAUNCH;
+}
+
+int maxsim_probe_read_streaming(const void *buf, int64_t bytes, float *sink, void *stream)
+{
+    if (!buf || !sink || bytes < 16 || !probe_aligned16(buf))
+        return MAXSIM_ERR_INVALID;
+    return maxsim::probe_read_launch(buf, bytes, sink, true, probe_num_cu(), static_cast<hipStream_t>(stream)) == hipSuccess
                ? MAXSIM_OK
                : MAXSIM_ERR_LAUNCH;
 }

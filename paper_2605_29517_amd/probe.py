@@ -8,7 +8,7 @@ from .binding import MaxSimError, _check, _dev, _on_device, _stream
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmaxsim_probe.so")
-SYMBOLS = ("maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_copy", "maxsim_probe_gather")
+SYMBOLS = ("maxsim_probe_mfma", "maxsim_probe_read", "maxsim_probe_read_streaming", "maxsim_probe_copy", "maxsim_probe_gather")
 PROBE_MFMA_OPS_PER_ITER = {0: 512 * 4 * 4 * 2 * 32 * 32 * 16, 1: 512 * 4 * 4 * 2 * 32 * 32 * 16, 2: 512 * 4 * 4 * 2 * 32 * 32 * 32}
 
 _lib = None
@@ -26,6 +26,8 @@ def load():
     L.maxsim_probe_mfma.argtypes = [i, p, i, p, p]
     L.maxsim_probe_read.restype = i
     L.maxsim_probe_read.argtypes = [p, l, p, p]
+    L.maxsim_probe_read_streaming.restype = i
+    L.maxsim_probe_read_streaming.argtypes = [p, l, p, p]
     L.maxsim_probe_copy.restype = i
     L.maxsim_probe_copy.argtypes = [p, p, l, p]
     L.maxsim_probe_gather.restype = l
@@ -46,12 +48,13 @@ def maxsim_probe_mfma(kind, operands, iters, sink):
     return PROBE_MFMA_OPS_PER_ITER[int(kind)] * int(iters)
 
 
-def maxsim_probe_read(buf, sink):
-    """Streaming read of a whole tensor.  Returns the bytes read."""
+def maxsim_probe_read(buf, sink, streaming=False):
+    """Streaming read of a whole tensor (streaming=True: with non-temporal loads).  Returns the bytes read."""
     L = load()
     nbytes = buf.numel() * buf.element_size() // 16 * 16
+    fn = L.maxsim_probe_read_streaming if streaming else L.maxsim_probe_read
     with _on_device(buf, "buf"):
-        rc = L.maxsim_probe_read(_dev(buf, "buf"), nbytes, _dev(sink, "sink", torch.float32), _stream(buf))
+        rc = fn(_dev(buf, "buf"), nbytes, _dev(sink, "sink", torch.float32), _stream(buf))
     _check(rc, "maxsim_probe_read")
     return nbytes
 

@@ -25,7 +25,9 @@
  *         operands in slabs of the embedding dimension (the paper's inner loop over d).
  *       backward (maxsim_backward, _ragged, _csr, _csr_static): any multiple of 8 from 8 to 8192; Q must stay
  *         below 4 GiB and D below 64 GiB.
- *       int8 entry points and the quantiser: 128 only.
+ *       int8 entry points and the quantiser: any multiple of 32 from 32 to 8192.  d = 128 takes the tuned kernels
+ *         (queries resident in LDS or registers); other widths a plain inner loop over d with the same arithmetic
+ *         and the same bits, at a fraction of the speed.
  *     Other widths must be zero-padded by the caller; anything else returns MAXSIM_ERR_UNSUPPORTED.
  *   - Four kernel families use more than 64 KB of LDS, which HIP wants allowed per kernel and device before the
  *     first launch.  maxsim_init() does that (and all other per-device set-up) for the current device; an entry

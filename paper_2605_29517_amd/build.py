@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmaxsim.so")
 PROBE_LIB = os.path.join(HERE, "libmaxsim_probe.so")
-SOURCES = ["api.hip", "forward.hip", "forward_f16.hip", "forward_bf16.hip", "forward_f32.hip", "forward_splitd.hip", "backward.hip", "int8.hip"]
+SOURCES = ["api.hip", "forward.hip", "forward_f16.hip", "forward_bf16.hip", "forward_f32.hip", "forward_splitd.hip", "backward.hip", "int8.hip", "int8_wide.hip"]
 PROBE_SOURCES = ["probe.hip"]
 # packed fp32 VALU forms are switched off on purpose (they have produced wrong results on
 # the test machines); the host pass warns that it does not know the feature, which is harmless

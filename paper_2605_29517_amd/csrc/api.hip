@@ -21,6 +21,11 @@ hipError_t backward_csr_static_launch(const void *Q, int n_q, int l_q, const voi
                                       const int32_t *argmax, const float *dscore, float *dQ, float *dD, int num_cu,
                                       hipStream_t stream);
 hipError_t quantize_launch(const void *X, int64_t rows, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
+bool i8_wide_width_ok(int d);
+hipError_t forward_i8_wide_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
+                                  const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, int d, float *scores,
+                                  int64_t ld, int num_cu, hipStream_t stream);
+hipError_t quantize_wide_launch(const void *X, int64_t rows, int d, int dtype, int8_t *X_i8, float *scale, hipStream_t stream);
 hipError_t forward_i8_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                              const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, float *scores,
                              int64_t ld, int num_cu, hipStream_t stream);
@@ -51,6 +56,17 @@ int num_cu()
     }
     return cached[dev];
 }
+
+// int8 scoring: the kernels built around 128-byte rows, or the plain inner loop over d for other widths
+static hipError_t i8_launch_any(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
+                                const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, int d, float *scores,
+                                int64_t ld, int cus, hipStream_t stream)
+{
+    if (d == maxsim::D_MODEL)
+        return maxsim::forward_i8_launch(Q, qs, n_q, l_q, D, ds, offsets, b, l_d, total_tokens, scores, ld, cus, stream);
+    return maxsim::forward_i8_wide_launch(Q, qs, n_q, l_q, D, ds, offsets, b, l_d, total_tokens, d, scores, ld, cus, stream);
+}
+static bool i8_width_ok(int d) { return d == maxsim::D_MODEL || maxsim::i8_wide_width_ok(d); }
 
 // embedding widths of the backward entry points: whole 16-byte chunks of 8 elements, up to 64 slabs of 128 columns
 bool backward_width_ok(int d) { return d >= 8 && d <= 8192 && d % 8 == 0; }
@@ -266,7 +282,7 @@ int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q
     if (!aligned(Q_i8, 16) || !aligned(D_i8_host, 16) || !aligned(staging_codes, 16) || !aligned(q_scale, 4) ||
         !aligned(d_scale_host, 4) || !aligned(staging_scales, 4) || !aligned(scores, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!i8_width_ok(d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (block_docs > b)
         block_docs = b;
@@ -288,9 +304,9 @@ int maxsim_forward_i8_streamed(const int8_t *Q_i8, const float *q_scale, int n_q
                                   (size_t)(docs * l_d) * sizeof(float), hipMemcpyHostToDevice, copy);
         },
         [&](int half, int64_t first, int64_t docs) {
-            return maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, staging_codes + half * block_docs * doc_bytes,
-                                             staging_scales + half * block_docs * l_d, nullptr, docs, l_d,
-                                             docs * (int64_t)l_d, scores + first, b, cus, compute);
+            return i8_launch_any(Q_i8, q_scale, n_q, l_q, staging_codes + half * block_docs * doc_bytes,
+                                 staging_scales + half * block_docs * l_d, nullptr, docs, l_d, docs * (int64_t)l_d, d,
+                                 scores + first, b, cus, compute);
         });
 }
 
@@ -411,12 +427,14 @@ int maxsim_quantize_rows_i8(const void *X, int64_t rows, int d, maxsim_dtype dty
         return MAXSIM_ERR_INVALID;
     if (!aligned(X, 16) || !aligned(X_i8, 16) || !aligned(scale, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!i8_width_ok(d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (rows >= (int64_t(1) << 40))
         return MAXSIM_ERR_UNSUPPORTED;
     if (int rc = ensure_init())
         return rc;
+    if (d != maxsim::D_MODEL)
+        return finish(maxsim::quantize_wide_launch(X, rows, d, (int)dtype, X_i8, scale, static_cast<hipStream_t>(stream)));
     return finish(maxsim::quantize_launch(X, rows, (int)dtype, X_i8, scale, static_cast<hipStream_t>(stream)));
 }
 
@@ -427,15 +445,15 @@ int maxsim_forward_i8(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q
         return MAXSIM_ERR_INVALID;
     if (!aligned(Q_i8, 16) || !aligned(D_i8, 16) || !aligned(q_scale, 4) || !aligned(d_scale, 4) || !aligned(scores, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!i8_width_ok(d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (b >= (int64_t(1) << 31) || (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) ||
         l_q > 1024 || b * (int64_t)l_d >= (int64_t(1) << 31))
         return MAXSIM_ERR_UNSUPPORTED;
     if (int rc = ensure_init())
         return rc;
-    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, nullptr, b, l_d, b * (int64_t)l_d,
-                                            scores, b, num_cu(), static_cast<hipStream_t>(stream)));
+    return finish(i8_launch_any(Q_i8, q_scale, n_q, l_q, D_i8, d_scale, nullptr, b, l_d, b * (int64_t)l_d, d, scores, b,
+                                num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, int l_q, const int8_t *D_i8_packed,
@@ -448,15 +466,15 @@ int maxsim_forward_i8_ragged(const int8_t *Q_i8, const float *q_scale, int n_q, 
     if (!aligned(Q_i8, 16) || !aligned(D_i8_packed, 16) || !aligned(q_scale, 4) || !aligned(d_scale_packed, 4) ||
         !aligned(doc_offsets, 4) || !aligned(scores, 4))
         return MAXSIM_ERR_INVALID;
-    if (d != maxsim::D_MODEL)
+    if (!i8_width_ok(d))
         return MAXSIM_ERR_UNSUPPORTED;
     if (b >= (int64_t(1) << 31) || total_tokens >= (int64_t(1) << 31) ||
         (int64_t)n_q * ((l_q + 31) / 32) >= (int64_t(1) << 24) || l_q > 1024)
         return MAXSIM_ERR_UNSUPPORTED;
     if (int rc = ensure_init())
         return rc;
-    return finish(maxsim::forward_i8_launch(Q_i8, q_scale, n_q, l_q, D_i8_packed, d_scale_packed, doc_offsets, b, 0,
-                                            total_tokens, scores, b, num_cu(), static_cast<hipStream_t>(stream)));
+    return finish(i8_launch_any(Q_i8, q_scale, n_q, l_q, D_i8_packed, d_scale_packed, doc_offsets, b, 0, total_tokens, d,
+                                scores, b, num_cu(), static_cast<hipStream_t>(stream)));
 }
 
 int maxsim_ce_grad(const float *scores, int n, int b, float tau, float *g, float *loss, void *stream)

@@ -64,6 +64,9 @@ def test_error_codes_without_touching_a_gpu():
     assert L.maxsim_backward(p, 1, 1, p, 1, 1, 100, 1, p, p, p, p, None) == -2     # backward: d must be a multiple of 8
     assert L.maxsim_backward(p, 1, 1, p, 1, 1, 16384, 1, p, p, p, p, None) == -2   # ... of at most 8192
     assert L.maxsim_forward_i8(p, p, 1, 2000, p, p, 1, 1, 128, p, None) == -2      # int8 queries above 1024 tokens
+    assert L.maxsim_forward_i8(p, p, 1, 20, p, p, 1, 1, 100, p, None) == -2        # int8 rows: a multiple of 32 bytes
+    assert L.maxsim_forward_i8(p, p, 1, 20, p, p, 1, 1, 8224, p, None) == -2       # ... of at most 8192
+    assert L.maxsim_quantize_rows_i8(p, 4, 24, 1, p, p, None) == -2                # the quantiser likewise
     assert L.maxsim_forward_streamed(p, 1, 32, p, 4, 40, 128, 1, 0, p, p, None) == -1  # block_docs < 1
     assert L.maxsim_forward_i8_ragged(p, p, 1, 32, p, p, None, 4, 100, 128, p, None) == -1  # no offsets
     assert L.maxsim_forward_i8_streamed(p, p, 1, 32, p, p, 4, 10, 128, 2, None, p, p, None) == -1  # no staging buffer

@@ -222,3 +222,102 @@ def test_forward_i8_shared_documents_negative_maxima():
     ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
     assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
     assert float(s[0, 0]) < 0 < float(s[0, 1])
+
+
+# ---- embedding widths other than 128 (every multiple of 32 up to 8192): the plain inner loop over d ----
+
+WIDE_D = [32, 64, 96, 256, 320, 768, 1024, 2048]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("d", WIDE_D + [8192])
+def test_quantiser_other_widths_bit_exact(d, dtype):
+    X = W.unit_rows((53, d), dtype, 300 + d, DEV)
+    X[5] = 0
+    X[6] = 0.25
+    X[7] *= 1e-3 if dtype != "f16" else 1e-2
+    codes, scale = M.maxsim_quantize_rows_i8(X)
+    torch.cuda.synchronize()
+    rc, rs = O.quantize_rows_i8(W.to_raw_numpy(X), dtype)
+    assert np.array_equal(bits(scale.cpu().numpy()), bits(rs))
+    assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+def wide_case(n_q, l_q, b, l_d, d, seed):
+    Qf = W.unit_rows((n_q, l_q, d), "f16", seed, DEV)
+    Df = W.unit_rows((b, l_d, d), "f32", seed + 1, DEV)
+    oq, oqs = O.quantize_rows_i8(W.to_raw_numpy(Qf), "f16")
+    od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df), "f32")
+    gq, gqs = M.maxsim_quantize_rows_i8(Qf)
+    gd, gds = M.maxsim_quantize_rows_i8(Df)
+    torch.cuda.synchronize()
+    assert np.array_equal(gq.cpu().numpy(), oq) and np.array_equal(bits(gqs.cpu().numpy()), bits(oqs))
+    assert np.array_equal(gd.cpu().numpy(), od) and np.array_equal(bits(gds.cpu().numpy()), bits(ods))
+    return (gq, gqs, gd, gds), (oq, oqs, od, ods)
+
+
+# (n_q, l_q, b, l_d): one block, ragged tails of blocks and tiles, several queries per workgroup, a query that fills a
+# workgroup (32 blocks), more queries than a workgroup holds, more documents than chunks
+@pytest.mark.parametrize("d", WIDE_D)
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (1, 32, 9, 64), (2, 33, 5, 65), (3, 100, 7, 31), (40, 32, 19, 70)])
+def test_forward_i8_other_widths_bit_exact(shape, d):
+    n_q, l_q, b, l_d = shape
+    g, o = wide_case(n_q, l_q, b, l_d, d, 400 + d)
+    s = M.maxsim_forward_i8(*g)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(*o)
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+
+
+@pytest.mark.parametrize("case", [(1, 1024, 3, 70, 256), (2, 700, 2100, 40, 64), (5, 300, 6, 130, 768)])
+def test_forward_i8_other_widths_long_queries_and_many_documents(case):
+    n_q, l_q, b, l_d, d = case
+    g, o = wide_case(n_q, l_q, b, l_d, d, 77)
+    s = M.maxsim_forward_i8(*g)
+    torch.cuda.synchronize()
+    keep = np.unique(np.concatenate([[0, b - 1], np.random.default_rng(5).integers(0, b, 40)]))
+    ref = O.forward_i8(o[0], o[1], np.ascontiguousarray(o[2][keep]), np.ascontiguousarray(o[3][keep]))
+    assert np.array_equal(bits(s[:, torch.from_numpy(keep).to(DEV)].cpu().numpy()), bits(ref))
+
+
+def test_forward_i8_other_widths_extreme_codes():
+    """All codes at +-127 and d = 8192: |n| = 127^2 * 8192 is past 2^24, where an fp32 conversion of n would round;
+    negative and positive maxima."""
+    d = 8192
+    Q = torch.full((1, 33, d), -127, dtype=torch.int8, device=DEV)
+    D = torch.full((3, 40, d), 127, dtype=torch.int8, device=DEV)
+    D[1, 5] = -127
+    D[2, :, 1::2] = 126
+    qs = torch.full((1, 33), 0.5, device=DEV)
+    ds = torch.rand(3, 40, device=DEV, generator=torch.Generator(DEV).manual_seed(3)) + 0.01
+    s = M.maxsim_forward_i8(Q, qs, D, ds)
+    torch.cuda.synchronize()
+    ref = O.forward_i8(Q.cpu().numpy(), qs.cpu().numpy(), D.cpu().numpy(), ds.cpu().numpy())
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+    assert float(s[0, 0]) < 0 < float(s[0, 1])
+
+
+@pytest.mark.parametrize("d", [64, 256, 1024])
+def test_forward_i8_ragged_other_widths_bit_exact(d):
+    lens = np.asarray([5, 0, 64, 65, 1, 130, 0, 33, 0], dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    Qf = W.unit_rows((3, 40, d), "f16", 500 + d, DEV)
+    Df = W.unit_rows((int(off[-1]), d), "f32", 501 + d, DEV)
+    oq, oqs = O.quantize_rows_i8(W.to_raw_numpy(Qf), "f16")
+    od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df), "f32")
+    gq, gqs = M.maxsim_quantize_rows_i8(Qf)
+    gd, gds = M.maxsim_quantize_rows_i8(Df)
+    s = M.maxsim_forward_i8_ragged(gq, gqs, gd, gds, torch.from_numpy(off).to(DEV))
+    torch.cuda.synchronize()
+    ref = O.forward_i8_ragged(oq, oqs, od, ods, off)
+    assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
+    assert np.isneginf(s.cpu().numpy()[:, lens == 0]).all()
+
+
+def test_int8_widths_that_are_refused():
+    for d in (16, 100, 8224):
+        with pytest.raises(M.MaxSimError):
+            M.maxsim_quantize_rows_i8(torch.zeros(4, d, device=DEV))
+        with pytest.raises(M.MaxSimError):
+            M.maxsim_forward_i8(torch.zeros(1, 4, d, dtype=torch.int8, device=DEV), torch.ones(1, 4, device=DEV),
+                                torch.zeros(2, 5, d, dtype=torch.int8, device=DEV), torch.ones(2, 5, device=DEV))

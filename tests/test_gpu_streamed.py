@@ -70,3 +70,17 @@ def test_int8_streamed_equals_resident(case):
     od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df[:50].contiguous()), "f32")
     ref = O.forward_i8(oq, oqs, od, ods)
     assert np.array_equal(s[:, :50].cpu().numpy().view(np.uint32), ref[:, :min(50, b)].view(np.uint32))
+
+
+def test_int8_streamed_other_width_equals_resident():
+    n_q, l_q, b, l_d, d, block_docs = 2, 70, 130, 45, 256, 50
+    q8, qs = M.maxsim_quantize_rows_i8(W.unit_rows((n_q, l_q, d), "f16", 61, DEV))
+    d8, ds = M.maxsim_quantize_rows_i8(W.unit_rows((b, l_d, d), "f32", 62, DEV))
+    resident = M.maxsim_forward_i8(q8, qs, d8, ds)
+    d8h = torch.empty(d8.shape, dtype=torch.int8, pin_memory=True)
+    dsh = torch.empty(ds.shape, dtype=torch.float32, pin_memory=True)
+    d8h.copy_(d8)
+    dsh.copy_(ds)
+    s = M.maxsim_forward_i8_streamed(q8, qs, d8h, dsh, block_docs)
+    torch.cuda.synchronize()
+    assert torch.equal(s, resident)

@@ -331,9 +331,20 @@ def main():
             w, a, m, mn = time_launches(lambda: M.maxsim_forward(Qw, Dw, scores=sw), 50, 5)
             small.append({"d": dw, "ms": round(w, 4), "kernel_ms": stats()})
             del Qw, Dw, sw
+        # int8 at the same widths (the plain, untuned inner loop over d; d = 128 is config 5): a quarter of the pages
+        wide8 = []
+        for dw, ndw in ((256, 500), (512, 250), (1024, 125), (2048, 64)):
+            q8w, qsw = M.maxsim_quantize_rows_i8(W.unit_rows((4, 1024, dw), "f16", 95, dev))
+            d8w, dsw = M.maxsim_quantize_rows_i8(W.unit_rows((ndw, 1024, dw), "bf16", 96, dev))
+            sw = torch.empty(4, ndw, dtype=torch.float32, device=dev)
+            w, a, m, mn = time_launches(lambda: M.maxsim_forward_i8(q8w, qsw, d8w, dsw, scores=sw), 50, 5)
+            ops = 2.0 * 4 * 1024 * ndw * 1024 * dw
+            wide8.append({"d": dw, "n_docs": ndw, "ms": round(w, 4), "kernel_ms": stats(), "TOP_per_s": round(ops / (a * 1e-3) / 1e12, 1),
+                          "mfma_frac": round(ops / (a * 1e-3) / 1e12 / PEAK_MFMA_I8_TOPS, 4)})
+            del q8w, qsw, d8w, dsw, sw
         extra.append({"leg": "wide_d", "workload": "N_q=4, L_q=L_d=1024, bf16, d=256 .. 2048 at about 2 GB of documents each; "
-                                                   "and B=128, N_q=1 (the paper's split-d table)",
-                      "results": wide, "b128_single_query": small,
+                                                   "and B=128, N_q=1 (the paper's split-d table); int8 at d=256 .. 2048",
+                      "results": wide, "b128_single_query": small, "int8": wide8,
                       "paper_context": {"split_d_ms_A100": {"768": 2.43, "1024": 2.60, "2048": 4.91},
                                         "split_d_ms_H100": {"768": 0.76, "1024": 1.07, "2048": 2.06}}})
 

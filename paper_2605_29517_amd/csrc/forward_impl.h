@@ -313,21 +313,24 @@ template <int DT> struct LdsTile {
 // piece of LDS (padded rows, no barrier: nobody else touches it) and reads it back in MFMA operand layout.  The
 // direct loads of fwd_stream_kernel take 32 bytes of each of 32 lines per instruction and cannot carry the hint;
 // a read stream of this shape measures 6.8 TB/s with it and 6.0 without.
+template <int DT> constexpr int lin_waves() { return Traits<DT>::NU <= 8 ? 4 : 2; } // wavefronts per workgroup (LDS tiles of 4 to 17 KB)
+
 template <int DT, int NCB, bool ARGMAX>
-__global__ void __launch_bounds__(256) fwd_stream_lin_kernel(FwdParams p, OffsetsPtr off)
+__global__ void __launch_bounds__(lin_waves<DT>() * 64) fwd_stream_lin_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
     constexpr int NU = TR::NU;
+    constexpr int WPB = lin_waves<DT>();
     constexpr int CPR = TR::ROW_BYTES / 16; // 16-byte chunks (= lanes) per row
     constexpr int RPI = 64 / CPR;           // rows per load instruction
     static_assert(CPR <= 64 && RPI * NU == TILE_ROWS, "NU instructions of 64 lanes cover a tile");
-    __shared__ __attribute__((aligned(16))) char lds_all[4][LT::BYTES];
+    __shared__ __attribute__((aligned(16))) char lds_all[WPB][LT::BYTES];
     const int lane = threadIdx.x & 63;
     const int rho = lane & 31, h = lane >> 5;
     const int wib = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     char *lds = lds_all[wib];
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wib;
+    const int64_t chunk = (int64_t)blockIdx.x * WPB + wib;
     const int gb0 = 0;
     int64_t doc0, doc1;
     chunk_doc_range(p, chunk, doc0, doc1);
@@ -1127,14 +1130,18 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
 template <int DT, int NCB, bool ARGMAX>
 static hipError_t launch_stream(const FwdParams &p, int grid, hipStream_t stream)
 {
-    if constexpr (Traits<DT>::NU <= 8) { // one wavefront per run and rows of up to 256 bytes: whole-line loads through LDS
-        if (p.n_groups == 1) {
-            hipLaunchKernelGGL((fwd_stream_lin_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p, p.offsets);
-            return hipGetLastError();
-        }
+    if (p.n_groups == 1) { // one wavefront per run: whole-line loads through LDS
+        constexpr int WPB = lin_waves<DT>();
+        const int grid_lin = (p.n_chunks + WPB - 1) / WPB;
+        hipLaunchKernelGGL((fwd_stream_lin_kernel<DT, NCB, ARGMAX>), dim3(grid_lin), dim3(WPB * 64), 0, stream, p, p.offsets);
+        return hipGetLastError();
     }
-    hipLaunchKernelGGL((fwd_stream_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p, p.offsets);
-    return hipGetLastError();
+    if constexpr (Traits<DT>::NU <= 8) { // narrow rows: more than four column blocks go to the tile kernel
+        return hipErrorInvalidValue;
+    } else {
+        hipLaunchKernelGGL((fwd_stream_kernel<DT, NCB, ARGMAX>), dim3(grid), dim3(256), 0, stream, p, p.offsets);
+        return hipGetLastError();
+    }
 }
 
 template <int DT, int W, int NCB, bool ARGMAX, int PFD = 1>

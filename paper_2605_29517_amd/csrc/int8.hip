@@ -271,6 +271,7 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P, OffsetsPtr o
 // 512 bytes of LDS private to the wavefront to get from "one per lane" to "the 16 rows of
 // this lane's accumulator registers".
 constexpr int I8D_WAVES = 8;
+constexpr int I8D_LIN_BLOCKS = 2;                        // up to this many column blocks the tiles are read as whole lines (no gain from 4 on)
 constexpr int I8D_MAX_BLOCKS = 32;                       // column blocks per group (1024 query tokens)
 constexpr int I8D_QSTRIDE = I8_ROW_BYTES + 16;           // padded LDS row of a query token
 
@@ -300,6 +301,12 @@ __device__ __forceinline__ void i8d_tile_scales(float *w_scale, float *w_bias, f
         bi[r4 * 4 + 3] = b4.w;
     }
 }
+
+// dynamic LDS of the document-stationary kernels for NB column blocks (queries, their scales, per wavefront 32 token
+// scales and biases); the whole-line variant adds a document tile per wavefront
+constexpr size_t i8_doc_lds(int nb) { return (size_t)nb * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float); }
+constexpr size_t i8_doc_lin_lds(int nb) { return i8_doc_lds(nb) + (size_t)I8D_WAVES * TILE_ROWS * I8D_QSTRIDE; }
+constexpr size_t i8_split_lds(int nb) { return i8_doc_lds(nb) + (size_t)2 * I8D_WAVES * nb * BLOCK_COLS * sizeof(float); }
 
 constexpr int I8D_LAG_STEPS = 2; // steps between a block's MFMAs and its epilogue in the document-stationary kernels
 
@@ -404,7 +411,12 @@ __device__ __forceinline__ void i8d_load_queries(const I8Params &P, char *q_tile
 
 // NB: column blocks the tile loop walks over (the group's block count rounded up; the surplus
 // blocks multiply zero rows and are never looked at).
-template <int NB>
+//
+// LIN (few column blocks, where the corpus read is the cost): a tile of 32 rows is 4 KB of contiguous memory and
+// is read as such, with four non-temporal loads of 1 KB (eight lanes per row), parked in a piece of LDS of the
+// wavefront's own and read back in operand layout; the direct loads take 32 bytes of each of 32 lines per
+// instruction and cannot carry the hint (see load_stream16).
+template <int NB, bool LIN>
 __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, OffsetsPtr off)
 {
     const FwdParams &p = P.f;
@@ -427,6 +439,7 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, 
     float *q_scale = reinterpret_cast<float *>(smem + NB * BLOCK_COLS * I8D_QSTRIDE);
     float *w_scale = q_scale + NB * BLOCK_COLS + w * 64;
     float *w_bias = w_scale + 32;
+    char *w_tile = smem + i8_doc_lds(NB) + w * (TILE_ROWS * I8D_QSTRIDE); // LIN only: this wavefront's document tile
 
     i8d_load_queries<NB>(P, q_tile, q_scale, gb0, nb, tid);
     __syncthreads(); // the only barrier: from here on every wavefront is on its own
@@ -449,18 +462,28 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, 
     if (!it_valid(ci))
         return;
 
-    i32x4 a_n[I8_NU];
+    i32x4 a_n[I8_NU]; // LIN: piece i holds 16 bytes of row 8 i + lane / 8, else chunk 2 u + h of row rho
     float s_n = 0.0f;
     auto gload = [&]() {
         if (!it_valid(li))
             return;
-        int row = li.len - li.t0 - 1; // rows past the document re-read its last token
-        row = rho < row ? rho : row;
+        const int last = li.len - li.t0 - 1; // rows past the document re-read its last token
+        const int row = rho < last ? rho : last;
         const int64_t grow = (int64_t)li.row0 + row;
-        const char *src = P.D + grow * I8_ROW_BYTES + h * 16;
+        if constexpr (LIN) {
 #pragma unroll
-        for (int u = 0; u < I8_NU; ++u)
-            a_n[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
+            for (int i = 0; i < I8_NU; ++i) {
+                int r = i * 8 + (lane >> 3);
+                r = r < last ? r : last;
+                const uint4 t = load_stream16(P.D + ((int64_t)li.row0 + r) * I8_ROW_BYTES + (lane & 7) * 16);
+                a_n[i] = i32x4{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
+            }
+        } else {
+            const char *src = P.D + grow * I8_ROW_BYTES + h * 16;
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u)
+                a_n[u] = *reinterpret_cast<const i32x4 *>(src + u * 32);
+        }
         s_n = P.ds[grow];
         it_next(li, p, off);
     };
@@ -480,11 +503,22 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_doc_kernel(I8Params P, 
     while (it_valid(ci)) {
         // the prefetched tile becomes the current one; its scales go through the wavefront's LDS area
         i32x4 a[I8_NU];
+        if constexpr (LIN) {
 #pragma unroll
-        for (int u = 0; u < I8_NU; ++u)
-            a[u] = a_n[u];
+            for (int i = 0; i < I8_NU; ++i)
+                *reinterpret_cast<i32x4 *>(w_tile + (i * 8 + (lane >> 3)) * I8D_QSTRIDE + (lane & 7) * 16) = a_n[i];
+        } else {
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u)
+                a[u] = a_n[u];
+        }
         const float s_cur = s_n;
         gload(); // next tile, in flight during this one
+        if constexpr (LIN) {
+#pragma unroll
+            for (int u = 0; u < I8_NU; ++u)
+                a[u] = *reinterpret_cast<const i32x4 *>(w_tile + b_off + u * 32);
+        }
         float sc[16], bi[16];
         i8d_tile_scales(w_scale, w_bias, s_cur, rho, h, sc, bi);
         if (ci.t0 == 0) {
@@ -631,9 +665,6 @@ __global__ void __launch_bounds__(I8D_WAVES * 64) fwd_i8_split_kernel(I8Params P
     }
 }
 
-// dynamic LDS of the document-stationary kernels for NB column blocks
-constexpr size_t i8_doc_lds(int nb) { return (size_t)nb * BLOCK_COLS * (I8D_QSTRIDE + 4) + I8D_WAVES * 64 * sizeof(float); }
-constexpr size_t i8_split_lds(int nb) { return i8_doc_lds(nb) + (size_t)2 * I8D_WAVES * nb * BLOCK_COLS * sizeof(float); }
 
 template <int NB> static hipError_t launch_i8_split(const I8Params &P, int grid, hipStream_t s)
 {
@@ -649,7 +680,10 @@ template <int W> static hipError_t launch_i8(const I8Params &P, int grid, hipStr
 
 template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, hipStream_t s)
 {
-    hipLaunchKernelGGL((fwd_i8_doc_kernel<NB>), dim3(grid), dim3(I8D_WAVES * 64), i8_doc_lds(NB), s, P, P.f.offsets);
+    if constexpr (NB <= I8D_LIN_BLOCKS)
+        hipLaunchKernelGGL((fwd_i8_doc_kernel<NB, true>), dim3(grid), dim3(I8D_WAVES * 64), i8_doc_lin_lds(NB), s, P, P.f.offsets);
+    else
+        hipLaunchKernelGGL((fwd_i8_doc_kernel<NB, false>), dim3(grid), dim3(I8D_WAVES * 64), i8_doc_lds(NB), s, P, P.f.offsets);
     return hipGetLastError();
 }
 
@@ -658,7 +692,7 @@ template <int NB> static hipError_t launch_i8_doc(const I8Params &P, int grid, h
 template <int NB> static hipError_t allow_i8_lds()
 {
     if (i8_doc_lds(NB) > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_i8_doc_kernel<NB, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)i8_doc_lds(NB));
         if (e != hipSuccess)
             return e;

@@ -10,7 +10,8 @@
  *   whose bits are used as MFMA operands (random bits give the rate under realistic switching activity, zeros the
  *   rate at full clocks).  Operations per launch: 512 * 4 * iters * 4 * (2*32*32*16 for kinds 0/1, 2*32*32*32 for 2).
  * maxsim_probe_read: streams `bytes` (multiple of 16) from `buf` and discards them (a reference read rate);
- *   maxsim_probe_read_streaming does the same with non-temporal loads (whole lines per instruction, no reuse).
+ *   maxsim_probe_read_streaming does the same the way the streaming kernels read a corpus: every wavefront a
+ *   contiguous run of its own, 1 KB per instruction, with non-temporal loads (the fastest read stream found).
  * maxsim_probe_copy: copies `bytes` (multiple of 16) from `src` to `dst`: a kernel of known HBM
  *   traffic for calibrating profiler byte counters.
  * maxsim_probe_gather: every wavefront (sixteen per CU) gathers iters x 16 pseudo-random whole rows of 256 bytes from

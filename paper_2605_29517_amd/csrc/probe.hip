@@ -51,31 +51,48 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(const uint4 *in, int it
         sink[0] = s;
 }
 
-// NT: the loads carry the non-temporal hint (the lines are not kept for reuse)
+// NT = false: grid-stride loop, plain loads.  NT = true: every wavefront reads a contiguous run of its own (the way
+// the streaming kernels walk a corpus) with loads that carry the non-temporal hint: the fastest read stream found
+// on this part.
 template <bool NT> __global__ void __launch_bounds__(256) probe_read_kernel(const uint4 *p, int64_t n_vec, float *sink)
 {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * 256;
     uint32_t acc = 0;
-    for (; i + 7 * stride < n_vec; i += 8 * stride) { // eight 16-byte loads in flight per lane
-        uint4 v[8];
+    if (NT) {
+        const int64_t waves = (int64_t)gridDim.x * 4;
+        const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        const int64_t per = (n_vec / 64 + waves - 1) / waves * 64; // 16-byte pieces per run, whole KB
+        int64_t i = wave * per + (threadIdx.x & 63);
+        const int64_t end = (wave + 1) * per < n_vec ? (wave + 1) * per : n_vec;
+        for (; i + 7 * 64 < end; i += 8 * 64) { // eight loads of 1 KB in flight per wavefront
+            u32x4 v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            if (NT) {
-                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + i + k * stride));
-                v[k] = make_uint4(t.x, t.y, t.z, t.w);
-            } else {
-                v[k] = p[i + k * stride];
-            }
+            for (int k = 0; k < 8; ++k)
+                v[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + i + k * 64));
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
         }
+        for (; i < end; i += 64) {
+            uint4 v = p[i];
+            acc ^= v.x ^ v.y ^ v.z ^ v.w;
+        }
+    } else {
+        int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        const int64_t stride = (int64_t)gridDim.x * 256;
+        for (; i + 7 * stride < n_vec; i += 8 * stride) { // eight 16-byte loads in flight per lane
+            uint4 v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
-    }
-    for (; i < n_vec; i += stride) {
-        uint4 v = p[i];
-        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+            for (int k = 0; k < 8; ++k)
+                v[k] = p[i + k * stride];
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+        }
+        for (; i < n_vec; i += stride) {
+            uint4 v = p[i];
+            acc ^= v.x ^ v.y ^ v.z ^ v.w;
+        }
     }
     if (acc == 0x12345678u)
         sink[0] = 1.0f;

@@ -137,12 +137,14 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     // a ragged corpus (or a uniform one whose documents are not a whole number of tiles) scored by many queries of
     // one block: 32-row windows over the packed rows (no padded tiles at the ends of documents)
     const bool ragged_ends = ragged || (p.l_d % TILE_ROWS != 0 && p.b * (int64_t)p.l_d < ((int64_t)1 << 31)); // 32-bit packed rows
-    if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 8 && total_blocks <= 16) {
-        // nine to sixteen queries: the same windows with two queries per wavefront (6 % over the per-document tiles of
-        // shape 82 on the ragged 100K corpus)
-        w = 8;
-        wave_blocks = 2;
-        shape = 92;
+    if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 4 && total_blocks <= 16) {
+        // five to sixteen queries: the same windows in workgroups of two (up to 8 queries) or four wavefronts with 3 or 4
+        // queries each, so that a wavefront has as many MFMAs per window and barrier as with 32 queries (against two
+        // queries on each of eight wavefronts, and against the per-document tiles of shapes 42 / 82: 7-16 % on the
+        // ragged 100K corpus)
+        w = total_blocks <= 8 ? 2 : 4;
+        wave_blocks = (total_blocks + w - 1) / w <= 3 ? 3 : 4;
+        shape = 900 + w * 10 + wave_blocks;
     }
     if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 16) {
         // as many workgroups per chunk as 32 queries each would need, then 3 or 4 queries per wavefront so that the

@@ -900,15 +900,25 @@ __device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const 
     }
 }
 
-// NCB: column blocks (queries) per wavefront, 3 or 4: a workgroup holds 24 or 32 queries
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+// NCB: column blocks (queries) per wavefront, 2 to 4; W: wavefronts per workgroup (8: 16 to 32 queries; 4 and 2 give
+//      fewer queries the same 3 or 4 blocks per wavefront, i.e. as many MFMAs per window and barrier)
 // UNI: uniform corpus (documents of l_d tokens, no offsets array)
-template <int DT, int NCB, bool UNI>
-__global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPtr off)
+template <int DT, int NCB, bool UNI, int W = 8>
+__global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, OffsetsPtr off)
 {
     using TR = Traits<DT>;
     using LT = LdsTile<DT>;
     constexpr int NU = TR::NU;
-    constexpr int W = 8, NT = W * 64;
+    constexpr int NT = W * 64;
     static_assert(NU <= 8, "the operand prefetch needs rows of at most 256 bytes");
     constexpr int CPT = (LT::CHUNKS + NT - 1) / NT;
     static_assert(LT::CHUNKS % NT == 0 || LT::CHUNKS < NT, "tile must split evenly over the workgroup");
@@ -966,7 +976,19 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
     if (!win_valid(ci))
         return;
 
-    uint4 g[CPT];
+    static_assert(CPT <= 4, "a thread moves at most four chunks per window");
+    uint4 g0, g1, g2, g3; // the window on its way from HBM; named, not an array: an array of several chunks ends up in scratch memory
+    auto g = [&](auto i) -> uint4 & {
+        constexpr int I = decltype(i)::value;
+        if constexpr (I == 0)
+            return g0;
+        else if constexpr (I == 1)
+            return g1;
+        else if constexpr (I == 2)
+            return g2;
+        else
+            return g3;
+    };
     bool g_has = false;
     auto gload = [&]() {
         g_has = win_valid(li);
@@ -977,21 +999,18 @@ __global__ void __launch_bounds__(512, 2) fwd_pack_kernel(FwdParams p, OffsetsPt
             // window row i holds A's row min(i, n_a - 1) below pa and B's row min(i - pa, n_b - 1) from pa on
             // (without a B that is A's last row again); A and B are neighbours in the packed corpus
             const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i) {
+            static_for<CPT>([&](auto i) {
                 const int wr = cp_row(i);
                 const int row = wr < lw.pa ? min(wr, lw.n_a - 1) : lw.n_a + min(wr - lw.pa, lw.n_b - 1);
-                g[i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff(i));
-            }
+                g(i) = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff(i));
+            });
         }
         win_advance<UNI>(li, lw, p, off);
     };
     auto lstore = [&](int buf_off) {
         if (!g_has || !copies)
             return;
-#pragma unroll
-        for (int i = 0; i < CPT; ++i)
-            *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff(i)]) = g[i];
+        static_for<CPT>([&](auto i) { *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff(i)]) = g(i); });
     };
 
     int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
@@ -1151,13 +1170,13 @@ static hipError_t launch_tile(const FwdParams &p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int DT, int NCB>
+template <int DT, int NCB, int W = 8>
 static hipError_t launch_pack(const FwdParams &p, int grid, hipStream_t stream)
 {
     if (p.offsets)
-        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, false>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
+        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, false, W>), dim3(grid), dim3(W * 64), 0, stream, p, p.offsets);
     else
-        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, true>), dim3(grid), dim3(512), 0, stream, p, p.offsets);
+        hipLaunchKernelGGL((fwd_pack_kernel<DT, NCB, true, W>), dim3(grid), dim3(W * 64), 0, stream, p, p.offsets);
     return hipGetLastError();
 }
 
@@ -1194,8 +1213,14 @@ static hipError_t dispatch_tile(const FwdParams &p, int w, int grid, hipStream_t
                 return launch_pack<DT, 3>(p, grid, s);
             if (w == 94)
                 return launch_pack<DT, 4>(p, grid, s);
-            if (w == 92)
-                return launch_pack<DT, 2>(p, grid, s);
+            if (w == 943)
+                return launch_pack<DT, 3, 4>(p, grid, s);
+            if (w == 944)
+                return launch_pack<DT, 4, 4>(p, grid, s);
+            if (w == 923)
+                return launch_pack<DT, 3, 2>(p, grid, s);
+            if (w == 924)
+                return launch_pack<DT, 4, 2>(p, grid, s);
         }
     }
     switch (w) {

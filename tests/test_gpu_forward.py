@@ -205,7 +205,7 @@ PACK_LENGTHS = {
 
 
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("f32", 64)])
-@pytest.mark.parametrize("n_q,l_q", [(9, 32), (12, 7), (16, 32), (17, 32), (40, 20), (64, 32), (33, 1)])
+@pytest.mark.parametrize("n_q,l_q", [(5, 32), (6, 9), (7, 32), (8, 31), (9, 32), (10, 32), (12, 7), (13, 32), (16, 32), (17, 32), (40, 20), (64, 32), (33, 1)])
 @pytest.mark.parametrize("mix", sorted(PACK_LENGTHS))
 def test_ragged_packed_windows(mix, n_q, l_q, dtype, d):
     lens = np.asarray(PACK_LENGTHS[mix] * 3)
@@ -215,18 +215,20 @@ def test_ragged_packed_windows(mix, n_q, l_q, dtype, d):
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, False, RTOL_F32 if dtype == "f32" else RTOL_16)
 
 
-def test_ragged_packed_windows_many_chunks():
+@pytest.mark.parametrize("n_q", [6, 8, 11, 48])
+def test_ragged_packed_windows_many_chunks(n_q):
     # enough documents that every workgroup gets its own chunk, with chunk borders inside runs of short documents
+    # (workgroups of two, four and eight wavefronts)
     rng = np.random.default_rng(7)
     lens = rng.integers(0, 90, size=6000)
     off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
     Dp = W.unit_rows((int(lens.sum()), 128), "f16", 103, DEV)
-    Q = W.unit_rows((48, 32, 128), "f16", 104, DEV)
+    Q = W.unit_rows((n_q, 32, 128), "f16", 104, DEV)
     forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, False, RTOL_16)
 
 
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 64)])
-@pytest.mark.parametrize("n_q,l_q", [(11, 32), (17, 32), (64, 20)])
+@pytest.mark.parametrize("n_q,l_q", [(5, 32), (8, 32), (11, 32), (14, 3), (17, 32), (64, 20)])
 @pytest.mark.parametrize("b,l_d", [(50, 1), (33, 7), (21, 33), (40, 100), (9, 300), (700, 45)])
 def test_uniform_packed_windows(b, l_d, n_q, l_q, dtype, d):
     """Uniform corpora whose documents are not a whole number of 32-row tiles take the packed windows as well."""

@@ -136,7 +136,10 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     }
     // a ragged corpus (or a uniform one whose documents are not a whole number of tiles) scored by many queries of
     // one block: 32-row windows over the packed rows (no padded tiles at the ends of documents)
-    const bool ragged_ends = ragged || (p.l_d % TILE_ROWS != 0 && p.b * (int64_t)p.l_d < ((int64_t)1 << 31)); // 32-bit packed rows
+    // (the windows also serve uniform corpora of whole tiles at 5-16 queries, where their narrow workgroups beat the
+    // tile kernel's one or two blocks per wavefront by 5-17 %)
+    const bool rows_32bit = ragged || p.b * (int64_t)p.l_d < ((int64_t)1 << 31); // the window iterator counts packed rows in 32 bits
+    const bool ragged_ends = rows_32bit && (ragged || p.l_d % TILE_ROWS != 0 || total_blocks <= 16);
     if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 4 && total_blocks <= 16) {
         // five to sixteen queries: the same windows in workgroups of two (up to 8 queries) or four wavefronts with 3 or 4
         // queries each, so that a wavefront has as many MFMAs per window and barrier as with 32 queries (against two

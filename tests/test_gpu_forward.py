@@ -229,9 +229,10 @@ def test_ragged_packed_windows_many_chunks(n_q):
 
 @pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 64)])
 @pytest.mark.parametrize("n_q,l_q", [(5, 32), (8, 32), (11, 32), (14, 3), (17, 32), (64, 20)])
-@pytest.mark.parametrize("b,l_d", [(50, 1), (33, 7), (21, 33), (40, 100), (9, 300), (700, 45)])
+@pytest.mark.parametrize("b,l_d", [(50, 1), (33, 7), (21, 33), (40, 100), (9, 300), (700, 45), (30, 64), (12, 256), (3000, 32)])
 def test_uniform_packed_windows(b, l_d, n_q, l_q, dtype, d):
-    """Uniform corpora whose documents are not a whole number of 32-row tiles take the packed windows as well."""
+    """Uniform corpora whose documents are not a whole number of 32-row tiles take the packed windows as well, and so
+    do corpora of whole tiles at 5-16 queries."""
     Q = W.unit_rows((n_q, l_q, d), dtype, 111, DEV)
     D = W.unit_rows((b, l_d, d), dtype, 112, DEV)
     forward_parity_uniform(Q, D, M.maxsim_forward, False, RTOL_16)

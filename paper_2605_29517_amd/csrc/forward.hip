@@ -122,7 +122,19 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     else if (total_blocks <= 4 * ncb)
         w = 4;
     int shape = w, wave_blocks = ncb;
-    if (ncb == 4 && total_blocks <= 16) {
+    // Five to sixteen blocks of narrow rows.  What a wavefront spends per tile beside its MFMAs (iterator, copies,
+    // barrier) does not depend on how many blocks it holds, so workgroups of two (up to 8 blocks) or four wavefronts
+    // with four blocks each beat eight wavefronts with one or two blocks by 6-15 % -- as long as there are documents
+    // enough for their many workgroups (at least two per workgroup; a small corpus is a chain of memory latencies
+    // per workgroup, and the shapes below keep several tiles in flight for that).
+    const int narrow_w = total_blocks <= 8 ? 2 : 4;
+    // (fp32 rows carry four times the MFMAs per block: there two wavefronts are 3 % behind four with two blocks each)
+    const bool narrow = ncb == 4 && total_blocks > 4 && total_blocks <= 16 && p.b >= 2 * ((int64_t)num_cu * 16 / narrow_w) &&
+                        !(dtype == MAXSIM_F32 && narrow_w == 2);
+    if (narrow) {
+        w = narrow_w;
+        shape = w;
+    } else if (ncb == 4 && total_blocks <= 16) {
         if (total_blocks <= 8 && !(am && p.bpq > 4)) {
             // four wavefronts with two column blocks each (shape code 42), two workgroups per CU
             wave_blocks = 2;
@@ -137,15 +149,12 @@ hipError_t forward_launch(FwdParams p, int dtype, int d, int num_cu, hipStream_t
     // a ragged corpus (or a uniform one whose documents are not a whole number of tiles) scored by many queries of
     // one block: 32-row windows over the packed rows (no padded tiles at the ends of documents)
     // (the windows also serve uniform corpora of whole tiles at 5-16 queries, where their narrow workgroups beat the
-    // tile kernel's one or two blocks per wavefront by 5-17 %)
+    // tile kernel's by 5-17 %)
     const bool rows_32bit = ragged || p.b * (int64_t)p.l_d < ((int64_t)1 << 31); // the window iterator counts packed rows in 32 bits
     const bool ragged_ends = rows_32bit && (ragged || p.l_d % TILE_ROWS != 0 || total_blocks <= 16);
-    if (ragged_ends && !am && ncb == 4 && p.bpq == 1 && total_blocks > 4 && total_blocks <= 16) {
-        // five to sixteen queries: the same windows in workgroups of two (up to 8 queries) or four wavefronts with 3 or 4
-        // queries each, so that a wavefront has as many MFMAs per window and barrier as with 32 queries (against two
-        // queries on each of eight wavefronts, and against the per-document tiles of shapes 42 / 82: 7-16 % on the
-        // ragged 100K corpus)
-        w = total_blocks <= 8 ? 2 : 4;
+    if (ragged_ends && !am && p.bpq == 1 && narrow) {
+        // five to sixteen queries: the same narrow workgroups with 3 or 4 queries per wavefront (7-16 % over eight
+        // wavefronts with two queries each, and over the per-document tiles, on the ragged 100K corpus)
         wave_blocks = (total_blocks + w - 1) / w <= 3 ? 3 : 4;
         shape = 900 + w * 10 + wave_blocks;
     }

@@ -295,6 +295,39 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p, OffsetsPtr
     }
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+// One of eight named 16-byte registers by compile-time index.  The chunks of a tile on its way from HBM to LDS are
+// kept this way: as an array indexed in unrolled loops inside lambdas they stayed in scratch memory whenever a
+// thread moves more than one chunk per tile.
+template <int I> __device__ __forceinline__ uint4 &reg_at(uint4 &r0, uint4 &r1, uint4 &r2, uint4 &r3, uint4 &r4, uint4 &r5, uint4 &r6, uint4 &r7)
+{
+    static_assert(I >= 0 && I < 8, "eight registers");
+    if constexpr (I == 0)
+        return r0;
+    else if constexpr (I == 1)
+        return r1;
+    else if constexpr (I == 2)
+        return r2;
+    else if constexpr (I == 3)
+        return r3;
+    else if constexpr (I == 4)
+        return r4;
+    else if constexpr (I == 5)
+        return r5;
+    else if constexpr (I == 6)
+        return r6;
+    else
+        return r7;
+}
+
 // ---------------------------------------------------------------------------------------
 // tile kernel: query-stationary workgroup, document tiles staged through LDS
 // ---------------------------------------------------------------------------------------
@@ -498,7 +531,7 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
     const bool copies = LT::CHUNKS >= NT || (int)threadIdx.x < LT::CHUNKS; // narrow rows: fewer chunks than threads
     constexpr int CPR = TR::ROW_BYTES / 16; // chunks per row
     constexpr int GROUP_BLOCKS = W * NCB;
-    constexpr bool PF = NU <= 8 && !ARGMAX; // operands of the next tile prefetched into registers
+    constexpr bool PF = NU <= 8 && !ARGMAX && !(W <= 2 && NCB == 4); // operands of the next tile prefetched into registers (no room for them beside four chunks in flight per thread)
 
     __shared__ __attribute__((aligned(16))) char lds_tile[3 * LT::BYTES];
     __shared__ float lds_part[2][GROUP_BLOCKS];
@@ -575,45 +608,48 @@ __global__ void __launch_bounds__(W * 64, (Traits<DT>::NU <= 8 || W == 8) ? 2 : 
         if (!it_valid(ci))
             break;
 
-        uint4 g[PFD][CPT]; // tiles in flight from HBM: g[0] is the oldest (next to be stored to LDS)
-        bool g_has[PFD];
-#pragma unroll
-        for (int s = 0; s < PFD; ++s)
-            g_has[s] = false;
+        // tiles in flight from HBM: ring slot 0 is the oldest (next to be stored to LDS), bit s of g_mask says that slot s holds a tile
+        constexpr bool NAMED = PFD * CPT <= 8;
+        uint4 g0, g1, g2, g3, g4, g5, g6, g7;
+        uint4 g_arr[NAMED ? 1 : PFD][NAMED ? 1 : CPT]; // workgroups of one wavefront and wide rows: more than eight chunks
+        auto g = [&](auto slot, auto i) -> uint4 & {
+            if constexpr (NAMED)
+                return reg_at<decltype(slot)::value * CPT + decltype(i)::value>(g0, g1, g2, g3, g4, g5, g6, g7);
+            else
+                return g_arr[decltype(slot)::value][decltype(i)::value];
+        };
+        constexpr std::integral_constant<int, 0> OLDEST{};
+        constexpr std::integral_constant<int, PFD - 1> NEWEST{};
+        unsigned g_mask = 0;
         // HBM -> registers (newest ring slot) for the next tile of the stream
         auto gload = [&]() {
-            g_has[PFD - 1] = it_valid(li);
-            if (!g_has[PFD - 1])
+            g_mask &= ~(1u << (PFD - 1));
+            if (!it_valid(li))
                 return;
+            g_mask |= 1u << (PFD - 1);
             if (!copies) {
                 it_next(li, p, off);
                 return;
             }
             int last_row = li.len - li.t0 - 1; // rows past the document re-read its last token
             const char *base = p.D + (int64_t)li.row0 * TR::ROW_BYTES;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i) {
+            static_for<CPT>([&](auto i) {
                 int row = cp_row[i] < last_row ? cp_row[i] : last_row;
-                g[PFD - 1][i] = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
-            }
+                g(NEWEST, i) = *reinterpret_cast<const uint4 *>(base + row * TR::ROW_BYTES + cp_goff[i]);
+            });
             it_next(li, p, off);
         };
         // oldest ring slot -> LDS
         auto lstore = [&](int buf_off) {
-            if (!g_has[0] || !copies)
+            if (!(g_mask & 1u) || !copies)
                 return;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g[0][i];
+            static_for<CPT>([&](auto i) { *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff[i]]) = g(OLDEST, i); });
         };
         auto rotate = [&]() {
-#pragma unroll
-            for (int s = 0; s + 1 < PFD; ++s) {
-                g_has[s] = g_has[s + 1];
-#pragma unroll
-                for (int i = 0; i < CPT; ++i)
-                    g[s][i] = g[s + 1][i];
-            }
+            static_for<PFD - 1>([&](auto slot) {
+                static_for<CPT>([&](auto i) { g(slot, i) = g(std::integral_constant<int, decltype(slot)::value + 1>{}, i); });
+            });
+            g_mask >>= 1;
         };
 
         // LDS buffers (byte offsets): o_cur holds the tile being computed (already in registers),
@@ -900,15 +936,6 @@ __device__ __forceinline__ void win_advance(WinIter &it, const Window &w, const 
     }
 }
 
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
-template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(f);
-        f(std::integral_constant<int, N - 1>{});
-    }
-}
-
 // NCB: column blocks (queries) per wavefront, 2 to 4; W: wavefronts per workgroup (8: 16 to 32 queries; 4 and 2 give
 //      fewer queries the same 3 or 4 blocks per wavefront, i.e. as many MFMAs per window and barrier)
 // UNI: uniform corpus (documents of l_d tokens, no offsets array)
@@ -977,18 +1004,8 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
         return;
 
     static_assert(CPT <= 4, "a thread moves at most four chunks per window");
-    uint4 g0, g1, g2, g3; // the window on its way from HBM; named, not an array: an array of several chunks ends up in scratch memory
-    auto g = [&](auto i) -> uint4 & {
-        constexpr int I = decltype(i)::value;
-        if constexpr (I == 0)
-            return g0;
-        else if constexpr (I == 1)
-            return g1;
-        else if constexpr (I == 2)
-            return g2;
-        else
-            return g3;
-    };
+    uint4 g0, g1, g2, g3, g4, g5, g6, g7; // the window on its way from HBM (see reg_at); four at most are used
+    auto g = [&](auto i) -> uint4 & { return reg_at<decltype(i)::value>(g0, g1, g2, g3, g4, g5, g6, g7); };
     bool g_has = false;
     auto gload = [&]() {
         g_has = win_valid(li);

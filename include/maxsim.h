@@ -26,8 +26,9 @@
  *       backward (maxsim_backward, _ragged, _csr, _csr_static): any multiple of 8 from 8 to 8192; Q must stay
  *         below 4 GiB and D below 64 GiB.
  *       int8 entry points and the quantiser: any multiple of 32 from 32 to 8192.  d = 128 takes the tuned kernels
- *         (queries resident in LDS or registers); other widths a plain inner loop over d with the same arithmetic
- *         and the same bits, at a fraction of the speed.
+ *         (queries resident in LDS or registers); other multiples of 64 stream both operands in slabs like the
+ *         float forward; the remaining widths take a plain inner loop over d at a fraction of the speed.  The same
+ *         arithmetic and the same bits everywhere.
  *     Other widths must be zero-padded by the caller; anything else returns MAXSIM_ERR_UNSUPPORTED.
  *   - Four kernel families use more than 64 KB of LDS, which HIP wants allowed per kernel and device before the
  *     first launch.  maxsim_init() does that (and all other per-device set-up) for the current device; an entry

@@ -17,6 +17,12 @@
 // tokens exactly as in the other kernels (documents on the MFMA rows, so the max is in-lane), and at the
 // end of a document the block sums are combined in block order.  A macro tile never spans two documents
 // (rows past the end re-read the document's last token).
+//
+// The same kernel scores int8 codes (Alg. 4 at embedding widths other than 128): element "type" SD_I8 runs the
+// contraction with v_mfma_i32_32x32x32_i8 on the same 16-byte chunks into exact int32 accumulators (kept in the
+// float accumulator registers bit for bit), and the fold after the last slab applies the document token's scale
+// with a single rounding, v = fl32(n * d_scale[j]); at the end of a document r_i = fl32(q_scale[i] * max) and the
+// sum over the query's tokens is carried in fp64 and rounded once: the oracle's bits.
 #include "forward_impl.h"
 
 #include <type_traits>
@@ -35,7 +41,12 @@ constexpr int SD_BUF = (SD_ROWS_A + SD_ROWS_B) * SD_SLAB; // one slab of both op
 constexpr int SD_CP_ROWS = SD_W * 64 / 4;                // rows covered by one copy instruction of the workgroup (4 chunks per row)
 constexpr int SD_NG = (SD_ROWS_A + SD_ROWS_B) / SD_CP_ROWS; // 16-byte chunks a thread moves per slab
 constexpr int SD_NGA = SD_ROWS_A / SD_CP_ROWS;            // ... of which document rows
-constexpr int SD_LDS = 3 * SD_BUF + 2 * SD_GROUP_BLOCKS * (int)sizeof(float);
+constexpr int SD_LDS = 3 * SD_BUF + 2 * SD_GROUP_BLOCKS * (int)sizeof(double); // + per-block sums of two documents in turn
+constexpr int SD_I8 = 3;                                 // element type code of int8 codes (beside maxsim_dtype's 0, 1, 2)
+// int8 queries of 17-32 blocks take two passes over a chunk; the fp64 sum of a document's first pass waits in LDS
+// for the second (a float in `scores` would round twice): one slot per non-empty document of the chunk
+constexpr int SD_I8_CARRY_DOCS = 4096;
+constexpr int SD_LDS_I8 = SD_LDS + SD_I8_CARRY_DOCS * (int)sizeof(double);
 
 // One MFMA step (k = 16 for 16-bit inputs; a 16-byte chunk of fp32 is four steps of k = 2).
 template <int DT> __device__ __forceinline__ void sd_mma(const i32x4 &a, const i32x4 &b, f32x16 &c)
@@ -44,6 +55,8 @@ template <int DT> __device__ __forceinline__ void sd_mma(const i32x4 &a, const i
         c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     } else if constexpr (DT == MAXSIM_BF16) {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else if constexpr (DT == SD_I8) { // 16 bytes = 16 codes per lane: k = 32 with both lane halves; int32 sums in c's bits
+        c = __builtin_bit_cast(f32x16, __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, __builtin_bit_cast(i32x16, c), 0, 0, 0));
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -51,11 +64,19 @@ template <int DT> __device__ __forceinline__ void sd_mma(const i32x4 &a, const i
     }
 }
 
+// n * s rounded once to fp32: the product of an int32 below 2^29 in magnitude and an fp32 is exact in fp64
+// (|n| <= 127^2 * 8192 < 2^27 here, so 27 + 24 bits)
+__device__ __forceinline__ float sd_scaled_once(int n, float s) { return (float)((double)n * (double)s); }
+
+// q_scale [n_q, l_q] and d_scale [b, l_d] or [T]: the per-token scales of int8 codes (DT == SD_I8), else unused
 template <int DT, bool ARGMAX>
-__global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, OffsetsPtr off, int row_bytes)
+__global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, OffsetsPtr off, int row_bytes, const float *q_scale, const float *d_scale)
 {
+    static_assert(!(DT == SD_I8 && ARGMAX), "int8 scoring has no argmax output");
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    float *lds_part = reinterpret_cast<float *>(lds + 3 * SD_BUF); // [2][SD_GROUP_BLOCKS]
+    float *lds_part = reinterpret_cast<float *>(lds + 3 * SD_BUF);    // [2][SD_GROUP_BLOCKS]
+    double *lds_part_d = reinterpret_cast<double *>(lds + 3 * SD_BUF); // the same for int8: sums in fp64
+    double *lds_carry = reinterpret_cast<double *>(lds + SD_LDS);      // int8 only: [SD_I8_CARRY_DOCS]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -128,6 +149,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
         bool col_valid[SD_NCB];
         float m[SD_NCB];
         int idx[SD_NCB];
+        float qsc[SD_NCB]; // int8: the scale of this lane's query token
 #pragma unroll
         for (int cb = 0; cb < SD_NCB; ++cb) {
             int lb = w * SD_NCB + cb;
@@ -136,8 +158,13 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
             col_valid[cb] = lb < nb && gb < total_blocks && tok < p.l_q;
             m[cb] = neg_inf();
             idx[cb] = 0;
+            qsc[cb] = 0.0f;
+            if constexpr (DT == SD_I8)
+                if (col_valid[cb])
+                    qsc[cb] = q_scale[(int64_t)(gb / p.bpq) * p.l_q + tok];
         }
         const bool wave_active = w * SD_NCB < nb;
+        int fin_count = 0; // documents finished in this pass (the same sequence in every pass)
 
         TileIter li, ci; // loader (four slabs ahead at steady state) and compute position
         int lks = 0, cks = 0;
@@ -315,14 +342,38 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
                 int fin_doc = -1;
                 if (advance_compute()) {
                     // macro tile complete: fold its eight result tiles, rows ascending (first occurrence wins)
-#pragma unroll
-                    for (int c = 0; c < SD_NCB; ++c) {
+                    if constexpr (DT == SD_I8) {
+                        // v = fl32(n * d_scale[row]) per cell; rows past the document's end hold its last token again
+                        // (an fp32 product would do up to d = 1024, where |n| < 2^24; as a second variant of this fold it
+                        // cost registers in the slab loop and was 20-60 % slower overall)
+                        const int last = ci.len - ci.t0 - 1;
 #pragma unroll
                         for (int t = 0; t < SD_MT; ++t) {
-                            fold_tile<ARGMAX>(acc[t][c], m[c], idx[c], ci.t0 + t * TILE_ROWS, h);
+                            float sc[16];
 #pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                acc[t][c][r] = 0.0f;
+                            for (int r = 0; r < 16; ++r) {
+                                const int row = t * TILE_ROWS + acc_row(r, h);
+                                sc[r] = d_scale[(int64_t)ci.row0 + (row < last ? row : last)];
+                            }
+#pragma unroll
+                            for (int c = 0; c < SD_NCB; ++c) {
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) {
+                                    m[c] = fmaxf(m[c], sd_scaled_once(__float_as_int(acc[t][c][r]), sc[r]));
+                                    acc[t][c][r] = 0.0f;
+                                }
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < SD_NCB; ++c) {
+#pragma unroll
+                            for (int t = 0; t < SD_MT; ++t) {
+                                fold_tile<ARGMAX>(acc[t][c], m[c], idx[c], ci.t0 + t * TILE_ROWS, h);
+#pragma unroll
+                                for (int r = 0; r < 16; ++r)
+                                    acc[t][c][r] = 0.0f;
+                            }
                         }
                     }
                     if (ci.t0 + SD_ROWS_A >= ci.len) { // last macro tile of its document
@@ -330,13 +381,31 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
 #pragma unroll
                         for (int cb = 0; cb < SD_NCB; ++cb) {
                             int lb = w * SD_NCB + cb;
-                            float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
-                            if (lane == 0) {
-                                if (direct) {
-                                    if (lb < nb)
-                                        p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
-                                } else {
-                                    lds_part[par * SD_GROUP_BLOCKS + lb] = sum;
+                            if constexpr (DT == SD_I8) {
+                                // the two lane halves hold the same column: merge, one IEEE fp32 multiply by the
+                                // query token's scale, the 32 columns added up in fp64
+                                const float mm = fmaxf(m[cb], __shfl_xor(m[cb], 32));
+                                double dv = col_valid[cb] ? (double)(qsc[cb] * mm) : 0.0;
+#pragma unroll
+                                for (int o = 16; o > 0; o >>= 1)
+                                    dv += __shfl_xor(dv, o);
+                                if (lane == 0) {
+                                    if (direct) {
+                                        if (lb < nb)
+                                            p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = (float)dv;
+                                    } else {
+                                        lds_part_d[par * SD_GROUP_BLOCKS + lb] = dv;
+                                    }
+                                }
+                            } else {
+                                float sum = finish_block<ARGMAX>(p, m[cb], idx[cb], col_valid[cb], gb0 + lb, ci.doc, ci.len, rho, h);
+                                if (lane == 0) {
+                                    if (direct) {
+                                        if (lb < nb)
+                                            p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
+                                    } else {
+                                        lds_part[par * SD_GROUP_BLOCKS + lb] = sum;
+                                    }
                                 }
                             }
                             m[cb] = neg_inf();
@@ -348,15 +417,29 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
                 __syncthreads();
                 if (fin_doc >= 0) {
                     if (!direct && tid < nq) { // thread t adds up the blocks of its query in block order
-                        float sum = 0.0f;
                         int first_blk = (p.n_pass == 1) ? tid * p.bpq : 0;
                         int cnt = (p.n_pass == 1) ? p.bpq : nb;
-                        for (int i = 0; i < cnt; ++i)
-                            sum += lds_part[par * SD_GROUP_BLOCKS + first_blk + i];
                         float *dst = p.scores + (int64_t)(q_first + tid) * p.ld + fin_doc;
-                        *dst = accumulate ? *dst + sum : sum;
+                        if constexpr (DT == SD_I8) { // fp64 sum over all tokens of the query, rounded once
+                            double sum = 0.0;
+                            for (int i = 0; i < cnt; ++i)
+                                sum += lds_part_d[par * SD_GROUP_BLOCKS + first_blk + i];
+                            if (p.n_pass > 1 && fin_count < SD_I8_CARRY_DOCS) { // (the host sizes chunks to that many documents)
+                                if (accumulate)
+                                    sum += lds_carry[fin_count];
+                                lds_carry[fin_count] = sum;
+                            }
+                            if (pass == p.n_pass - 1)
+                                *dst = (float)sum;
+                        } else {
+                            float sum = 0.0f;
+                            for (int i = 0; i < cnt; ++i)
+                                sum += lds_part[par * SD_GROUP_BLOCKS + first_blk + i];
+                            *dst = accumulate ? *dst + sum : sum;
+                        }
                     }
                     par ^= 1;
+                    ++fin_count;
                 }
                 rotate_buffers();
             };
@@ -376,14 +459,15 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
 template <int DT, bool ARGMAX>
 hipError_t launch_splitd(const FwdParams &p, int row_bytes, int grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((fwd_splitd_kernel<DT, ARGMAX>), dim3(grid), dim3(SD_W * 64), SD_LDS, stream, p, p.offsets, row_bytes);
+    hipLaunchKernelGGL((fwd_splitd_kernel<DT, ARGMAX>), dim3(grid), dim3(SD_W * 64), SD_LDS, stream, p, p.offsets, row_bytes,
+                       static_cast<const float *>(nullptr), static_cast<const float *>(nullptr));
     return hipGetLastError();
 }
 
 template <int DT, bool ARGMAX> hipError_t allow_splitd_lds()
 {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(&fwd_splitd_kernel<DT, ARGMAX>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, SD_LDS);
+                               hipFuncAttributeMaxDynamicSharedMemorySize, DT == SD_I8 ? SD_LDS_I8 : SD_LDS);
 }
 
 } // namespace
@@ -395,18 +479,17 @@ hipError_t forward_splitd_init_device()
     hipError_t e = hipSuccess;
     if ((e = allow_splitd_lds<MAXSIM_F32, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_F32, true>()) != hipSuccess ||
         (e = allow_splitd_lds<MAXSIM_F16, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_F16, true>()) != hipSuccess ||
-        (e = allow_splitd_lds<MAXSIM_BF16, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_BF16, true>()) != hipSuccess)
+        (e = allow_splitd_lds<MAXSIM_BF16, false>()) != hipSuccess || (e = allow_splitd_lds<MAXSIM_BF16, true>()) != hipSuccess ||
+        (e = allow_splitd_lds<SD_I8, false>()) != hipSuccess)
         return e;
     return hipSuccess;
 }
 
-// Any row width that is a multiple of 64 bytes.  `num_cu` is the device's CU count.
-hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_cu, hipStream_t stream)
+// The work split of the slab kernel: column groups of up to 16 blocks, document chunks.  Returns the grid size.
+// max_chunk_docs > 0: no chunk may hold more non-empty documents than that.
+static int64_t splitd_plan(FwdParams &p, int num_cu, int max_chunk_docs = 0)
 {
-    if (row_bytes < SD_SLAB || row_bytes % SD_SLAB != 0)
-        return hipErrorNotSupported;
     const bool ragged = p.offsets != nullptr;
-    const bool am = p.argmax != nullptr;
     p.bpq = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS;
     if (p.ld == 0)
         p.ld = p.b;
@@ -427,12 +510,26 @@ hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_
     int64_t n_chunks = ((int64_t)num_cu * 4 + p.n_groups - 1) / p.n_groups;
     if (n_chunks > p.b)
         n_chunks = p.b;
+    if (max_chunk_docs > 0) { // a chunk of u tokens (ragged) or u documents holds at most u non-empty documents
+        const int64_t need = (units + max_chunk_docs - 1) / max_chunk_docs;
+        if (n_chunks < need)
+            n_chunks = need;
+    }
     n_chunks = (n_chunks + 7) / 8 * 8;
     p.unit_per_chunk = (units + n_chunks - 1) / n_chunks;
     if (p.unit_per_chunk < 1)
         p.unit_per_chunk = 1;
     p.n_chunks = (int)n_chunks;
-    const int grid = p.n_groups * p.n_chunks;
+    return (int64_t)p.n_groups * n_chunks;
+}
+
+// Any row width that is a multiple of 64 bytes.  `num_cu` is the device's CU count.
+hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_cu, hipStream_t stream)
+{
+    if (row_bytes < SD_SLAB || row_bytes % SD_SLAB != 0)
+        return hipErrorNotSupported;
+    const bool am = p.argmax != nullptr;
+    const int grid = (int)splitd_plan(p, num_cu);
     switch (dtype) {
     case MAXSIM_F32:
         return am ? launch_splitd<MAXSIM_F32, true>(p, row_bytes, grid, stream) : launch_splitd<MAXSIM_F32, false>(p, row_bytes, grid, stream);
@@ -441,6 +538,23 @@ hipError_t forward_splitd_launch(FwdParams p, int dtype, int row_bytes, int num_
     default:
         return am ? launch_splitd<MAXSIM_BF16, true>(p, row_bytes, grid, stream) : launch_splitd<MAXSIM_BF16, false>(p, row_bytes, grid, stream);
     }
+}
+
+// int8 codes with per-token scales through the slab kernel: widths that are a multiple of 64 and queries of up to
+// 1024 tokens (up to 512: whole queries per workgroup; beyond: two passes with the fp64 carry in LDS)
+bool forward_splitd_i8_ok(int l_q, int d) { return d >= SD_SLAB && d % SD_SLAB == 0 && (l_q + BLOCK_COLS - 1) / BLOCK_COLS <= 2 * SD_GROUP_BLOCKS; }
+
+hipError_t forward_splitd_i8_launch(FwdParams p, const float *q_scale, const float *d_scale, int d, int num_cu, hipStream_t stream)
+{
+    if (!forward_splitd_i8_ok(p.l_q, d) || p.argmax != nullptr)
+        return hipErrorNotSupported;
+    const bool two_pass = (p.l_q + BLOCK_COLS - 1) / BLOCK_COLS > SD_GROUP_BLOCKS;
+    const int64_t grid = splitd_plan(p, num_cu, two_pass ? SD_I8_CARRY_DOCS : 0);
+    if (grid >= (int64_t(1) << 31))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fwd_splitd_kernel<SD_I8, false>), dim3((unsigned)grid), dim3(SD_W * 64), two_pass ? SD_LDS_I8 : SD_LDS, stream, p,
+                       p.offsets, d, q_scale, d_scale);
+    return hipGetLastError();
 }
 
 } // namespace maxsim

@@ -4,9 +4,10 @@
 // contraction walks d in steps of 32 bytes -- the inner loop over d of App. "split-d" with an exact int32
 // accumulator -- and the arithmetic after it is the same: v = fl32(n * d_scale[j]) per cell, the maximum over the
 // document's tokens, r_i = fl32(q_scale[i] * max), the sum over the query's tokens carried in fp64 and rounded
-// once.  The same bits as the oracle's definition.  Not tuned: every wavefront re-reads its query blocks' bytes
-// from the caches for every step of 32 or 64 document tokens, which holds long queries at about 9 % of the int8
-// MFMA peak (a slab kernel through LDS like the float one's would be the next step).
+// once.  The same bits as the oracle's definition.  Widths that are a multiple of 64 are scored by the slab kernel
+// of forward_splitd.hip (both operands through LDS, the same arithmetic after the contraction); the kernel below
+// serves the other multiples of 32 and is not tuned: every wavefront re-reads its query blocks' bytes from the
+// caches for every step of 32 or 64 document tokens, which holds long queries at about 9 % of the int8 MFMA peak.
 #include "common.h"
 
 namespace maxsim {
@@ -242,10 +243,30 @@ __global__ void __launch_bounds__(256) quantize_rows_wide_kernel(const char *X, 
 
 bool i8_wide_width_ok(int d) { return d >= 32 && d <= 8192 && d % 32 == 0; }
 
+bool forward_splitd_i8_ok(int l_q, int d);
+hipError_t forward_splitd_i8_launch(FwdParams p, const float *q_scale, const float *d_scale, int d, int num_cu, hipStream_t stream);
+
 hipError_t forward_i8_wide_launch(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                                   const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, int d, float *scores,
                                   int64_t ld, int num_cu, hipStream_t stream)
 {
+    // widths that are a multiple of 64: the slab kernel through LDS (3 x this one on long queries; up to four column
+    // blocks of rows of up to 256 bytes are faster here: 0.14 against 0.20 ms for 32 tokens on 1000 pages at d = 256)
+    const bool few_narrow = d <= 256 && (int64_t)n_q * ((l_q + BLOCK_COLS - 1) / BLOCK_COLS) <= I8W_NB;
+    if (forward_splitd_i8_ok(l_q, d) && !few_narrow) {
+        FwdParams f{};
+        f.Q = reinterpret_cast<const char *>(Q);
+        f.D = reinterpret_cast<const char *>(D);
+        f.offsets = offsets;
+        f.scores = scores;
+        f.b = b;
+        f.ld = ld;
+        f.total_tokens = total_tokens;
+        f.n_q = n_q;
+        f.l_q = l_q;
+        f.l_d = l_d;
+        return forward_splitd_i8_launch(f, qs, ds, d, num_cu, stream);
+    }
     I8WideParams P;
     P.Q = reinterpret_cast<const char *>(Q);
     P.qs = qs;

@@ -224,7 +224,8 @@ def test_forward_i8_shared_documents_negative_maxima():
     assert float(s[0, 0]) < 0 < float(s[0, 1])
 
 
-# ---- embedding widths other than 128 (every multiple of 32 up to 8192): the plain inner loop over d ----
+# ---- embedding widths other than 128 (every multiple of 32 up to 8192): the slab kernel (multiples of 64) and the
+# plain inner loop over d ----
 
 WIDE_D = [32, 64, 96, 256, 320, 768, 1024, 2048]
 
@@ -269,7 +270,8 @@ def test_forward_i8_other_widths_bit_exact(shape, d):
     assert np.array_equal(bits(s.cpu().numpy()), bits(ref))
 
 
-@pytest.mark.parametrize("case", [(1, 1024, 3, 70, 256), (2, 700, 2100, 40, 64), (5, 300, 6, 130, 768)])
+# (the last case: two passes over chunks of more than a thousand documents each, whose first-pass sums wait in LDS)
+@pytest.mark.parametrize("case", [(1, 1024, 3, 70, 256), (2, 700, 2100, 40, 64), (5, 300, 6, 130, 768), (1, 600, 1200000, 1, 64)])
 def test_forward_i8_other_widths_long_queries_and_many_documents(case):
     n_q, l_q, b, l_d, d = case
     g, o = wide_case(n_q, l_q, b, l_d, d, 77)
@@ -297,11 +299,12 @@ def test_forward_i8_other_widths_extreme_codes():
     assert float(s[0, 0]) < 0 < float(s[0, 1])
 
 
+@pytest.mark.parametrize("n_q,l_q", [(3, 40), (2, 700)])
 @pytest.mark.parametrize("d", [64, 256, 1024])
-def test_forward_i8_ragged_other_widths_bit_exact(d):
+def test_forward_i8_ragged_other_widths_bit_exact(d, n_q, l_q):
     lens = np.asarray([5, 0, 64, 65, 1, 130, 0, 33, 0], dtype=np.int64)
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-    Qf = W.unit_rows((3, 40, d), "f16", 500 + d, DEV)
+    Qf = W.unit_rows((n_q, l_q, d), "f16", 500 + d, DEV)
     Df = W.unit_rows((int(off[-1]), d), "f32", 501 + d, DEV)
     oq, oqs = O.quantize_rows_i8(W.to_raw_numpy(Qf), "f16")
     od, ods = O.quantize_rows_i8(W.to_raw_numpy(Df), "f32")

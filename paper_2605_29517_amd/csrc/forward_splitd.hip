@@ -46,7 +46,10 @@ constexpr int SD_I8 = 3;                                 // element type code of
 // int8 queries of 17-32 blocks take two passes over a chunk; the fp64 sum of a document's first pass waits in LDS
 // for the second (a float in `scores` would round twice): one slot per non-empty document of the chunk
 constexpr int SD_I8_CARRY_DOCS = 4096;
-constexpr int SD_LDS_I8 = SD_LDS + SD_I8_CARRY_DOCS * (int)sizeof(double);
+// the scales of a macro tile's 128 document tokens travel with its first slab into one of four LDS buffers (a tile's
+// slab is stored up to two tiles before the tile is folded)
+constexpr int SD_I8_SC_BUFS = 4;
+constexpr int SD_LDS_I8 = SD_LDS + SD_I8_CARRY_DOCS * (int)sizeof(double) + SD_I8_SC_BUFS * SD_ROWS_A * (int)sizeof(float);
 
 // One MFMA step (k = 16 for 16-bit inputs; a 16-byte chunk of fp32 is four steps of k = 2).
 template <int DT> __device__ __forceinline__ void sd_mma(const i32x4 &a, const i32x4 &b, f32x16 &c)
@@ -77,6 +80,7 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
     float *lds_part = reinterpret_cast<float *>(lds + 3 * SD_BUF);    // [2][SD_GROUP_BLOCKS]
     double *lds_part_d = reinterpret_cast<double *>(lds + 3 * SD_BUF); // the same for int8: sums in fp64
     double *lds_carry = reinterpret_cast<double *>(lds + SD_LDS);      // int8 only: [SD_I8_CARRY_DOCS]
+    float *lds_sc = reinterpret_cast<float *>(lds + SD_LDS + SD_I8_CARRY_DOCS * sizeof(double)); // int8 only: [SD_I8_SC_BUFS][SD_ROWS_A]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -179,11 +183,15 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
         int64_t s_row0 = 0;
         const char *a_base = nullptr;
         int64_t q_add = 0;
+        bool s_new_tile = false; // the loader's slab is the first of a macro tile
+        int l_tile = 0, c_tile = 0; // macro tiles begun by the loader / folded, modulo SD_I8_SC_BUFS
         auto gaddr = [&]() {
+            s_new_tile = false;
             if (it_valid(li)) {
                 s_row0 = li.row0;
                 s_last = li.len - li.t0 - 1;
                 s_ks = lks;
+                s_new_tile = lks == 0;
                 if (++lks == n_slabs) {
                     lks = 0;
                     it_next(li, p, off, SD_ROWS_A);
@@ -195,13 +203,25 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
         // two register sets of staged slabs; which one is a compile-time choice (the two copies of the loop body
         // must not be merged into one that selects a set through a pointer)
         i32x4 g[2][SD_NG];
+        float g_sc[2] = {0.0f, 0.0f}; // int8: the scale of document row r0 of a macro tile, in flight with its first slab
+        int g_sc_buf[2] = {-1, -1};   // ... and the LDS buffer it goes to (-1: this set carries none)
         constexpr std::integral_constant<int, 0> g0{};
         constexpr std::integral_constant<int, 1> g1{};
+        static_assert(DT != SD_I8 || SD_NGA == 1, "one copy instruction of the workgroup covers a macro tile's rows");
         auto gload1 = [&](auto set, int k) {
             i32x4(&gs)[SD_NG] = g[decltype(set)::value];
             if (k < SD_NGA) {
                 int row = min(r0 + SD_CP_ROWS * k, s_last);
                 gs[k] = *reinterpret_cast<const i32x4 *>(a_base + (int64_t)row * row_bytes);
+                if constexpr (DT == SD_I8) {
+                    g_sc_buf[decltype(set)::value] = -1;
+                    if (s_new_tile) {
+                        g_sc_buf[decltype(set)::value] = l_tile;
+                        l_tile = (l_tile + 1) & (SD_I8_SC_BUFS - 1);
+                        if (cc == 0)
+                            g_sc[decltype(set)::value] = d_scale[s_row0 + row];
+                    }
+                }
             } else {
                 gs[k] = *reinterpret_cast<const i32x4 *>(p.Q + qoff[k - SD_NGA] + q_add);
             }
@@ -209,6 +229,10 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
         auto lstore1 = [&](auto set, int k, int buf_off) {
             const i32x4(&gs)[SD_NG] = g[decltype(set)::value];
             *reinterpret_cast<i32x4 *>(&lds[buf_off + w_off + k * (SD_CP_ROWS * SD_SLAB)]) = gs[k];
+            if constexpr (DT == SD_I8) {
+                if (k == 0 && g_sc_buf[decltype(set)::value] >= 0 && cc == 0)
+                    lds_sc[g_sc_buf[decltype(set)::value] * SD_ROWS_A + r0] = g_sc[decltype(set)::value];
+            }
         };
 
         int o_cur = 0, o_nxt = SD_BUF, o_wr = 2 * SD_BUF;
@@ -345,22 +369,25 @@ __global__ void __launch_bounds__(SD_W * 64) fwd_splitd_kernel(FwdParams p, Offs
                     if constexpr (DT == SD_I8) {
                         // v = fl32(n * d_scale[row]) per cell; rows past the document's end hold its last token again
                         // (an fp32 product would do up to d = 1024, where |n| < 2^24; as a second variant of this fold it
-                        // cost registers in the slab loop and was 20-60 % slower overall)
-                        const int last = ci.len - ci.t0 - 1;
+                        // cost registers in the slab loop and was slower).  The scales came into LDS with the tile's first slab.
+                        const float *sc_tile = lds_sc + c_tile * SD_ROWS_A;
+                        c_tile = (c_tile + 1) & (SD_I8_SC_BUFS - 1);
 #pragma unroll
                         for (int t = 0; t < SD_MT; ++t) {
-                            float sc[16];
 #pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int row = t * TILE_ROWS + acc_row(r, h);
-                                sc[r] = d_scale[(int64_t)ci.row0 + (row < last ? row : last)];
-                            }
+                            for (int q4 = 0; q4 < 4; ++q4) { // accumulator registers 4 q4 .. 4 q4 + 3 hold rows 8 q4 + 4 h .. + 3
+                                const float4 sc = *reinterpret_cast<const float4 *>(sc_tile + t * TILE_ROWS + q4 * 8 + h * 4);
 #pragma unroll
-                            for (int c = 0; c < SD_NCB; ++c) {
+                                for (int c = 0; c < SD_NCB; ++c) {
+                                    float v = m[c];
+                                    v = fmaxf(v, sd_scaled_once(__float_as_int(acc[t][c][4 * q4 + 0]), sc.x));
+                                    v = fmaxf(v, sd_scaled_once(__float_as_int(acc[t][c][4 * q4 + 1]), sc.y));
+                                    v = fmaxf(v, sd_scaled_once(__float_as_int(acc[t][c][4 * q4 + 2]), sc.z));
+                                    v = fmaxf(v, sd_scaled_once(__float_as_int(acc[t][c][4 * q4 + 3]), sc.w));
+                                    m[c] = v;
 #pragma unroll
-                                for (int r = 0; r < 16; ++r) {
-                                    m[c] = fmaxf(m[c], sd_scaled_once(__float_as_int(acc[t][c][r]), sc[r]));
-                                    acc[t][c][r] = 0.0f;
+                                    for (int j = 0; j < 4; ++j)
+                                        acc[t][c][4 * q4 + j] = 0.0f;
                                 }
                             }
                         }
@@ -552,8 +579,8 @@ hipError_t forward_splitd_i8_launch(FwdParams p, const float *q_scale, const flo
     const int64_t grid = splitd_plan(p, num_cu, two_pass ? SD_I8_CARRY_DOCS : 0);
     if (grid >= (int64_t(1) << 31))
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_splitd_kernel<SD_I8, false>), dim3((unsigned)grid), dim3(SD_W * 64), two_pass ? SD_LDS_I8 : SD_LDS, stream, p,
-                       p.offsets, d, q_scale, d_scale);
+    hipLaunchKernelGGL((fwd_splitd_kernel<SD_I8, false>), dim3((unsigned)grid), dim3(SD_W * 64), SD_LDS_I8, stream, p, p.offsets, d, q_scale,
+                       d_scale);
     return hipGetLastError();
 }
 

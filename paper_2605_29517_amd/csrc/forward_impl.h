@@ -295,39 +295,6 @@ __global__ void __launch_bounds__(256) fwd_stream_kernel(FwdParams p, OffsetsPtr
     }
 }
 
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in this order
-template <int N, class F> __device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(f);
-        f(std::integral_constant<int, N - 1>{});
-    }
-}
-
-// One of eight named 16-byte registers by compile-time index.  The chunks of a tile on its way from HBM to LDS are
-// kept this way: as an array indexed in unrolled loops inside lambdas they stayed in scratch memory whenever a
-// thread moves more than one chunk per tile.
-template <int I> __device__ __forceinline__ uint4 &reg_at(uint4 &r0, uint4 &r1, uint4 &r2, uint4 &r3, uint4 &r4, uint4 &r5, uint4 &r6, uint4 &r7)
-{
-    static_assert(I >= 0 && I < 8, "eight registers");
-    if constexpr (I == 0)
-        return r0;
-    else if constexpr (I == 1)
-        return r1;
-    else if constexpr (I == 2)
-        return r2;
-    else if constexpr (I == 3)
-        return r3;
-    else if constexpr (I == 4)
-        return r4;
-    else if constexpr (I == 5)
-        return r5;
-    else if constexpr (I == 6)
-        return r6;
-    else
-        return r7;
-}
-
 // ---------------------------------------------------------------------------------------
 // tile kernel: query-stationary workgroup, document tiles staged through LDS
 // ---------------------------------------------------------------------------------------

@@ -43,8 +43,9 @@ struct I8Params {
     FwdParams f;        // sizes, optional offsets and the work split
 };
 
+// (four wavefronts: asked to fit two per SIMD, which they do without spilling; one or two run faster unconstrained)
 template <int W>
-__global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P, OffsetsPtr off)
+__global__ void __launch_bounds__(W * 64, W >= 4 ? 2 : 1) fwd_i8_kernel(I8Params P, OffsetsPtr off)
 {
     const FwdParams &p = P.f;
     constexpr int NT = W * 64;
@@ -110,17 +111,18 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P, OffsetsPtr o
 
     Cursor lc;
     cursor_init(lc, p, off, doc0, doc1);
-    uint4 g[CPT];
+    static_assert(CPT <= 8, "eight named registers hold a thread's share of a tile");
+    uint4 g0, g1, g2, g3, g4, g5, g6, g7; // (named: see reg_at)
+    auto g = [&](auto i) -> uint4 & { return reg_at<decltype(i)::value>(g0, g1, g2, g3, g4, g5, g6, g7); };
     float gs = 0.0f;
     auto gload = [&](const Cursor &c) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
+        static_for<CPT>([&](auto i) {
             int ch = tid + i * NT;
             int row = c.t0 + ch / CPR;
             if (row > c.len - 1)
                 row = c.len - 1;
-            g[i] = *reinterpret_cast<const uint4 *>(P.D + (c.start + row) * I8_ROW_BYTES + (ch % CPR) * 16);
-        }
+            g(i) = *reinterpret_cast<const uint4 *>(P.D + (c.start + row) * I8_ROW_BYTES + (ch % CPR) * 16);
+        });
         if (tid < I8_TILE_ROWS) {
             int row = c.t0 + tid;
             if (row > c.len - 1)
@@ -129,11 +131,10 @@ __global__ void __launch_bounds__(W * 64) fwd_i8_kernel(I8Params P, OffsetsPtr o
         }
     };
     auto lstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < CPT; ++i) {
+        static_for<CPT>([&](auto i) {
             int ch = tid + i * NT;
-            *reinterpret_cast<uint4 *>(&lds_tile[buf][(ch / CPR) * I8_ROW_STRIDE + (ch % CPR) * 16]) = g[i];
-        }
+            *reinterpret_cast<uint4 *>(&lds_tile[buf][(ch / CPR) * I8_ROW_STRIDE + (ch % CPR) * 16]) = g(i);
+        });
         if (tid < I8_TILE_ROWS) {
             lds_scale[buf][tid] = gs;
             lds_bias[buf][tid] = gs * -8388608.0f;

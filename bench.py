@@ -331,9 +331,9 @@ def main():
             w, a, m, mn = time_launches(lambda: M.maxsim_forward(Qw, Dw, scores=sw), 50, 5)
             small.append({"d": dw, "ms": round(w, 4), "kernel_ms": stats()})
             del Qw, Dw, sw
-        # int8 at the same widths (the plain, untuned inner loop over d; d = 128 is config 5): a quarter of the pages
+        # int8 at the same widths and page counts (the slab kernel with i8 MFMAs; d = 128 is config 5)
         wide8 = []
-        for dw, ndw in ((256, 500), (512, 250), (1024, 125), (2048, 64)):
+        for dw, ndw in ((256, 2000), (512, 1000), (1024, 500), (2048, 250)):
             q8w, qsw = M.maxsim_quantize_rows_i8(W.unit_rows((4, 1024, dw), "f16", 95, dev))
             d8w, dsw = M.maxsim_quantize_rows_i8(W.unit_rows((ndw, 1024, dw), "bf16", 96, dev))
             sw = torch.empty(4, ndw, dtype=torch.float32, device=dev)

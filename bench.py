@@ -239,10 +239,23 @@ def main():
         Q1 = Q[:1].contiguous()
         s1 = torch.empty(1, n_docs, dtype=torch.float32, device=dev)
         w, a, m, mn = time_launches(lambda: M.maxsim_forward_ragged(Q1, Dp, off, total_tokens=T, scores=s1), 50, 5)
-        extra.append({"leg": "c2_nq1", "workload": "configs[1] single-query slice (N_q=1): the streaming, HBM-bound regime",
-                      "kernel_ms": stats(), "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
-                      "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 2, True), a, PEAK_HBM_GBS, "GB/s", "c2_nq1")})
+        leg_nq1 = {"leg": "c2_nq1", "workload": "configs[1] single-query slice (N_q=1): the streaming, HBM-bound regime",
+                   "kernel_ms": stats(), "ms": round(w, 4), "docs_per_s": round(n_docs / (w * 1e-3), 1), "kernel_ms_avg": round(a, 4),
+                   "roofline": roof("hbm", forward_bytes(1, l_q, T, n_docs, 2, True), a, PEAK_HBM_GBS, "GB/s", "c2_nq1")}
         del s1
+        # between the two regimes: the same corpus at 2 .. 32 queries (both fractions of every point: neither roof binds alone)
+        sweep = []
+        for nq in (2, 4, 8, 16, 32):
+            if nq > Q.shape[0]:
+                break
+            Qn = Q[:nq].contiguous()
+            sn = torch.empty(nq, n_docs, dtype=torch.float32, device=dev)
+            w, a, m, mn = time_launches(lambda: M.maxsim_forward_ragged(Qn, Dp, off, total_tokens=T, scores=sn), 20, 3)
+            sweep.append({"n_q": nq, "ms": round(a, 4), "hbm_frac": round(forward_bytes(nq, l_q, T, n_docs, 2, True) / (a * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                          "mfma_frac": round(2.0 * nq * l_q * T * D_MODEL / (a * 1e-3) / 1e12 / PEAK_MFMA_16BIT_TFLOPS, 4)})
+            del Qn, sn
+        leg_nq1["query_count_sweep"] = sweep
+        extra.append(leg_nq1)
     if "c1" in legs:
         # config 1 (the parity case): 1 x 32 query tokens, 1000 x 128 document tokens, fp32 with argmax; 65.7 MB,
         # timed cold (it would sit in the Infinity Cache otherwise); report only

@@ -57,7 +57,7 @@ int num_cu()
     return cached[dev];
 }
 
-// int8 scoring: the kernels built around 128-byte rows, or the plain inner loop over d for other widths
+// int8 scoring: the kernels built around 128-byte rows, or (other widths) the slab kernel / the plain inner loop over d
 static hipError_t i8_launch_any(const int8_t *Q, const float *qs, int n_q, int l_q, const int8_t *D, const float *ds,
                                 const int32_t *offsets, int64_t b, int l_d, int64_t total_tokens, int d, float *scores,
                                 int64_t ld, int cus, hipStream_t stream)

@@ -107,8 +107,9 @@ def test_forward_variants_replay_from_a_graph():
 
 def test_capture_without_a_warm_up_of_the_captured_shapes():
     """maxsim_init does the per-device set-up (LDS limits of every instantiation), so a shape class may meet its
-    first launch under capture: the int8 document-stationary kernel with 24 column blocks and the fp32 slab kernel
-    with argmax are captured here without an eager call of theirs before, and checked against eager calls after."""
+    first launch under capture: the int8 document-stationary kernel with 24 column blocks, the fp32 slab kernel
+    with argmax and the int8 slab kernel (two passes, 157 KB of LDS) are captured here without an eager call of
+    theirs before, and checked against eager calls after."""
     M.maxsim_init()
     big8, bigs = M.maxsim_quantize_rows_i8(W.unit_rows((4100, 36, 128), "f32", 31, DEV))
     q8, qs = M.maxsim_quantize_rows_i8(W.unit_rows((1, 700, 128), "f16", 32, DEV))
@@ -117,10 +118,14 @@ def test_capture_without_a_warm_up_of_the_captured_shapes():
     Dw = W.unit_rows((7, 90, 320), "f32", 34, DEV)
     sw = torch.empty(1, 7, device=DEV)
     aw = torch.empty(1, 7, 40, dtype=torch.int32, device=DEV)
+    q8w, qsw = M.maxsim_quantize_rows_i8(W.unit_rows((1, 600, 256), "f16", 35, DEV))
+    d8w, dsw = M.maxsim_quantize_rows_i8(W.unit_rows((6, 50, 256), "f32", 36, DEV))
+    s8w = torch.empty(1, 6, device=DEV)
 
     def step():
         M.maxsim_forward_i8(q8, qs, big8, bigs, scores=s8)
         M.maxsim_forward(Qw, Dw, scores=sw, argmax=aw)
+        M.maxsim_forward_i8(q8w, qsw, d8w, dsw, scores=s8w)
 
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
@@ -132,14 +137,14 @@ def test_capture_without_a_warm_up_of_the_captured_shapes():
     torch.cuda.synchronize()
     got = []
     for rep in range(2):
-        s8.fill_(0), sw.fill_(0), aw.fill_(-7)
+        s8.fill_(0), sw.fill_(0), aw.fill_(-7), s8w.fill_(0)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        got.append([t.clone() for t in (s8, sw, aw)])
-    s8.fill_(0), sw.fill_(0), aw.fill_(-7)
+        got.append([t.clone() for t in (s8, sw, aw, s8w)])
+    s8.fill_(0), sw.fill_(0), aw.fill_(-7), s8w.fill_(0)
     step()
     torch.cuda.synchronize()
     for rep in range(2):
-        for g_, ref in zip(got[rep], (s8, sw, aw)):
+        for g_, ref in zip(got[rep], (s8, sw, aw, s8w)):
             assert torch.equal(g_, ref), "replay %d differs from the eager result" % rep

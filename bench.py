@@ -581,6 +581,21 @@ def main():
         "mfma_frac_lq1024": by_leg["c3"]["roofline"]["frac"] if "c3" in by_leg else None,
         "hbm_frac_lq32": by_leg["c2_nq1"]["roofline"]["frac"] if "c2_nq1" in by_leg else None,
     }
+    # the same legs against what this box sustained in this run (the register-only MFMA loops and the read probe of
+    # the ceilings leg): the part lowers its clock under matrix load by an amount that differs between boxes and hours
+    ceil = out.get("ceilings")
+    if ceil:
+        def of_probe(leg, key, probe, unit):
+            if leg is None or probe not in ceil:
+                return None
+            return round(leg["roofline"]["achieved"] / ceil[probe][unit], 4)
+        out["fractions_of_this_box_probes"] = {
+            "headline_of_fp16_mfma_probe": round(out["roofline"]["achieved"] / ceil["mfma_f16_unit_norm_operands"]["tera_ops_per_s"], 4)
+            if "mfma_f16_unit_norm_operands" in ceil else None,
+            "c3_of_bf16_mfma_probe": of_probe(by_leg.get("c3"), "c3", "mfma_bf16_unit_norm_operands", "tera_ops_per_s"),
+            "c5_of_i8_mfma_probe": of_probe(by_leg.get("c5"), "c5", "mfma_i8_random_operands", "tera_ops_per_s"),
+            "c2_nq1_of_read_probe": of_probe(by_leg.get("c2_nq1"), "c2_nq1", "hbm_read_stream_non_temporal", "GB_per_s"),
+        }
     # context only (another machine, the authors' Triton kernels): figures the paper prints for an A100-40GB
     # (Tab. "mem", Fig. 1 caption, Sec. 1) and for the ColPali shape on an A100-80GB (Tab. "fwd_abs", inference frontier)
     out["paper_context"] = {

@@ -964,21 +964,29 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
     }
     const bool wave_active = w * NCB < nb;
 
-    WinIter li, ci;
+    // One iterator walks the windows, three ahead of the MFMAs (at load time).  What the stage needs of a window
+    // later -- is there one, does it hold a boundary and where, which documents end in it -- travels in three scalar
+    // words through a ring of three descriptors, instead of a second iterator that would derive it all again.
+    struct WinDesc {
+        int flags; // bit 0: the window exists; 1: it holds a boundary; 2: A ends in it; 3: B ends in it; bits 8..: pa
+        int doc_a, doc_b;
+    };
+    WinIter li;
     win_init<UNI>(li, p, off, doc0, doc1);
-    ci = li;
-    if (!win_valid(ci))
+    if (!win_valid(li))
         return;
 
     static_assert(CPT <= 4, "a thread moves at most four chunks per window");
     uint4 g0, g1, g2, g3, g4, g5, g6, g7; // the window on its way from HBM (see reg_at); four at most are used
     auto g = [&](auto i) -> uint4 & { return reg_at<decltype(i)::value>(g0, g1, g2, g3, g4, g5, g6, g7); };
-    bool g_has = false;
-    auto gload = [&]() {
-        g_has = win_valid(li);
-        if (!g_has)
-            return;
+    auto gload = [&]() -> WinDesc { // the next window of the stream -> registers; returns its descriptor
+        WinDesc d = {0, 0, 0};
+        if (!win_valid(li))
+            return d;
         const Window lw = win_describe<UNI>(li, p, off);
+        d.flags = 1 | (lw.n_b > 0 ? 2 : 0) | (lw.fin_a ? 4 : 0) | (lw.fin_b ? 8 : 0) | (lw.pa << 8);
+        d.doc_a = li.doc;
+        d.doc_b = lw.doc_b;
         if (copies) {
             // window row i holds A's row min(i, n_a - 1) below pa and B's row min(i - pa, n_b - 1) from pa on
             // (without a B that is A's last row again); A and B are neighbours in the packed corpus
@@ -990,19 +998,23 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
             });
         }
         win_advance<UNI>(li, lw, p, off);
+        return d;
     };
-    auto lstore = [&](int buf_off) {
-        if (!g_has || !copies)
+    WinDesc d_cur, d_n1, d_n2; // the windows being computed, read from LDS next, and on their way from HBM
+    auto lstore = [&](int buf_off) { // the window in the registers (d_n2) -> LDS
+        if (!(d_n2.flags & 1) || !copies)
             return;
         static_for<CPT>([&](auto i) { *reinterpret_cast<uint4 *>(&lds_tile[buf_off + cp_loff(i)]) = g(i); });
     };
 
     int o_cur = 0, o_nxt = LT::BYTES, o_wr = 2 * LT::BYTES;
-    gload();
+    d_n2 = gload();
     lstore(o_cur);
-    gload();
+    d_cur = d_n2;
+    d_n2 = gload();
     lstore(o_nxt);
-    gload();
+    d_n1 = d_n2;
+    d_n2 = gload();
     __syncthreads();
     // One operand set: during the LAST chain of a window every operand chunk is replaced, right after the
     // MFMA that used it last, by the next window's (the second set of fwd_tile_kernel would not fit beside
@@ -1013,8 +1025,11 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
         ac[u] = *reinterpret_cast<const uint4 *>(&lds_tile[o_cur + a_off + u * 32]);
 
     // BND: the window holds rows of two documents
-    auto stage = [&](auto bnd_tag, const Window &cw) {
+    auto stage = [&](auto bnd_tag) {
         constexpr bool BND = decltype(bnd_tag)::value;
+        const int cw_pa = d_cur.flags >> 8;
+        const bool cw_fin_a = (d_cur.flags & 4) != 0, cw_fin_b = (d_cur.flags & 8) != 0;
+        WinDesc d_new = {0, 0, 0};
         constexpr int LAG = NU >= 4 ? 2 : NU / 2;
         float mb[NCB];
 #pragma unroll
@@ -1029,7 +1044,7 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
 #pragma unroll
                 for (int q = q0; q < q1; ++q) {
                     const float qm = fmaxf(fmaxf(fmaxf(acc[4 * q], acc[4 * q + 1]), acc[4 * q + 2]), acc[4 * q + 3]);
-                    const bool in_a = 8 * q + 4 * h < cw.pa;
+                    const bool in_a = 8 * q + 4 * h < cw_pa;
                     ma = fmaxf(ma, in_a ? qm : neg_inf());
                     mbv = fmaxf(mbv, in_a ? neg_inf() : qm);
                 }
@@ -1055,7 +1070,7 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
                 if (cb == 0) {
                     if (u == NU - 1) {
                         lstore(o_wr);
-                        gload();
+                        d_new = gload();
                     }
                 } else {
                     fold(acc[cb - 1], u, m[cb - 1], mb[cb - 1]);
@@ -1067,61 +1082,61 @@ __global__ void __launch_bounds__(W * 64, 2) fwd_pack_kernel(FwdParams p, Offset
         for (int u = 0; u < NU; ++u)
             fold(acc[NCB - 1], u, m[NCB - 1], mb[NCB - 1]);
 
-        if (cw.fin_a) {
+        if (cw_fin_a) {
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
                 int lb = w * NCB + cb;
-                float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, ci.doc, 0, rho, h);
+                float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, d_cur.doc_a, 0, rho, h);
                 if (lane == 0 && lb < nb)
-                    p.scores[(int64_t)(gb0 + lb) * p.ld + ci.doc] = sum;
+                    p.scores[(int64_t)(gb0 + lb) * p.ld + d_cur.doc_a] = sum;
                 m[cb] = BND ? mb[cb] : neg_inf();
             }
-            if (BND && cw.fin_b) {
+            if (BND && cw_fin_b) {
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb) {
                     int lb = w * NCB + cb;
-                    float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, cw.doc_b, 0, rho, h);
+                    float sum = finish_block<false>(p, m[cb], 0, col_valid[cb], gb0 + lb, d_cur.doc_b, 0, rho, h);
                     if (lane == 0 && lb < nb)
-                        p.scores[(int64_t)(gb0 + lb) * p.ld + cw.doc_b] = sum;
+                        p.scores[(int64_t)(gb0 + lb) * p.ld + d_cur.doc_b] = sum;
                     m[cb] = neg_inf();
                 }
             }
         }
-        win_advance<UNI>(ci, cw, p, off);
         __syncthreads();
         int t = o_cur;
         o_cur = o_nxt;
         o_nxt = o_wr;
         o_wr = t;
+        d_cur = d_n1;
+        d_n1 = d_n2;
+        d_n2 = d_new;
     };
 
     if (!wave_active) {
         // fewer than 32 queries in this group: the wavefront only helps moving tiles (same barriers as the others)
-        while (win_valid(ci)) {
-            const Window cw = win_describe<UNI>(ci, p, off);
+        while (d_cur.flags & 1) {
             lstore(o_wr);
-            gload();
-            win_advance<UNI>(ci, cw, p, off);
+            const WinDesc d_new = gload();
             __syncthreads();
             int t = o_cur;
             o_cur = o_nxt;
             o_nxt = o_wr;
             o_wr = t;
+            d_cur = d_n1;
+            d_n1 = d_n2;
+            d_n2 = d_new;
         }
     } else {
         // runs of plain windows, each ended by one boundary window
-        Window cw = win_describe<UNI>(ci, p, off);
         for (;;) {
-            while (cw.n_b == 0) {
-                stage(std::false_type{}, cw);
-                if (!win_valid(ci))
+            while (!(d_cur.flags & 2)) {
+                stage(std::false_type{});
+                if (!(d_cur.flags & 1))
                     return;
-                cw = win_describe<UNI>(ci, p, off);
             }
-            stage(std::true_type{}, cw);
-            if (!win_valid(ci))
+            stage(std::true_type{});
+            if (!(d_cur.flags & 1))
                 return;
-            cw = win_describe<UNI>(ci, p, off);
         }
     }
 }

@@ -236,3 +236,24 @@ def test_uniform_packed_windows(b, l_d, n_q, l_q, dtype, d):
     Q = W.unit_rows((n_q, l_q, d), dtype, 111, DEV)
     D = W.unit_rows((b, l_d, d), dtype, 112, DEV)
     forward_parity_uniform(Q, D, M.maxsim_forward, False, RTOL_16)
+
+
+# Five to sixteen column blocks on a corpus of thousands of documents: the workgroups of two and four wavefronts with
+# four blocks each (tile kernel: argmax or queries of several blocks; packed windows otherwise), uniform and ragged.
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("n_q,l_q,want_argmax", [(1, 200, False), (1, 256, True), (3, 130, True), (2, 250, False), (7, 32, True),
+                                                 (12, 32, True), (6, 32, False), (14, 20, False)])
+@pytest.mark.parametrize("ragged", [False, True])
+def test_mid_block_counts_on_many_documents(ragged, n_q, l_q, want_argmax, dtype, d):
+    b = 4500
+    rtol = RTOL_F32 if dtype == "f32" else RTOL_16
+    Q = W.unit_rows((n_q, l_q, d), dtype, 131, DEV)
+    if ragged:
+        lens = np.random.default_rng(n_q * 1000 + l_q).integers(0, 50, size=b)
+        lens[:3] = [0, 33, 1]
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(DEV)
+        Dp = W.unit_rows((int(lens.sum()), d), dtype, 132, DEV)
+        forward_parity_ragged(Q, Dp, off, M.maxsim_forward_ragged, want_argmax, rtol)
+    else:
+        D = W.unit_rows((b, 32 if l_q > 100 else 40, d), dtype, 132, DEV)
+        forward_parity_uniform(Q, D, M.maxsim_forward, want_argmax, rtol)

@@ -316,9 +316,30 @@ def main():
             M.maxsim_backward_ragged(Qt, Dt, offt, at, gt, total_tokens=Tt, dQ=dQt, dD=dDt)
         w, _, _, _ = time_launches(step_rt, 50, 5, cold=True)
         wb, ab, _, _ = time_launches(lambda: M.maxsim_backward_ragged(Qt, Dt, offt, at, gt, total_tokens=Tt, dQ=dQt, dD=dDt), 50, 5, cold=True)
+        # the same step replayed from a HIP graph (its five kernels are short enough for launch gaps to count): captured
+        # on a side stream after an eager call, timed back to back
+        graph_ms = None
+        try:
+            M.maxsim_init()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                step_rt()
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    step_rt()
+            torch.cuda.synchronize()
+            wg, _, _, _ = time_launches(graph.replay, 50, 5)
+            we, _, _, _ = time_launches(step_rt, 50, 5)
+            graph_ms = {"graph_replay_ms": round(wg, 4), "eager_back_to_back_ms": round(we, 4)}
+            del graph
+        except Exception as e:  # a capture problem must not cost the bench line
+            graph_ms = {"error": repr(e)[:200]}
         extra.append({"leg": "c2_train", "workload": "ragged training step: 256 queries (L_q=32) x 256 ragged documents (%d tokens), fp16, "
                                                      "forward+argmax, CE, maxsim_backward_ragged" % Tt,
-                      "step_ms": round(w, 4), "backward_ms": round(wb, 4), "pairs_per_s": round(nt * nt / (w * 1e-3), 1)})
+                      "step_ms": round(w, 4), "backward_ms": round(wb, 4), "pairs_per_s": round(nt * nt / (w * 1e-3), 1),
+                      "hip_graph": graph_ms})
         del Qt, Dt, st, at, gt, dQt, dDt
     del Dp, Q
 

@@ -88,3 +88,13 @@ def test_missing_library_fails_loudly(monkeypatch):
     import pytest
     with pytest.raises(binding.MaxSimError):
         binding.load()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build measures one GPU: `bench.py --gpus N` with N above 1 exits with a message and prints no JSON line."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
